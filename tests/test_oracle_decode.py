@@ -1,0 +1,286 @@
+"""Pins for the oracle's decode algorithm (method section, Eq. 1, shared KV addressing).
+
+What fixes the expected values here: a dense block composed of torch library ops; the
+plain no-cache definition (oracle/plain_definition.py); the invariants the method fixes
+(never-exit = dense, exit at L = dense, lossless river = dense for any schedule, every
+cache slot written exactly once, exit position range, monotonicity in tau)."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from helpers import grid_model
+from oracle import plain_definition as pd
+from oracle import river_oracle as ro
+from paper_2604_18396_amd import configs, inputs
+
+TINY_BF16 = configs.TINY.with_(name="tiny-bf16", dtype=configs.DTYPE_BF16)
+
+
+def torch_dense_block(cfg, blk, h, K_prev, V_prev, pos):
+    """One pre-norm Llama block at position `pos` from torch library ops, fp64.
+    K_prev/V_prev: [pos, nkv, hd] stored entries of earlier positions."""
+    d, nq, nkv, hd = cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    W = {k: v.double() for k, v in blk.items()}
+    eps = float(np.float32(cfg.rms_eps))          # the configuration field is single precision
+    x = F.rms_norm(h, (d,), W["attn_norm"], eps=eps)
+    q = F.linear(x, W["wq"]).reshape(nq, hd)
+    k = F.linear(x, W["wk"]).reshape(nkv, hd)
+    v = F.linear(x, W["wv"]).reshape(nkv, hd)
+    theta = cfg.rope_base ** (-2.0 * torch.arange(hd // 2, dtype=torch.float64) / hd)
+    rot = torch.polar(torch.ones_like(theta), pos * theta)
+
+    def rope(t):
+        z = torch.complex(t[:, :hd // 2], t[:, hd // 2:]) * rot
+        return torch.cat([z.real, z.imag], dim=1)
+
+    q, k = rope(q), rope(k)
+    st = torch.bfloat16 if cfg.dtype == 1 else torch.float32
+    k, v = k.to(st).double(), v.to(st).double()
+    K = torch.cat([K_prev, k[None]], dim=0)
+    V = torch.cat([V_prev, v[None]], dim=0)
+    o = F.scaled_dot_product_attention(q[None, :, None, :], K.permute(1, 0, 2)[None],
+                                       V.permute(1, 0, 2)[None], enable_gqa=True)[0, :, 0]
+    h1 = h + F.linear(o.reshape(-1), W["wo"])
+    y = F.rms_norm(h1, (d,), W["ffn_norm"], eps=eps)
+    h2 = h1 + F.linear(F.silu(F.linear(y, W["w_gate"])) * F.linear(y, W["w_up"]), W["w_down"])
+    return h2, k, v
+
+
+@pytest.mark.parametrize("cfg", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
+def test_dense_model_matches_library_composition(cfg):
+    w = inputs.make_weights(cfg, 5)
+    # non-trivial norm gains so that a gain applied in the wrong place would show
+    g = torch.Generator().manual_seed(9)
+    for blk in w["layers"]:
+        blk["attn_norm"] = (1 + 0.1 * torch.randn(cfg.d_model, generator=g)).to(blk["wq"].dtype)
+        blk["ffn_norm"] = (1 + 0.1 * torch.randn(cfg.d_model, generator=g)).to(blk["wq"].dtype)
+    w["final_norm"] = (1 + 0.1 * torch.randn(cfg.d_model, generator=g)).to(w["lm_head"].dtype)
+    o = ro.Oracle(cfg, w, None)
+    toks = inputs.make_prompt(cfg.vocab, 7, 3)
+    o.prefill(toks[:-1])
+    nxt, e, sims = o.decode_step(int(toks[-1]), cfg.n_layers)
+    hid = o.hidden()
+    kvd = cfg.n_kv_heads * cfg.head_dim
+    Ks = [torch.zeros(0, cfg.n_kv_heads, cfg.head_dim, dtype=torch.float64) for _ in range(cfg.n_layers)]
+    Vs = [k.clone() for k in Ks]
+    for p, t in enumerate(toks):
+        h = w["tok_emb"][int(t)].double()
+        for l, blk in enumerate(w["layers"]):
+            h_in = h
+            h, k, v = torch_dense_block(cfg, blk, h, Ks[l], Vs[l], p)
+            Ks[l] = torch.cat([Ks[l], k[None]])
+            Vs[l] = torch.cat([Vs[l], v[None]])
+            if p == len(toks) - 1:
+                np.testing.assert_allclose(hid[l + 1], h.numpy(), rtol=1e-9, atol=1e-12)
+                ref_s = F.cosine_similarity(h_in[None], h[None]).item()
+                assert sims[l] == pytest.approx(ref_s, rel=1e-10)
+    logits = F.linear(F.rms_norm(h, (cfg.d_model,), w["final_norm"].double(),
+                                 eps=float(np.float32(cfg.rms_eps))),
+                      w["lm_head"].double())
+    np.testing.assert_allclose(o.logits(), logits.numpy(), rtol=1e-9, atol=1e-12)
+    assert nxt == int(logits.argmax()) and e == cfg.n_layers
+    # the cache holds exactly what the library composition stored
+    for l in range(cfg.n_layers):
+        np.testing.assert_allclose(o.kcache()[l, :len(toks)], Ks[l].reshape(len(toks), kvd).numpy(),
+                                   rtol=0, atol=1e-9 if cfg.dtype == 0 else 0)
+
+
+def _free_run(o, prompt, steps, forced=None):
+    tok = o.prefill(prompt)
+    toks, es, sims, hids, logits = [tok], [], [], [], []
+    for i in range(steps):
+        tok, e, s = o.decode_step(toks[-1], None if forced is None else int(forced[i]))
+        toks.append(tok); es.append(e); sims.append(s)
+        hids.append(o.hidden()); logits.append(o.logits())
+    return toks, es, np.array(sims), hids, logits
+
+
+@pytest.mark.parametrize("tau", [0.9, 0.68, 0.675, 0.6, 0.52, 0.3])
+def test_threshold_mode_equals_plain_definition(tiny_setup, tau):
+    cfg, w, river = tiny_setup
+    cfg = cfg.with_(tau=tau)
+    prompt = inputs.make_prompt(cfg.vocab, 16, configs.C1.seed_prompt)
+    o = ro.Oracle(cfg, w, river)
+    toks, es, sims, hids, logits = _free_run(o, prompt, 32)
+    L = cfg.n_layers
+    ref = pd.run(cfg, w, river, list(prompt) + toks[:-1], exits=[L] * 16 + [None] * 32)
+    assert list(ref["tokens"][15:]) == toks
+    assert list(ref["exits"][16:]) == es
+    for i in range(32):
+        np.testing.assert_allclose(hids[i], ref["hidden"][16 + i], rtol=1e-8, atol=1e-11)
+        np.testing.assert_allclose(logits[i], ref["logits"][16 + i], rtol=1e-8, atol=1e-11)
+        k = es[i]
+        np.testing.assert_allclose(sims[i][:k], ref["sims"][16 + i][:k], rtol=1e-9)
+        assert np.all(np.isnan(sims[i][k:]))
+    if tau == 0.9:
+        assert set(es) == {L}            # the stated C1 threshold never fires on random weights
+    if tau in (0.68, 0.675, 0.52):
+        assert len(set(es)) > 1          # both branches exercised
+    if tau == 0.3:
+        assert set(es) == {cfg.min_exit_layer}
+
+
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
+def test_forced_mixed_schedule_equals_plain_definition(cfg0):
+    cfg = cfg0.with_(min_exit_layer=0)
+    w = inputs.make_weights(cfg, 21)
+    river = ro.quantize_river(cfg, w)
+    prompt = inputs.make_prompt(cfg.vocab, 5, 22)
+    sched = [0, 4, 1, 2, 3, 3, 0, 2, 4, 1, 1, 4]
+    o = ro.Oracle(cfg, w, river)
+    toks, es, sims, hids, logits = _free_run(o, prompt, len(sched), sched)
+    assert es == sched
+    ref = pd.run(cfg, w, river, list(prompt) + toks[:-1], exits=[cfg.n_layers] * 5 + sched)
+    assert list(ref["tokens"][4:]) == toks
+    for i in range(len(sched)):
+        np.testing.assert_allclose(hids[i], ref["hidden"][5 + i], rtol=1e-8, atol=1e-11)
+        np.testing.assert_allclose(logits[i], ref["logits"][5 + i], rtol=1e-8, atol=1e-11)
+    # the river really differs from the backbone here (quantisation error is visible)
+    dense = ro.Oracle(cfg, w, None)
+    dense.prefill(prompt)
+    dense.decode_step(toks[0], cfg.n_layers)
+    assert np.abs(dense.hidden()[-1] - hids[0][-1]).max() > 1e-4
+
+
+def test_never_exit_and_exit_at_L_equal_dense(tiny_setup):
+    cfg, w, river = tiny_setup
+    prompt = inputs.make_prompt(cfg.vocab, 16, configs.C1.seed_prompt)
+    dense = _free_run(ro.Oracle(cfg, w, None), prompt, 12, [cfg.n_layers] * 12)
+    never = _free_run(ro.Oracle(cfg.with_(tau=1.0), w, river), prompt, 12)
+    at_L = _free_run(ro.Oracle(cfg.with_(tau=-2.0), w, river), prompt, 12, [cfg.n_layers] * 12)
+    for run in (never, at_L):
+        assert run[0] == dense[0] and run[1] == [cfg.n_layers] * 12
+        for a, b in zip(run[4], dense[4]):
+            np.testing.assert_array_equal(a, b)      # the river adds nothing: bit-identical
+
+
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
+def test_lossless_river_any_schedule_equals_dense(cfg0):
+    """If every block matrix lies on its 4-bit grid the twin equals the backbone, so any exit
+    schedule must reproduce the dense run: pins the traversal and the shared cache slots
+    independently of quantisation error."""
+    cfg = cfg0.with_(min_exit_layer=1)
+    w = grid_model(cfg, 31)
+    river = ro.quantize_river(cfg, w)
+    prompt = inputs.make_prompt(cfg.vocab, 6, 32)
+    sched = [1, 3, 2, 4, 1, 2, 3, 1]
+    dense = _free_run(ro.Oracle(cfg, w, None), prompt, len(sched), [cfg.n_layers] * len(sched))
+    mixed = _free_run(ro.Oracle(cfg, w, river), prompt, len(sched), sched)
+    assert mixed[0] == dense[0] and mixed[1] == sched
+    for a, b in zip(mixed[3], dense[3]):
+        np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+    # and the grid weights are not degenerate: hidden states do move
+    assert np.abs(dense[3][0][-1] - dense[3][0][0]).max() > 1e-3
+
+
+def test_kv_slots_written_exactly_once(tiny_setup):
+    cfg, w, river = tiny_setup
+    cfg = cfg.with_(tau=0.52)
+    o = ro.Oracle(cfg, w, river)
+    prompt = inputs.make_prompt(cfg.vocab, 16, configs.C1.seed_prompt)
+    toks, es, *_ = _free_run(o, prompt, 20)
+    wr = o.written()
+    assert np.all(wr[:, :36] == 1) and np.all(wr[:, 36:] == 0)
+    assert o.pos == 36
+    # every slot of a skipped layer holds finite, non-zero river output
+    assert np.all(np.abs(o.kcache()[:, :36]).sum(axis=2) > 0)
+    # rewind + replay rewrites only the replayed slot and reproduces the step
+    h_before, l_before = o.hidden(), o.logits()
+    o.rewind(35)
+    assert o.written()[:, 35].sum() == 0
+    tok, e, _ = o.decode_step(toks[-2])
+    assert (tok, e) == (toks[-1], es[-1])
+    np.testing.assert_array_equal(o.hidden(), h_before)
+    np.testing.assert_array_equal(o.logits(), l_before)
+    assert np.all(o.written()[:, :36] == 1)
+
+
+def test_exit_rule_range_and_monotone_in_tau(tiny_setup):
+    cfg, w, river = tiny_setup
+    prompt = inputs.make_prompt(cfg.vocab, 16, configs.C1.seed_prompt)
+    L, Ls = cfg.n_layers, cfg.min_exit_layer
+    base = ro.Oracle(cfg.with_(tau=1.0), w, river)
+    tok = base.prefill(prompt)
+    prev = None
+    for tau in [-2.0, 0.3, 0.5, 0.52, 0.55, 0.6, 0.7, 0.8, 1.0, 1.5]:
+        o = ro.Oracle(cfg.with_(tau=tau), w, river)
+        o.prefill(prompt)
+        _, e, sims = o.decode_step(tok)           # same teacher-forced state for every tau
+        assert Ls <= e <= L
+        assert np.all((sims[:e] >= -1) & (sims[:e] <= 1)) and np.all(np.isnan(sims[e:]))
+        if tau < -1:
+            assert e == Ls
+        if tau >= 1:
+            assert e == L
+        if e < L:                                 # first hit: blocks before e did not pass
+            assert sims[e - 1] > tau and np.all(sims[Ls - 1:e - 1] <= tau)
+        else:
+            assert np.all(sims[Ls - 1:L - 1] <= tau)
+        if prev is not None:
+            assert e >= prev
+        prev = e
+
+
+def test_error_paths(tiny_setup):
+    cfg, w, river = tiny_setup
+    o = ro.Oracle(cfg, w, river)
+    with pytest.raises(ValueError):
+        o.prefill([cfg.vocab])                    # token out of range
+    o.prefill([1, 2, 3])
+    with pytest.raises(ValueError):
+        o.decode_step(1, 1)                       # below L_s = 2
+    with pytest.raises(ValueError):
+        o.decode_step(1, cfg.n_layers + 1)
+    with pytest.raises(ValueError):
+        o.rewind(99)
+    small = ro.Oracle(cfg.with_(max_seq=4), w, river)
+    small.prefill([1, 2, 3, 4])
+    with pytest.raises(ValueError):
+        small.decode_step(1)                      # cache full
+    no_river = ro.Oracle(cfg.with_(tau=-2.0), w, None)
+    no_river.prefill([1])
+    with pytest.raises(ValueError):
+        no_river.decode_step(1)                   # exits at L_s but has no twin to continue in
+
+
+def test_argmax_ties_go_to_lowest_index(tiny_setup):
+    cfg, w, _ = tiny_setup
+    w2 = dict(w)
+    head = w["lm_head"].clone()
+    head[:] = head[7]                              # every logit equal
+    w2["lm_head"] = head
+    o = ro.Oracle(cfg, w2, None)
+    assert o.prefill([3, 4, 5]) == 0
+    head = w["lm_head"].clone()
+    o_ref = ro.Oracle(cfg, w, None)
+    best = o_ref.prefill([3, 4, 5])
+    lo, hi = (best - 1, best) if best > 0 else (best, best + 1)
+    head[lo] = head[best]
+    head[hi] = head[best]                          # the maximum now appears twice
+    w2["lm_head"] = head
+    assert ro.Oracle(cfg, w2, None).prefill([3, 4, 5]) == lo
+
+
+def test_similarity_equal_to_tau_does_not_exit(tiny_setup):
+    """Eq. 1 is a strict inequality.  A block whose output projections are zero is the
+    identity, so s = 1 exactly when |h|^2 is a perfect square; tau = 1 must not fire."""
+    cfg, w, river = tiny_setup
+    w2 = {k: v for k, v in w.items()}
+    w2["layers"] = []
+    for blk in w["layers"]:
+        b = dict(blk)
+        b["wo"] = torch.zeros_like(blk["wo"])
+        b["w_down"] = torch.zeros_like(blk["w_down"])
+        w2["layers"].append(b)
+    emb = torch.zeros_like(w["tok_emb"])
+    emb[:, 0] = 2.0
+    w2["tok_emb"] = emb
+    river2 = ro.quantize_river(cfg, w2)
+    o = ro.Oracle(cfg.with_(tau=1.0), w2, river2)
+    o.prefill([1, 2])
+    _, e, sims = o.decode_step(3)
+    assert np.all(sims == 1.0) and e == cfg.n_layers
+    o2 = ro.Oracle(cfg.with_(tau=float(np.nextafter(np.float32(1.0), np.float32(0.0)))), w2, river2)
+    o2.prefill([1, 2])
+    assert o2.decode_step(3)[1] == cfg.min_exit_layer
