@@ -1,0 +1,269 @@
+"""Thin ctypes binding of libriver.so (include/river.h).
+
+Argument marshalling only: every step of the decode path runs in the library's HIP
+kernels.  torch is used for device memory and the stream.  If the library has not
+been built, loading raises: there is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+from . import build as _build
+from .configs import MATRICES, ModelConfig
+
+RIVER_OK, RIVER_EINVAL, RIVER_ENOSPC, RIVER_ESTATE, RIVER_EHIP = 0, -1, -2, -3, -4
+EXEC_KERNELS, EXEC_PERSISTENT = 0, 1
+DBG_HIDDEN, DBG_LOGITS, DBG_KCACHE, DBG_VCACHE = 0, 1, 2, 3
+
+EXPORTS = ("river_quantize_w4", "river_workspace_bytes", "river_create", "river_prefill",
+           "river_decode_step", "river_read_records", "river_rewind", "river_position",
+           "river_get_debug", "river_fill_cache", "river_last_error", "river_destroy")
+
+
+class RiverError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"river error {code}: {msg}")
+        self.code = code
+
+
+class river_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
+               [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
+                ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("min_exit_layer", C.c_int32),
+                ("tau", C.c_float), ("river_bits", C.c_int32), ("river_group", C.c_int32),
+                ("exec_mode", C.c_int32), ("spin_limit", C.c_int32)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class river_weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)] + \
+               [(n, _PP) for n in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up",
+                                   "w_down")]
+
+
+class river_qweights(C.Structure):
+    _fields_ = [("codes", _PP * 7), ("scale", _PP * 7), ("zero", _PP * 7)]
+
+
+_lib = None
+
+
+def load():
+    """Load libriver.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        raise ImportError(f"{_build.LIB} is missing: build it first "
+                          "(python -c 'import __graft_entry__ as g; g.build()')")
+    L = C.CDLL(_build.LIB)
+    L.river_quantize_w4.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.river_workspace_bytes.argtypes = [C.POINTER(river_config)]
+    L.river_workspace_bytes.restype = C.c_size_t
+    L.river_create.argtypes = [C.POINTER(river_config), C.POINTER(river_weights),
+                               C.POINTER(river_qweights), C.c_void_p, C.c_size_t, C.c_void_p,
+                               C.POINTER(C.c_void_p)]
+    L.river_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    L.river_decode_step.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
+    L.river_read_records.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.river_rewind.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    L.river_position.argtypes = [C.c_void_p]
+    L.river_get_debug.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t]
+    L.river_fill_cache.argtypes = [C.c_void_p, C.c_int32]
+    L.river_last_error.argtypes = [C.c_void_p]
+    L.river_last_error.restype = C.c_char_p
+    L.river_destroy.argtypes = [C.c_void_p]
+    _lib = L
+    return L
+
+
+def make_config(cfg: ModelConfig, exec_mode: int = EXEC_PERSISTENT, spin_limit: int = 0) -> river_config:
+    return river_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                        cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps, cfg.dtype, 1, cfg.max_seq,
+                        cfg.min_exit_layer, cfg.tau, 4, cfg.river_group, exec_mode, spin_limit)
+
+
+def _stream_ptr() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def river_quantize_w4(w: torch.Tensor, group: int):
+    """Device tensor [rows, cols] (fp32 / bf16) -> (codes u8 [rows, cols/2], scale, zero)."""
+    assert w.is_cuda and w.is_contiguous() and w.dim() == 2
+    rows, cols = w.shape
+    gpr = -(-cols // group)
+    codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=w.device)
+    scale = torch.empty((rows, gpr), dtype=w.dtype, device=w.device)
+    zero = torch.empty((rows, gpr), dtype=w.dtype, device=w.device)
+    dt = 1 if w.dtype == torch.bfloat16 else 0
+    rc = load().river_quantize_w4(w.data_ptr(), rows, cols, group, dt, codes.data_ptr(),
+                                  scale.data_ptr(), zero.data_ptr(), _stream_ptr())
+    if rc:
+        raise RiverError(rc, "river_quantize_w4")
+    return codes, scale, zero
+
+
+def upload_weights(weights: dict, device="cuda:0") -> dict:
+    """CPU weight dict (inputs.make_weights) -> same structure on the device."""
+    out = {k: weights[k].to(device) for k in ("tok_emb", "final_norm", "lm_head")}
+    out["layers"] = [{k: v.to(device) for k, v in blk.items()} for blk in weights["layers"]]
+    return out
+
+
+def quantize_river(cfg: ModelConfig, dev_weights: dict) -> list:
+    """River construction on the device for every block (list of {name: (codes, scale, zero)})."""
+    return [{m: river_quantize_w4(blk[m], cfg.river_group) for m in MATRICES}
+            for blk in dev_weights["layers"]]
+
+
+class River:
+    """One decode context (river_create .. river_destroy)."""
+
+    def __init__(self, cfg: ModelConfig, dev_weights: dict, dev_river: list | None,
+                 exec_mode: int = EXEC_PERSISTENT, spin_limit: int = 0):
+        L = load()
+        self.cfg = cfg
+        self._c = make_config(cfg, exec_mode, spin_limit)
+        self._keep = [dev_weights, dev_river]
+        n = cfg.n_layers
+        w = river_weights()
+        w.tok_emb = dev_weights["tok_emb"].data_ptr()
+        w.final_norm = dev_weights["final_norm"].data_ptr()
+        w.lm_head = dev_weights["lm_head"].data_ptr()
+        for name in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"):
+            arr = (C.c_void_p * n)(*[blk[name].data_ptr() for blk in dev_weights["layers"]])
+            self._keep.append(arr)
+            setattr(w, name, C.cast(arr, _PP))
+        q = None
+        if dev_river is not None:
+            q = river_qweights()
+            for j, m in enumerate(MATRICES):
+                for k, field in enumerate(("codes", "scale", "zero")):
+                    arr = (C.c_void_p * n)(*[(r[m][k].data_ptr() if r is not None else None)
+                                             for r in dev_river])
+                    self._keep.append(arr)
+                    getattr(q, field)[j] = C.cast(arr, _PP)
+        nbytes = L.river_workspace_bytes(C.byref(self._c))
+        if nbytes == 0:
+            raise RiverError(RIVER_EINVAL, "invalid configuration")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev_weights["tok_emb"].device)
+        h = C.c_void_p()
+        rc = L.river_create(C.byref(self._c), C.byref(w), C.byref(q) if q is not None else None,
+                            self.workspace.data_ptr(), nbytes, _stream_ptr(), C.byref(h))
+        if rc:
+            raise RiverError(rc, L.river_last_error(None).decode())
+        self._h = h
+
+    def _check(self, rc: int):
+        if rc:
+            raise RiverError(rc, load().river_last_error(self._h).decode())
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load().river_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def prefill(self, tokens) -> int:
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        out = C.c_int32()
+        self._check(load().river_prefill(self._h, 0, t.ctypes.data, len(t), C.byref(out)))
+        return out.value
+
+    def decode_step(self, token: int | None = None, forced_exit: int | None = None, sync: bool = True):
+        """sync=True -> (next_token, exit_position, sims[L]); sync=False queues the step only."""
+        tin = C.byref(C.c_int32(int(token))) if token is not None else None
+        fe = C.byref(C.c_int32(int(forced_exit))) if forced_exit is not None else None
+        if not sync:
+            self._check(load().river_decode_step(self._h, tin, fe, None, None, None))
+            return None
+        tok, e = C.c_int32(), C.c_int32()
+        sims = np.empty(self.cfg.n_layers, dtype=np.float32)
+        self._check(load().river_decode_step(self._h, tin, fe, C.byref(tok), C.byref(e),
+                                             sims.ctypes.data))
+        return tok.value, e.value, sims
+
+    def read_records(self, n: int):
+        toks = np.empty(n, dtype=np.int32)
+        es = np.empty(n, dtype=np.int32)
+        sims = np.empty((n, self.cfg.n_layers), dtype=np.float32)
+        self._check(load().river_read_records(self._h, n, toks.ctypes.data, es.ctypes.data,
+                                              sims.ctypes.data))
+        return toks, es, sims
+
+    def rewind(self, new_len: int):
+        self._check(load().river_rewind(self._h, 0, new_len))
+
+    @property
+    def pos(self) -> int:
+        return load().river_position(self._h)
+
+    def hidden(self) -> np.ndarray:
+        out = np.empty((self.cfg.n_layers + 1, self.cfg.d_model), dtype=np.float32)
+        self._check(load().river_get_debug(self._h, DBG_HIDDEN, out.ctypes.data, out.nbytes))
+        return out
+
+    def logits(self) -> np.ndarray:
+        out = np.empty(self.cfg.vocab, dtype=np.float32)
+        self._check(load().river_get_debug(self._h, DBG_LOGITS, out.ctypes.data, out.nbytes))
+        return out
+
+    def _cache(self, what) -> np.ndarray:
+        c = self.cfg
+        kvd = c.n_kv_heads * c.head_dim
+        if c.dtype == 1:
+            raw = np.empty((c.n_layers, c.max_seq, kvd), dtype=np.uint16)
+            self._check(load().river_get_debug(self._h, what, raw.ctypes.data, raw.nbytes))
+            return (raw.astype(np.uint32) << 16).view(np.float32)      # bf16 words -> fp32 values
+        raw = np.empty((c.n_layers, c.max_seq, kvd), dtype=np.float32)
+        self._check(load().river_get_debug(self._h, what, raw.ctypes.data, raw.nbytes))
+        return raw
+
+    def kcache(self) -> np.ndarray:
+        return self._cache(DBG_KCACHE)
+
+    def vcache(self) -> np.ndarray:
+        return self._cache(DBG_VCACHE)
+
+    def fill_cache(self, byte: int):
+        self._check(load().river_fill_cache(self._h, byte))
+
+
+# The C entry points under their own names (the class above is the same calls with
+# the context kept in an object).
+def river_create(cfg, dev_weights, dev_river, exec_mode=EXEC_PERSISTENT, spin_limit=0) -> River:
+    return River(cfg, dev_weights, dev_river, exec_mode, spin_limit)
+
+
+def river_prefill(ctx: River, tokens) -> int:
+    return ctx.prefill(tokens)
+
+
+def river_decode_step(ctx: River, token=None, forced_exit=None, sync=True):
+    return ctx.decode_step(token, forced_exit, sync)
+
+
+def river_read_records(ctx: River, n: int):
+    return ctx.read_records(n)
+
+
+def river_rewind(ctx: River, new_len: int):
+    ctx.rewind(new_len)
+
+
+def river_destroy(ctx: River):
+    ctx.close()

@@ -1,0 +1,603 @@
+// Host side of the C ABI declared in include/river.h: workspace layout, launches,
+// bookkeeping.  All arithmetic of the decode step lives in river_device.h.
+#include "river.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstddef>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "river_device.h"
+
+using namespace river;
+
+// ------------------------------------------------------------------ kernels
+
+template <int DT>
+__global__ void k_embed(Dev D, StepArgs A) { phase_embed<DT>(D, A); }
+template <int DT>
+__global__ void k_qkv(Dev D, StepArgs A, int l) {
+  extern __shared__ float lds[];
+  phase_qkv<DT>(D, A, l, lds);
+}
+template <int DT>
+__global__ void k_attn(Dev D, StepArgs A, int l) {
+  extern __shared__ float lds[];
+  phase_attn<DT>(D, A, l, lds);
+}
+template <int DT>
+__global__ void k_oproj(Dev D, StepArgs A, int l) {
+  extern __shared__ float lds[];
+  phase_oproj<DT>(D, A, l, lds);
+}
+template <int DT>
+__global__ void k_gateup(Dev D, StepArgs A, int l) {
+  extern __shared__ float lds[];
+  phase_gateup<DT>(D, A, l, lds);
+}
+template <int DT>
+__global__ void k_down(Dev D, StepArgs A, int l) {
+  extern __shared__ float lds[];
+  phase_down<DT>(D, A, l, lds);
+}
+template <int DT>
+__global__ void k_head(Dev D, StepArgs A) {
+  extern __shared__ float lds[];
+  phase_head<DT>(D, A, lds);
+}
+
+// One launch per token: all phases in order, device-wide barriers in between.  The
+// number of barriers (1 + 5 L) is the same for every workgroup whatever the exit state.
+template <int DT>
+__global__ void k_step_persistent(Dev D, StepArgs A) {
+  extern __shared__ float lds[];
+  unsigned long long target = A.bar_base;
+  const unsigned long long n = gridDim.x;
+  phase_embed<DT>(D, A);
+  grid_barrier(D.st, target += n, D.spin_limit);
+  for (int l = 0; l < D.L; ++l) {
+    phase_qkv<DT>(D, A, l, lds);
+    grid_barrier(D.st, target += n, D.spin_limit);
+    phase_attn<DT>(D, A, l, lds);
+    grid_barrier(D.st, target += n, D.spin_limit);
+    phase_oproj<DT>(D, A, l, lds);
+    grid_barrier(D.st, target += n, D.spin_limit);
+    phase_gateup<DT>(D, A, l, lds);
+    grid_barrier(D.st, target += n, D.spin_limit);
+    phase_down<DT>(D, A, l, lds);
+    grid_barrier(D.st, target += n, D.spin_limit);
+  }
+  if (A.want_head) phase_head<DT>(D, A, lds);
+}
+
+// River construction: one thread per quantisation group.
+template <int DT>
+__global__ void k_quantize_w4(const void *w, long long rows, int cols, int group, uint8_t *codes,
+                              void *scale, void *zero) {
+  const int gpr = (cols + group - 1) / group;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows * gpr) return;
+  const long long r = idx / gpr;
+  const int g = (int)(idx % gpr);
+  const int c0 = g * group;
+  const int glen = min(group, cols - c0);
+  const size_t base = (size_t)r * cols + c0;
+  float mn = Store<DT>::ld(w, base), mx = mn;
+  for (int i = 1; i < glen; ++i) {
+    const float v = Store<DT>::ld(w, base + i);
+    mn = fminf(mn, v);
+    mx = fmaxf(mx, v);
+  }
+  float s = (mx > mn) ? (mx - mn) / 15.0f : 1.0f;
+  Store<DT>::st(scale, idx, s);
+  s = Store<DT>::ld(scale, idx);              // the stored (rounded) value defines the grid
+  float z = -mn / s;
+  Store<DT>::st(zero, idx, z);
+  z = Store<DT>::ld(zero, idx);
+  for (int i = 0; i < glen; i += 2) {
+    int q[2];
+    for (int k = 0; k < 2; ++k) {
+      const float t = rintf(Store<DT>::ld(w, base + i + k) / s + z);
+      q[k] = t < 0.f ? 0 : (t > 15.f ? 15 : (int)t);
+    }
+    codes[(base + i) >> 1] = (uint8_t)(q[0] | (q[1] << 4));
+  }
+}
+
+__global__ void k_fill_bytes(uint4 *p, size_t n16, uint32_t word) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_uint4(word, word, word, word);
+}
+
+// ------------------------------------------------------------------ context
+
+struct Layout {
+  size_t kcache, vcache, rope, hidden, qbuf, obuf, h1, abuf, logits, part_o, part_ml, cos_part,
+      amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, total;
+  size_t cache_bytes;
+};
+
+struct river_ctx {
+  river_config cfg;
+  Dev dev;
+  Layout lay;
+  char *ws;
+  hipStream_t stream;
+  int pos;              // positions in the cache
+  bool have_token;      // DevState::cur_token is valid
+  bool have_river;
+  long long steps;      // decode steps recorded so far
+  unsigned long long bar_total;
+  int grid_persist, grid_gemv, block;
+  size_t lds_bytes;
+  bool broken;
+  std::string err;
+};
+
+static thread_local std::string g_create_err;
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static bool valid_cfg(const river_config *c, std::string *why) {
+  auto bad = [&](const char *m) { if (why) *why = m; return false; };
+  if (!c) return bad("null config");
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 1 ||
+      c->vocab < 1 || c->max_seq < 1)
+    return bad("non-positive dimension");
+  if (c->dtype != RIVER_F32 && c->dtype != RIVER_BF16) return bad("dtype must be RIVER_F32 or RIVER_BF16");
+  if (c->max_batch != 1) return bad("max_batch must be 1");
+  if (c->river_bits != 4) return bad("river_bits must be 4");
+  if (c->river_group < 32 || c->river_group % 32) return bad("river_group must be a multiple of 32");
+  if (c->n_q_heads % c->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return bad("query heads per kv head must be 1, 2, 4 or 8");
+  if (c->n_kv_heads > kMaxKvHeads) return bad("too many kv heads");
+  const int hd = c->head_dim;
+  if (hd < 32 || hd > 256 || (hd & (hd - 1))) return bad("head_dim must be a power of two in [32, 256]");
+  if (c->d_model % 16 || c->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
+  if (c->min_exit_layer < 0 || c->min_exit_layer > c->n_layers) return bad("min_exit_layer out of range");
+  if (c->exec_mode != RIVER_EXEC_KERNELS && c->exec_mode != RIVER_EXEC_PERSISTENT) return bad("bad exec_mode");
+  if (c->spin_limit < 0) return bad("negative spin_limit");
+  if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return bad("bad rope_base / rms_eps");
+  return true;
+}
+
+static constexpr int kBlock = 256;
+
+static int x_capacity(const river_config *c) {
+  const int G = c->n_q_heads / c->n_kv_heads;
+  int cap = c->d_model;
+  cap = std::max(cap, c->n_q_heads * c->head_dim);
+  cap = std::max(cap, c->d_ffn);
+  cap = std::max(cap, (kBlock / 64) * G * (c->head_dim + 2));
+  return (int)align_up(cap, 4);
+}
+
+static Layout make_layout(const river_config *c) {
+  Layout y{};
+  const size_t es = c->dtype == RIVER_BF16 ? 2 : 4;
+  const size_t kvd = (size_t)c->n_kv_heads * c->head_dim;
+  const int G = c->n_q_heads / c->n_kv_heads;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  y.cache_bytes = (size_t)c->n_layers * c->max_seq * kvd * es;
+  y.kcache = take(y.cache_bytes);
+  y.vcache = take(y.cache_bytes);
+  y.rope = take((size_t)c->max_seq * (c->head_dim / 2) * sizeof(float2));
+  y.hidden = take((size_t)(c->n_layers + 1) * c->d_model * 4);
+  y.qbuf = take((size_t)c->n_q_heads * c->head_dim * 4);
+  y.obuf = take((size_t)c->n_q_heads * c->head_dim * 4);
+  y.h1 = take((size_t)c->d_model * 4);
+  y.abuf = take((size_t)c->d_ffn * 4);
+  y.logits = take((size_t)c->vocab * 4);
+  y.part_o = take((size_t)c->n_kv_heads * kMaxSplits * G * c->head_dim * 4);
+  y.part_ml = take((size_t)c->n_kv_heads * kMaxSplits * G * sizeof(float2));
+  y.cos_part = take((size_t)kMaxGrid * 3 * 4);
+  y.amax_val = take((size_t)kMaxGrid * 4);
+  y.amax_idx = take((size_t)kMaxGrid * 4);
+  y.state = take(sizeof(DevState));
+  y.rec_token = take((size_t)kRecords * 4);
+  y.rec_exit = take((size_t)kRecords * 4);
+  y.rec_sims = take((size_t)kRecords * c->n_layers * 4);
+  y.layers = take((size_t)c->n_layers * sizeof(DevLayer));
+  y.total = off;
+  return y;
+}
+
+#define HIP_TRY(ctx, expr)                                                              \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) {                                                             \
+      (ctx)->err = std::string(#expr) + ": " + hipGetErrorString(e_);                   \
+      (ctx)->broken = true;                                                             \
+      return RIVER_EHIP;                                                                \
+    }                                                                                   \
+  } while (0)
+
+extern "C" size_t river_workspace_bytes(const river_config *cfg) {
+  if (!valid_cfg(cfg, nullptr)) return 0;
+  return make_layout(cfg).total;
+}
+
+extern "C" int river_quantize_w4(const void *w, int64_t rows, int64_t cols, int32_t group,
+                                 int32_t dtype, void *codes, void *scale, void *zero,
+                                 void *hip_stream) {
+  if (!w || !codes || !scale || !zero || rows < 1 || cols < 16 || cols % 16 || group < 32 ||
+      group % 32 || cols > (1 << 30) || (dtype != RIVER_F32 && dtype != RIVER_BF16))
+    return RIVER_EINVAL;
+  const long long gpr = (cols + group - 1) / group;
+  const long long n = rows * gpr;
+  const int bs = 256;
+  const long long nb = (n + bs - 1) / bs;
+  if (nb > 0x7fffffffLL) return RIVER_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (dtype == RIVER_BF16)
+    k_quantize_w4<1><<<dim3((unsigned)nb), dim3(bs), 0, st>>>(w, rows, (int)cols, group,
+                                                               (uint8_t *)codes, scale, zero);
+  else
+    k_quantize_w4<0><<<dim3((unsigned)nb), dim3(bs), 0, st>>>(w, rows, (int)cols, group,
+                                                               (uint8_t *)codes, scale, zero);
+  return hipGetLastError() == hipSuccess ? RIVER_OK : RIVER_EHIP;
+}
+
+static int reset_state(river_ctx *x) {
+  HIP_TRY(x, hipMemsetAsync(x->ws + x->lay.state, 0, sizeof(DevState), x->stream));
+  x->bar_total = 0;
+  return RIVER_OK;
+}
+
+extern "C" int river_create(const river_config *cfg, const river_weights *w, const river_qweights *q,
+                            void *workspace, size_t workspace_bytes, void *hip_stream,
+                            river_ctx **out) {
+  std::string why;
+  if (!out) { g_create_err = "null out"; return RIVER_EINVAL; }
+  *out = nullptr;
+  if (!valid_cfg(cfg, &why)) { g_create_err = why; return RIVER_EINVAL; }
+  if (!w || !workspace) { g_create_err = "null weights or workspace"; return RIVER_EINVAL; }
+  if (((uintptr_t)workspace) % 256) { g_create_err = "workspace must be 256-byte aligned"; return RIVER_EINVAL; }
+  if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv ||
+      !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down) {
+    g_create_err = "null weight table";
+    return RIVER_EINVAL;
+  }
+  const int L = cfg->n_layers;
+  const void *const *tabs[9] = {w->attn_norm, w->ffn_norm, w->wq, w->wk, w->wv, w->wo,
+                                w->w_gate, w->w_up, w->w_down};
+  for (int l = 0; l < L; ++l)
+    for (int t = 0; t < 9; ++t)
+      if (!tabs[t][l] || ((uintptr_t)tabs[t][l]) % 16) {
+        g_create_err = "null or misaligned (16 B) layer weight";
+        return RIVER_EINVAL;
+      }
+  Layout lay = make_layout(cfg);
+  if (workspace_bytes < lay.total) { g_create_err = "workspace too small"; return RIVER_ENOSPC; }
+
+  river_ctx *x = new river_ctx();
+  x->cfg = *cfg;
+  x->lay = lay;
+  x->ws = (char *)workspace;
+  x->stream = (hipStream_t)hip_stream;
+  x->pos = 0;
+  x->have_token = false;
+  x->steps = 0;
+  x->bar_total = 0;
+  x->broken = false;
+  x->block = kBlock;
+
+  // river twins: a block's twin is usable only if all its 21 pointers are given
+  std::vector<DevLayer> hl(L);
+  x->have_river = q != nullptr;
+  for (int l = 0; l < L; ++l) {
+    DevLayer &d = hl[l];
+    d.attn_norm = w->attn_norm[l];
+    d.ffn_norm = w->ffn_norm[l];
+    d.w[0] = w->wq[l]; d.w[1] = w->wk[l]; d.w[2] = w->wv[l]; d.w[3] = w->wo[l];
+    d.w[4] = w->w_gate[l]; d.w[5] = w->w_up[l]; d.w[6] = w->w_down[l];
+    for (int m = 0; m < 7; ++m) {
+      d.qc[m] = nullptr; d.qs[m] = nullptr; d.qz[m] = nullptr;
+      if (q && q->codes[m] && q->scale[m] && q->zero[m]) {
+        d.qc[m] = (const uint8_t *)q->codes[m][l];
+        d.qs[m] = q->scale[m][l];
+        d.qz[m] = q->zero[m][l];
+        if (((uintptr_t)d.qc[m]) % 16) {
+          g_create_err = "misaligned (16 B) river codes";
+          delete x;
+          return RIVER_EINVAL;
+        }
+      }
+    }
+  }
+  // blocks above L_s must have a complete twin if a river is given at all
+  if (q)
+    for (int l = std::max(cfg->min_exit_layer, 0); l < L; ++l)
+      for (int m = 0; m < 7; ++m)
+        if (!hl[l].qc[m] || !hl[l].qs[m] || !hl[l].qz[m]) {
+          g_create_err = "river twin missing for a block above min_exit_layer";
+          delete x;
+          return RIVER_EINVAL;
+        }
+
+  int dev_id = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev_id) != hipSuccess || hipGetDeviceProperties(&prop, dev_id) != hipSuccess) {
+    g_create_err = "no HIP device";
+    delete x;
+    return RIVER_EHIP;
+  }
+  const int cus = prop.multiProcessorCount;
+  x->grid_persist = std::min(cus, kMaxGrid);
+  x->grid_gemv = std::min(2 * cus, kMaxGrid);
+  if (const char *e = getenv("RIVER_GRID_PERSIST")) x->grid_persist = std::max(1, std::min(atoi(e), cus));
+
+  Dev &D = x->dev;
+  D.L = L; D.d = cfg->d_model; D.nq = cfg->n_q_heads; D.nkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
+  D.ffn = cfg->d_ffn; D.vocab = cfg->vocab; D.max_seq = cfg->max_seq; D.min_exit = cfg->min_exit_layer;
+  D.group = cfg->river_group;
+  D.spin_limit = cfg->spin_limit > 0 ? cfg->spin_limit : (1 << 22);
+  D.xcap = x_capacity(cfg);
+  D.eps = cfg->rms_eps; D.tau = cfg->tau;
+  D.tok_emb = w->tok_emb; D.final_norm = w->final_norm; D.lm_head = w->lm_head;
+  char *ws = x->ws;
+  D.layers = (const DevLayer *)(ws + lay.layers);
+  D.kcache = ws + lay.kcache; D.vcache = ws + lay.vcache;
+  D.rope = (const float2 *)(ws + lay.rope);
+  D.hidden = (float *)(ws + lay.hidden);
+  D.qbuf = (float *)(ws + lay.qbuf); D.obuf = (float *)(ws + lay.obuf);
+  D.h1 = (float *)(ws + lay.h1); D.abuf = (float *)(ws + lay.abuf);
+  D.logits = (float *)(ws + lay.logits);
+  D.part_o = (float *)(ws + lay.part_o); D.part_ml = (float2 *)(ws + lay.part_ml);
+  D.cos_part = (float *)(ws + lay.cos_part);
+  D.amax_val = (float *)(ws + lay.amax_val); D.amax_idx = (int *)(ws + lay.amax_idx);
+  D.st = (DevState *)(ws + lay.state);
+  D.rec_token = (int *)(ws + lay.rec_token); D.rec_exit = (int *)(ws + lay.rec_exit);
+  D.rec_sims = (float *)(ws + lay.rec_sims);
+  x->lds_bytes = ((size_t)D.xcap + 64) * sizeof(float);
+
+  // RoPE table in double precision: angle = pos * base^(-2i/hd)
+  const int half = cfg->head_dim / 2;
+  std::vector<float2> rope((size_t)cfg->max_seq * half);
+  for (int i = 0; i < half; ++i) {
+    const double th = std::pow((double)cfg->rope_base, -2.0 * i / cfg->head_dim);
+    for (int p = 0; p < cfg->max_seq; ++p) {
+      const double a = (double)p * th;
+      rope[(size_t)p * half + i] = make_float2((float)std::cos(a), (float)std::sin(a));
+    }
+  }
+  auto fail = [&](const char *what, hipError_t e) {
+    g_create_err = std::string(what) + ": " + hipGetErrorString(e);
+    delete x;
+    return RIVER_EHIP;
+  };
+  hipError_t e;
+  if ((e = hipMemcpyAsync(ws + lay.rope, rope.data(), rope.size() * sizeof(float2),
+                          hipMemcpyHostToDevice, x->stream)) != hipSuccess)
+    return fail("rope upload", e);
+  if ((e = hipMemcpyAsync(ws + lay.layers, hl.data(), hl.size() * sizeof(DevLayer),
+                          hipMemcpyHostToDevice, x->stream)) != hipSuccess)
+    return fail("layer table upload", e);
+  // everything after the caches starts at zero (state, counters, records, activations)
+  if ((e = hipMemsetAsync(ws + lay.hidden, 0, lay.layers - lay.hidden, x->stream)) != hipSuccess)
+    return fail("workspace clear", e);
+  if ((e = hipMemsetAsync(ws + lay.kcache, 0, 2 * align_up(lay.cache_bytes, 256), x->stream)) != hipSuccess)
+    return fail("cache clear", e);
+  if ((e = hipStreamSynchronize(x->stream)) != hipSuccess) return fail("create sync", e);
+
+  if (x->lds_bytes > 48 * 1024) {
+    const int lb = (int)x->lds_bytes;
+    const void *fns[] = {
+        (const void *)k_qkv<0>, (const void *)k_qkv<1>, (const void *)k_attn<0>, (const void *)k_attn<1>,
+        (const void *)k_oproj<0>, (const void *)k_oproj<1>, (const void *)k_gateup<0>,
+        (const void *)k_gateup<1>, (const void *)k_down<0>, (const void *)k_down<1>,
+        (const void *)k_head<0>, (const void *)k_head<1>, (const void *)k_step_persistent<0>,
+        (const void *)k_step_persistent<1>};
+    for (const void *f : fns)
+      if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lb)) != hipSuccess)
+        return fail("hipFuncSetAttribute(max dynamic LDS)", e);
+  }
+  *out = x;
+  return RIVER_OK;
+}
+
+// Enqueue one token (prompt position or decode step).
+template <int DT>
+static int launch_step(river_ctx *x, const StepArgs &A0) {
+  StepArgs A = A0;
+  const Dev &D = x->dev;
+  const dim3 blk(x->block);
+  const size_t lds = x->lds_bytes;
+  hipStream_t s = x->stream;
+  if (x->cfg.exec_mode == RIVER_EXEC_PERSISTENT) {
+    A.bar_base = x->bar_total;
+    k_step_persistent<DT><<<dim3(x->grid_persist), blk, lds, s>>>(D, A);
+    x->bar_total += (unsigned long long)x->grid_persist * (1 + 5ull * D.L);
+  } else {
+    const dim3 gg(x->grid_gemv);
+    k_embed<DT><<<dim3(8), blk, 0, s>>>(D, A);
+    for (int l = 0; l < D.L; ++l) {
+      k_qkv<DT><<<gg, blk, lds, s>>>(D, A, l);
+      k_attn<DT><<<dim3(std::min(D.nkv * A.n_splits, kMaxGrid)), blk, lds, s>>>(D, A, l);
+      k_oproj<DT><<<gg, blk, lds, s>>>(D, A, l);
+      k_gateup<DT><<<gg, blk, lds, s>>>(D, A, l);
+      k_down<DT><<<gg, blk, lds, s>>>(D, A, l);
+    }
+    if (A.want_head) k_head<DT><<<gg, blk, lds, s>>>(D, A);
+  }
+  HIP_TRY(x, hipGetLastError());
+  return RIVER_OK;
+}
+
+static int enqueue(river_ctx *x, int token, int forced_e, int want_head, int rec_slot) {
+  StepArgs A{};
+  A.pos = x->pos;
+  A.token = token;
+  A.forced_e = forced_e;
+  A.want_head = want_head;
+  A.rec_slot = rec_slot;
+  const int T = x->pos + 1;
+  A.n_splits = std::max(1, std::min(kMaxSplits, (T + kPosPerSplit - 1) / kPosPerSplit));
+  A.bar_base = 0;
+  const int rc = x->cfg.dtype == RIVER_BF16 ? launch_step<1>(x, A) : launch_step<0>(x, A);
+  if (rc == RIVER_OK) x->pos += 1;
+  return rc;
+}
+
+// After a synchronising call: did a bounded device wait give up?
+static int check_device_error(river_ctx *x) {
+  int err = 0;
+  HIP_TRY(x, hipMemcpyAsync(&err, (char *)x->dev.st + offsetof(DevState, error), sizeof(int),
+                            hipMemcpyDeviceToHost, x->stream));
+  HIP_TRY(x, hipStreamSynchronize(x->stream));
+  if (err) {
+    x->err = "a device-wide barrier wait exceeded spin_limit; results of the step are invalid";
+    x->broken = true;
+    return RIVER_EHIP;
+  }
+  return RIVER_OK;
+}
+
+#define CHECK_CTX(x)                                   \
+  do {                                                 \
+    if (!(x)) return RIVER_EINVAL;                     \
+    if ((x)->broken) return RIVER_EHIP;                \
+  } while (0)
+
+extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, int32_t n_tokens,
+                             int32_t *out_token) {
+  if (!x) return RIVER_EINVAL;
+  if (seq != 0 || !tokens || n_tokens < 1) { x->err = "bad prefill arguments"; return RIVER_EINVAL; }
+  if (n_tokens > x->cfg.max_seq) { x->err = "prompt longer than max_seq"; return RIVER_ENOSPC; }
+  for (int i = 0; i < n_tokens; ++i)
+    if (tokens[i] < 0 || tokens[i] >= x->cfg.vocab) { x->err = "token id out of range"; return RIVER_EINVAL; }
+  // a new sequence also clears a previous device-side time-out
+  x->broken = false;
+  int rc = reset_state(x);
+  if (rc) return rc;
+  x->pos = 0;
+  x->have_token = false;
+  for (int i = 0; i < n_tokens; ++i) {
+    rc = enqueue(x, tokens[i], x->cfg.n_layers, i == n_tokens - 1, -1);
+    if (rc) return rc;
+  }
+  rc = check_device_error(x);
+  if (rc) return rc;
+  x->have_token = true;
+  if (out_token) {
+    HIP_TRY(x, hipMemcpyAsync(out_token, (char *)x->dev.st + offsetof(DevState, cur_token), sizeof(int),
+                              hipMemcpyDeviceToHost, x->stream));
+    HIP_TRY(x, hipStreamSynchronize(x->stream));
+  }
+  return RIVER_OK;
+}
+
+extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const int32_t *forced_exit,
+                                 int32_t *out_token, int32_t *out_exit_layer, float *out_sims) {
+  CHECK_CTX(x);
+  if (!x->have_token && !in_token) { x->err = "decode before prefill"; return RIVER_ESTATE; }
+  if (x->pos < 1) { x->err = "decode before prefill"; return RIVER_ESTATE; }
+  if (x->pos >= x->cfg.max_seq) { x->err = "KV cache full"; return RIVER_ENOSPC; }
+  const int L = x->cfg.n_layers;
+  int tok = -1, fe = -1;
+  if (in_token) {
+    tok = *in_token;
+    if (tok < 0 || tok >= x->cfg.vocab) { x->err = "token id out of range"; return RIVER_EINVAL; }
+  }
+  if (forced_exit) {
+    fe = *forced_exit;
+    const bool ok = fe == L || (fe >= x->cfg.min_exit_layer && fe <= L && fe >= 0);
+    if (!ok) { x->err = "forced exit position outside [L_s, L]"; return RIVER_EINVAL; }
+  }
+  if ((fe >= 0 && fe < L) || (fe < 0 && x->cfg.tau < 1.0f)) {
+    if (!x->have_river) { x->err = "an exit is possible but no river weights were given"; return RIVER_ESTATE; }
+  }
+  const int slot = (int)(x->steps % kRecords);
+  int rc = enqueue(x, tok, fe, 1, slot);
+  if (rc) return rc;
+  x->steps += 1;
+  x->have_token = true;
+  if (!out_token) {
+    if (out_exit_layer || out_sims) { x->err = "out_token is NULL but other outputs are not"; return RIVER_EINVAL; }
+    return RIVER_OK;
+  }
+  HIP_TRY(x, hipMemcpyAsync(out_token, x->dev.rec_token + slot, 4, hipMemcpyDeviceToHost, x->stream));
+  if (out_exit_layer)
+    HIP_TRY(x, hipMemcpyAsync(out_exit_layer, x->dev.rec_exit + slot, 4, hipMemcpyDeviceToHost, x->stream));
+  if (out_sims)
+    HIP_TRY(x, hipMemcpyAsync(out_sims, x->dev.rec_sims + (size_t)slot * L, (size_t)L * 4,
+                              hipMemcpyDeviceToHost, x->stream));
+  return check_device_error(x);
+}
+
+extern "C" int river_read_records(river_ctx *x, int32_t n, int32_t *tokens, int32_t *exit_layers,
+                                  float *sims) {
+  CHECK_CTX(x);
+  if (n < 0 || n > kRecords || n > x->steps || (n > 0 && (!tokens || !exit_layers))) {
+    x->err = "bad record count";
+    return RIVER_EINVAL;
+  }
+  const int L = x->cfg.n_layers;
+  int rc = check_device_error(x);
+  if (rc) return rc;
+  for (int i = 0; i < n; ++i) {
+    const int slot = (int)((x->steps - n + i) % kRecords);
+    HIP_TRY(x, hipMemcpyAsync(tokens + i, x->dev.rec_token + slot, 4, hipMemcpyDeviceToHost, x->stream));
+    HIP_TRY(x, hipMemcpyAsync(exit_layers + i, x->dev.rec_exit + slot, 4, hipMemcpyDeviceToHost, x->stream));
+    if (sims)
+      HIP_TRY(x, hipMemcpyAsync(sims + (size_t)i * L, x->dev.rec_sims + (size_t)slot * L, (size_t)L * 4,
+                                hipMemcpyDeviceToHost, x->stream));
+  }
+  HIP_TRY(x, hipStreamSynchronize(x->stream));
+  return RIVER_OK;
+}
+
+extern "C" int river_rewind(river_ctx *x, int32_t seq, int32_t new_len) {
+  CHECK_CTX(x);
+  if (seq != 0 || new_len < 0 || new_len > x->pos) { x->err = "bad rewind length"; return RIVER_EINVAL; }
+  x->pos = new_len;
+  return RIVER_OK;
+}
+
+extern "C" int river_position(const river_ctx *x) { return x ? x->pos : RIVER_EINVAL; }
+
+extern "C" int river_get_debug(river_ctx *x, int32_t what, void *dst, size_t bytes) {
+  if (!x || !dst) return RIVER_EINVAL;
+  const char *src = nullptr;
+  size_t n = 0;
+  switch (what) {
+    case RIVER_DBG_HIDDEN: src = (const char *)x->dev.hidden; n = (size_t)(x->cfg.n_layers + 1) * x->cfg.d_model * 4; break;
+    case RIVER_DBG_LOGITS: src = (const char *)x->dev.logits; n = (size_t)x->cfg.vocab * 4; break;
+    case RIVER_DBG_KCACHE: src = (const char *)x->dev.kcache; n = x->lay.cache_bytes; break;
+    case RIVER_DBG_VCACHE: src = (const char *)x->dev.vcache; n = x->lay.cache_bytes; break;
+    default: x->err = "unknown debug buffer"; return RIVER_EINVAL;
+  }
+  if (bytes != n) { x->err = "debug buffer size mismatch"; return RIVER_EINVAL; }
+  HIP_TRY(x, hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToHost, x->stream));
+  HIP_TRY(x, hipStreamSynchronize(x->stream));
+  return RIVER_OK;
+}
+
+extern "C" int river_fill_cache(river_ctx *x, int32_t value) {
+  CHECK_CTX(x);
+  const uint32_t b = (uint32_t)value & 0xffu;
+  const uint32_t word = b | (b << 8) | (b << 16) | (b << 24);
+  const size_t n16 = 2 * align_up(x->lay.cache_bytes, 256) / 16;
+  k_fill_bytes<<<dim3(1024), dim3(256), 0, x->stream>>>((uint4 *)x->dev.kcache, n16, word);
+  HIP_TRY(x, hipGetLastError());
+  return RIVER_OK;
+}
+
+extern "C" const char *river_last_error(const river_ctx *x) {
+  return x ? x->err.c_str() : g_create_err.c_str();
+}
+
+extern "C" int river_destroy(river_ctx *x) {
+  if (!x) return RIVER_OK;
+  hipStreamSynchronize(x->stream);
+  delete x;
+  return RIVER_OK;
+}

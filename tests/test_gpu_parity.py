@@ -1,0 +1,347 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Bars (from the benchmark spec): exit positions and token ids bit-exact under teacher
+forcing except at steps whose similarity lies within 1e-3 of tau; hidden states and
+logits within max relative error 1e-4 (fp32) / 2e-2 (bf16), where the relative error of a
+vector is |a-b|_inf / |b|_inf with b the oracle's."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import grid_model
+from oracle import river_oracle as ro
+from paper_2604_18396_amd import binding, configs, inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {configs.DTYPE_F32: 1e-4, configs.DTYPE_BF16: 2e-2}
+BAND = 1e-3
+MODES = [binding.EXEC_KERNELS, binding.EXEC_PERSISTENT]
+MODE_IDS = ["kernels", "persistent"]
+
+TINY_BF16 = configs.TINY.with_(name="tiny-bf16", dtype=configs.DTYPE_BF16)
+# spans several wavefront tiles with ragged tails: 2816 columns = 1 full + 1 partial
+# 2048-code wave load, vocab not a multiple of the 4-row task, 3 splits of attention
+MID = configs.ModelConfig("mid-bf16", 3, 1024, 8, 2, 128, 2816, 1002, 500000.0, 1e-5,
+                          configs.DTYPE_BF16, 192, 1, 2.0)
+MID_F32 = MID.with_(name="mid-fp32", dtype=configs.DTYPE_F32, n_q_heads=16, n_kv_heads=2, head_dim=64)
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def relerr(a, b):
+    return float(np.abs(np.asarray(a, np.float64) - b).max() / max(np.abs(b).max(), 1e-30))
+
+
+class Pair:
+    """Oracle and HIP context on the same weights; each side quantises its own river."""
+
+    def __init__(self, cfg, weights, mode, with_river=True):
+        self.cfg = cfg
+        self.o = ro.Oracle(cfg, weights, ro.quantize_river(cfg, weights) if with_river else None)
+        self.dw = binding.upload_weights(weights)
+        self.dr = binding.quantize_river(cfg, self.dw) if with_river else None
+        self.g = binding.River(cfg, self.dw, self.dr, exec_mode=mode)
+
+    def prefill(self, prompt):
+        to = self.o.prefill(prompt)
+        tg = self.g.prefill(prompt)
+        self.compare_state("prefill")
+        assert tg == to
+        return to
+
+    def compare_state(self, what):
+        tol = TOL[self.cfg.dtype]
+        ho, hg = self.o.hidden(), self.g.hidden()
+        for l in range(self.cfg.n_layers + 1):
+            err = relerr(hg[l], ho[l])
+            assert err <= tol, f"{what}: hidden state h({l}) rel err {err:.3e} > {tol}"
+        err = relerr(self.g.logits(), self.o.logits())
+        assert err <= tol, f"{what}: logits rel err {err:.3e} > {tol}"
+
+    def step(self, token, forced=None, what="step"):
+        """Teacher-forced step: both sides consume `token`.  Returns the oracle's outputs."""
+        cfg = self.cfg
+        to, eo, so = self.o.decode_step(token, forced)
+        tg, eg, sg = self.g.decode_step(token, forced)
+        if forced is None and eg != eo:
+            # allowed only if a similarity that decided lies within the band around tau
+            k = min(eg, eo)
+            assert abs(so[k - 1] - np.float32(cfg.tau)) < BAND, \
+                f"{what}: exit {eg} vs oracle {eo}, s={so[k - 1]} not near tau={cfg.tau}"
+            self.g.rewind(self.g.pos - 1)            # replay with the oracle's decision
+            tg, eg, sg = self.g.decode_step(token, eo)
+        assert eg == eo, f"{what}: exit position {eg} vs oracle {eo}"
+        ne = eo if eo > 0 else 0
+        np.testing.assert_allclose(sg[:ne], so[:ne], rtol=0, atol=2e-4 if cfg.dtype else 2e-5,
+                                   err_msg=f"{what}: similarities")
+        assert np.all(np.isnan(sg[ne:])) and np.all(np.isnan(so[ne:]))
+        self.compare_state(what)
+        if tg != to:
+            # a different greedy token is only acceptable on a numerical near-tie of the logits
+            lo = self.o.logits()
+            gap = (lo[to] - lo[tg]) / max(np.abs(lo).max(), 1e-30)
+            assert gap <= TOL[cfg.dtype], f"{what}: token {tg} vs oracle {to} (gap {gap:.3e})"
+        return to, eo, so
+
+    def compare_cache(self, n_pos):
+        ko, vo = self.o.kcache(), self.o.vcache()
+        kg, vg = self.g.kcache(), self.g.vcache()
+        tol = TOL[self.cfg.dtype]
+        for name, a, b in (("K", kg, ko), ("V", vg, vo)):
+            assert np.all(np.isfinite(a[:, :n_pos])), f"{name} cache has unwritten slots"
+            for l in range(self.cfg.n_layers):
+                err = relerr(a[l, :n_pos], b[l, :n_pos])
+                assert err <= tol, f"{name} cache layer {l + 1}: rel err {err:.3e}"
+
+    def close(self):
+        self.g.close()
+        self.o.close()
+
+
+def run_teacher_forced(pair, prompt, steps, forced=None, label=""):
+    tok = pair.prefill(prompt)
+    exits = []
+    for i in range(steps):
+        f = None if forced is None else int(forced[i])
+        tok, e, _ = pair.step(tok, f, what=f"{label} step {i}")
+        exits.append(e)
+    return exits
+
+
+# ---------------------------------------------------------------- quantiser
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["fp32", "bf16"])
+def test_river_construction_bit_exact(dtype):
+    say(f"quantiser parity {dtype}")
+    g = torch.Generator().manual_seed(5)
+    for rows, cols, group in [(64, 256, 64), (50, 688, 64), (33, 4096, 64), (7, 2816, 128)]:
+        w = (torch.randn(rows, cols, generator=g) * 0.02).to(dtype)
+        w[0, :64] = 0.25                                   # a constant group
+        co, so, zo = ro.quantize_w4(w, group)
+        cg, sg, zg = binding.river_quantize_w4(w.cuda(), group)
+        torch.cuda.synchronize()
+        assert torch.equal(cg.cpu(), co), (rows, cols, group)
+        assert torch.equal(sg.cpu().view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                           so.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+        assert torch.equal(zg.cpu().view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                           zo.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+
+
+# ------------------------------------------------------------- tiny configs
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("tau", [0.9, 0.675, 0.52])
+def test_c1_threshold_mode(mode, tau):
+    say(f"C1 threshold tau={tau} mode={mode}")
+    cfg = configs.TINY.with_(tau=tau)
+    w = inputs.make_weights(cfg, configs.C1.seed_weights)
+    pair = Pair(cfg, w, mode)
+    prompt = inputs.make_prompt(cfg.vocab, configs.C1.prompt_len, configs.C1.seed_prompt)
+    exits = run_teacher_forced(pair, prompt, configs.C1.decode_steps, label=f"C1 tau={tau}")
+    if tau == 0.9:
+        assert set(exits) == {cfg.n_layers}
+    else:
+        assert len(set(exits)) > 1
+    pair.compare_cache(configs.C1.prompt_len + configs.C1.decode_steps)
+    pair.close()
+
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
+def test_forced_mixed_schedule_all_depths(mode, cfg0):
+    say(f"forced schedule {cfg0.name} mode={mode}")
+    cfg = cfg0.with_(min_exit_layer=0)
+    w = inputs.make_weights(cfg, 21)
+    pair = Pair(cfg, w, mode)
+    sched = [0, 4, 1, 2, 3, 3, 0, 2, 4, 1, 1, 4]
+    exits = run_teacher_forced(pair, inputs.make_prompt(cfg.vocab, 5, 22), len(sched), sched, cfg0.name)
+    assert exits == sched
+    pair.compare_cache(5 + len(sched))
+    pair.close()
+
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+def test_never_exit_equals_dense_bitwise(mode):
+    """tau >= 1 and exit forced at L run no river block: logits identical to a context
+    that has no river at all."""
+    say(f"never-exit mode={mode}")
+    cfg = configs.TINY
+    w = inputs.make_weights(cfg, configs.C1.seed_weights)
+    dw = binding.upload_weights(w)
+    dr = binding.quantize_river(cfg, dw)
+    prompt = inputs.make_prompt(cfg.vocab, 16, configs.C1.seed_prompt)
+    outs = []
+    for c, river, forced in ((cfg.with_(tau=1.0), dr, None), (cfg.with_(tau=-2.0), dr, cfg.n_layers),
+                             (cfg.with_(tau=2.0), None, None)):
+        g = binding.River(c, dw, river, exec_mode=mode)
+        tok = g.prefill(prompt)
+        logs = []
+        for _ in range(6):
+            tok, e, _ = g.decode_step(tok, forced)
+            assert e == cfg.n_layers
+            logs.append(g.logits())
+        outs.append(np.array(logs))
+        g.close()
+    np.testing.assert_array_equal(outs[0], outs[2])
+    np.testing.assert_array_equal(outs[1], outs[2])
+
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
+def test_lossless_river_equals_dense(mode, cfg0):
+    """Block matrices on the 4-bit grid: the twin equals the backbone, so any schedule
+    reproduces the dense run (traversal + shared cache slots, no quantisation error)."""
+    say(f"lossless river {cfg0.name} mode={mode}")
+    cfg = cfg0.with_(min_exit_layer=1)
+    w = grid_model(cfg, 31)
+    dw = binding.upload_weights(w)
+    dr = binding.quantize_river(cfg, dw)
+    prompt = inputs.make_prompt(cfg.vocab, 6, 32)
+    sched = [1, 3, 2, 4, 1, 2, 3, 1]
+    runs = []
+    for forced in ([cfg.n_layers] * len(sched), sched):
+        g = binding.River(cfg, dw, dr, exec_mode=mode)
+        tok = g.prefill(prompt)
+        hs = []
+        for f in forced:
+            tok, e, _ = g.decode_step(tok, f)
+            assert e == f
+            hs.append(g.hidden())
+        runs.append(np.array(hs))
+        g.close()
+    for a, b in zip(runs[1], runs[0]):
+        for l in range(cfg.n_layers + 1):
+            assert relerr(a[l], b[l].astype(np.float64)) <= 1e-5
+
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+def test_kv_canary_every_slot_written(mode):
+    """Intrinsic KV integrity: with the cache pre-filled with NaN, every slot (l, p < pos)
+    is finite after the run (backbone or river wrote it) and no slot beyond pos was touched."""
+    say(f"KV canary mode={mode}")
+    cfg = configs.TINY.with_(tau=0.52)
+    w = inputs.make_weights(cfg, configs.C1.seed_weights)
+    pair = Pair(cfg, w, mode)
+    pair.g.fill_cache(0xFF)
+    prompt = inputs.make_prompt(cfg.vocab, 16, configs.C1.seed_prompt)
+    exits = run_teacher_forced(pair, prompt, 20, label="canary")
+    assert min(exits) < cfg.n_layers
+    n = 36
+    pair.compare_cache(n)
+    assert np.all(np.isnan(pair.g.kcache()[:, n:])) and np.all(np.isnan(pair.g.vcache()[:, n:]))
+    assert np.all(pair.o.written()[:, :n] == 1)
+    pair.close()
+
+
+# ------------------------------------------------- several tiles, ragged tails
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("cfg", [MID, MID_F32], ids=lambda c: c.name)
+def test_mid_shape_ragged_tiles(mode, cfg):
+    say(f"mid shape {cfg.name} mode={mode}")
+    w = inputs.make_weights(cfg, 77)
+    pair = Pair(cfg, w, mode)
+    prompt = inputs.make_prompt(cfg.vocab, 130, 78)          # 3 attention splits, ragged
+    sched = [1, 3, 2, 3, 1, 2, 3, 3, 1, 2]
+    exits = run_teacher_forced(pair, prompt, len(sched), sched, cfg.name)
+    assert exits == sched
+    pair.compare_cache(130 + len(sched))
+    pair.close()
+
+
+# ------------------------------------------------------------ API behaviour
+
+def test_async_steps_and_records_match_sync():
+    say("async records")
+    cfg = configs.TINY.with_(tau=0.675)
+    w = inputs.make_weights(cfg, configs.C1.seed_weights)
+    dw = binding.upload_weights(w)
+    dr = binding.quantize_river(cfg, dw)
+    prompt = inputs.make_prompt(cfg.vocab, 16, configs.C1.seed_prompt)
+    g = binding.River(cfg, dw, dr)
+    tok = g.prefill(prompt)
+    sync = []
+    for _ in range(24):
+        tok, e, s = g.decode_step(tok)
+        sync.append((tok, e, s.copy()))
+    h_sync, l_sync = g.hidden(), g.logits()
+    g.close()
+    g = binding.River(cfg, dw, dr)
+    g.prefill(prompt)
+    for _ in range(24):
+        g.decode_step(None, None, sync=False)      # consumes the device-side token, no host sync
+    toks, es, sims = g.read_records(24)
+    assert list(toks) == [t for t, _, _ in sync]
+    assert list(es) == [e for _, e, _ in sync]
+    np.testing.assert_array_equal(sims, np.array([s for _, _, s in sync]))
+    # determinism: same seed, same bits
+    np.testing.assert_array_equal(g.hidden(), h_sync)
+    np.testing.assert_array_equal(g.logits(), l_sync)
+    g.close()
+
+
+def test_error_paths_through_the_abi():
+    say("error paths")
+    cfg = configs.TINY.with_(max_seq=8)
+    w = inputs.make_weights(cfg, 3)
+    dw = binding.upload_weights(w)
+    dr = binding.quantize_river(cfg, dw)
+    g = binding.River(cfg, dw, dr)
+    with pytest.raises(binding.RiverError) as ei:
+        g.decode_step(1)
+    assert ei.value.code == binding.RIVER_ESTATE                 # decode before prefill
+    with pytest.raises(binding.RiverError) as ei:
+        g.prefill([cfg.vocab])
+    assert ei.value.code == binding.RIVER_EINVAL
+    with pytest.raises(binding.RiverError) as ei:
+        g.prefill(list(range(9)))
+    assert ei.value.code == binding.RIVER_ENOSPC
+    g.prefill([1, 2, 3, 4, 5, 6, 7])
+    with pytest.raises(binding.RiverError) as ei:
+        g.decode_step(1, 1)                                      # below L_s
+    assert ei.value.code == binding.RIVER_EINVAL
+    g.decode_step(1)
+    with pytest.raises(binding.RiverError) as ei:
+        g.decode_step(1)                                         # cache full
+    assert ei.value.code == binding.RIVER_ENOSPC
+    with pytest.raises(binding.RiverError):
+        g.rewind(99)
+    g.rewind(3)
+    assert g.pos == 3
+    g.close()
+    dense = binding.River(cfg.with_(tau=0.1), dw, None)
+    dense.prefill([1, 2])
+    with pytest.raises(binding.RiverError) as ei:
+        dense.decode_step(1)                                     # could exit but has no river
+    assert ei.value.code == binding.RIVER_ESTATE
+    dense.close()
+
+
+def test_barrier_wait_is_bounded():
+    """A spin limit of one poll makes device-wide waits give up at once: the kernel must
+    still run to completion and the host must report the time-out, not hang."""
+    say("bounded barrier wait")
+    cfg = configs.TINY
+    w = inputs.make_weights(cfg, 3)
+    dw = binding.upload_weights(w)
+    g = binding.River(cfg.with_(tau=2.0), dw, None, exec_mode=binding.EXEC_PERSISTENT, spin_limit=1)
+    try:
+        g.prefill([1, 2, 3, 4])
+        timed_out = False
+    except binding.RiverError as e:
+        timed_out = e.code == binding.RIVER_EHIP
+    # with one poll per wait at least one of the 21 barriers per token gives up
+    assert timed_out
+    with pytest.raises(binding.RiverError):
+        g.decode_step(1)
+    g.close()
+    # a fresh context on the same device works afterwards
+    g = binding.River(cfg.with_(tau=2.0), dw, None, exec_mode=binding.EXEC_PERSISTENT)
+    assert 0 <= g.prefill([1, 2, 3, 4]) < cfg.vocab
+    g.close()
