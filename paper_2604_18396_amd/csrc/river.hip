@@ -18,61 +18,126 @@ using namespace river;
 
 // ------------------------------------------------------------------ kernels
 
+// One-kernel-per-phase mode.  The exit state travels between the kernels of a token in
+// DevState: the QKV kernel of block l derives it (every workgroup identically), workgroup 0
+// stores it in slot l & 1, the other kernels of the block read that slot.
+__device__ __forceinline__ Ctl load_ctl(const Dev &D, int l) {
+  Ctl c;
+  c.river = D.st->slot_river[l & 1] != 0;
+  c.exit_pos = D.st->slot_exit[l & 1];
+  return c;
+}
+
 template <int DT>
-__global__ void k_embed(Dev D, StepArgs A) { phase_embed<DT>(D, A); }
-template <int DT>
-__global__ void k_qkv(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_qkv(Dev D, StepArgs A, int l) {
   extern __shared__ float lds[];
-  phase_qkv<DT>(D, A, l, lds);
+  Ctl ctl;
+  if (l == 0) {
+    ctl = ctl_init(D, A);
+    record_init(D, A);
+  } else {
+    ctl = load_ctl(D, l - 1);
+    exit_test(D, A, l, ctl, lds);
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    D.st->slot_river[l & 1] = ctl.river;
+    D.st->slot_exit[l & 1] = ctl.exit_pos;
+  }
+  Regs<DT> pre;
+  prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);
+  phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ void k_attn(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_attn(Dev D, StepArgs A, int l) {
   extern __shared__ float lds[];
   phase_attn<DT>(D, A, l, lds);
 }
 template <int DT>
-__global__ void k_oproj(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_oproj(Dev D, StepArgs A, int l) {
   extern __shared__ float lds[];
-  phase_oproj<DT>(D, A, l, lds);
+  const Ctl ctl = load_ctl(D, l);
+  Regs<DT> pre;
+  prefetch_phase<DT>(D, l, PH_O, ctl.river, pre);
+  phase_oproj<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ void k_gateup(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_gateup(Dev D, StepArgs A, int l) {
   extern __shared__ float lds[];
-  phase_gateup<DT>(D, A, l, lds);
+  const Ctl ctl = load_ctl(D, l);
+  Regs<DT> pre;
+  prefetch_phase<DT>(D, l, PH_GU, ctl.river, pre);
+  phase_gateup<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ void k_down(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_down(Dev D, StepArgs A, int l) {
   extern __shared__ float lds[];
-  phase_down<DT>(D, A, l, lds);
+  const Ctl ctl = load_ctl(D, l);
+  Regs<DT> pre;
+  prefetch_phase<DT>(D, l, PH_DOWN, ctl.river, pre);
+  phase_down<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ void k_head(Dev D, StepArgs A) {
+__global__ __launch_bounds__(kBlock) void k_head(Dev D, StepArgs A) {
   extern __shared__ float lds[];
-  phase_head<DT>(D, A, lds);
+  const Ctl ctl = load_ctl(D, D.L - 1);
+  Regs<DT> pre;
+  prefetch_head<DT>(D, pre);
+  phase_head<DT>(D, A, ctl, lds, pre);
 }
 
-// One launch per token: all phases in order, device-wide barriers in between.  The
-// number of barriers (1 + 5 L) is the same for every workgroup whatever the exit state.
+// One launch per token: all phases in order, device-wide barriers in between; the first
+// step of each phase's weights is issued between arriving at and waiting on the barrier
+// before it.  The number of barriers (5 L) is the same for every workgroup whatever the
+// exit state.
 template <int DT>
-__global__ void k_step_persistent(Dev D, StepArgs A) {
+__global__ __launch_bounds__(kBlock) void k_step_persistent(Dev D, StepArgs A) {
   extern __shared__ float lds[];
-  unsigned long long target = A.bar_base;
-  const unsigned long long n = gridDim.x;
-  phase_embed<DT>(D, A);
-  grid_barrier(D.st, target += n, D.spin_limit);
+  unsigned long long k = A.bar_base;
+  Ctl ctl = ctl_init(D, A);
+  record_init(D, A);
+  Regs<DT> pre;
+  bool pre_river = ctl.river;
+  prefetch_phase<DT>(D, 0, PH_QKV, pre_river, pre);
   for (int l = 0; l < D.L; ++l) {
-    phase_qkv<DT>(D, A, l, lds);
-    grid_barrier(D.st, target += n, D.spin_limit);
+    if (l > 0) {
+      exit_test(D, A, l, ctl, lds);
+      if (ctl.river != pre_river) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
+    }
+    phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
+    barrier_arrive(D.st, ++k);
+    barrier_wait(D.st, k, D.spin_limit);
     phase_attn<DT>(D, A, l, lds);
-    grid_barrier(D.st, target += n, D.spin_limit);
-    phase_oproj<DT>(D, A, l, lds);
-    grid_barrier(D.st, target += n, D.spin_limit);
-    phase_gateup<DT>(D, A, l, lds);
-    grid_barrier(D.st, target += n, D.spin_limit);
-    phase_down<DT>(D, A, l, lds);
-    grid_barrier(D.st, target += n, D.spin_limit);
+    barrier_arrive(D.st, ++k);
+    prefetch_phase<DT>(D, l, PH_O, ctl.river, pre);
+    barrier_wait(D.st, k, D.spin_limit);
+    phase_oproj<DT>(D, A, l, ctl.river, lds, pre);
+    barrier_arrive(D.st, ++k);
+    prefetch_phase<DT>(D, l, PH_GU, ctl.river, pre);
+    barrier_wait(D.st, k, D.spin_limit);
+    phase_gateup<DT>(D, A, l, ctl.river, lds, pre);
+    barrier_arrive(D.st, ++k);
+    prefetch_phase<DT>(D, l, PH_DOWN, ctl.river, pre);
+    barrier_wait(D.st, k, D.spin_limit);
+    phase_down<DT>(D, A, l, ctl.river, lds, pre);
+    barrier_arrive(D.st, ++k);
+    if (l + 1 < D.L) {
+      pre_river = guess_river_after(A, ctl, l + 1);
+      prefetch_phase<DT>(D, l + 1, PH_QKV, pre_river, pre);
+    } else if (A.want_head) {
+      prefetch_head<DT>(D, pre);
+    }
+    barrier_wait(D.st, k, D.spin_limit);
   }
-  if (A.want_head) phase_head<DT>(D, A, lds);
+  if (A.want_head) phase_head<DT>(D, A, ctl, lds, pre);
+}
+
+// Interleaves the river's scale and zero arrays into one (scale, zero) pair per group,
+// so that a lane fetches both with one load.
+template <int DT>
+__global__ void k_pack_sz(const void *scale, const void *zero, void *out, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n)
+    ((typename Store<DT>::SZ *)out)[i] = Store<DT>::pack(Store<DT>::ld(scale, i), Store<DT>::ld(zero, i));
 }
 
 // River construction: one thread per quantisation group.
@@ -118,9 +183,9 @@ __global__ void k_fill_bytes(uint4 *p, size_t n16, uint32_t word) {
 // ------------------------------------------------------------------ context
 
 struct Layout {
-  size_t kcache, vcache, rope, hidden, qbuf, obuf, h1, abuf, logits, part_o, part_ml, cos_part,
-      amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, total;
-  size_t cache_bytes;
+  size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part,
+      amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, qsz, total;
+  size_t cache_bytes, qsz_bytes;
 };
 
 struct river_ctx {
@@ -156,11 +221,12 @@ static bool valid_cfg(const river_config *c, std::string *why) {
   if (c->river_group < 32 || c->river_group % 32) return bad("river_group must be a multiple of 32");
   if (c->n_q_heads % c->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
   const int G = c->n_q_heads / c->n_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return bad("query heads per kv head must be 1, 2, 4 or 8");
-  if (c->n_kv_heads > kMaxKvHeads) return bad("too many kv heads");
+  if (G != 1 && G != 2 && G % 4) return bad("query heads per kv head must be 1, 2 or a multiple of 4");
+  if (c->n_kv_heads * (G > 4 ? G / 4 : 1) > kMaxKvHeads) return bad("too many kv heads");
   const int hd = c->head_dim;
   if (hd < 32 || hd > 256 || (hd & (hd - 1))) return bad("head_dim must be a power of two in [32, 256]");
   if (c->d_model % 16 || c->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
+  if (c->vocab % 2) return bad("vocab must be even");
   if (c->min_exit_layer < 0 || c->min_exit_layer > c->n_layers) return bad("min_exit_layer out of range");
   if (c->exec_mode != RIVER_EXEC_KERNELS && c->exec_mode != RIVER_EXEC_PERSISTENT) return bad("bad exec_mode");
   if (c->spin_limit < 0) return bad("negative spin_limit");
@@ -168,15 +234,29 @@ static bool valid_cfg(const river_config *c, std::string *why) {
   return true;
 }
 
-static constexpr int kBlock = 256;
 
 static int x_capacity(const river_config *c) {
   const int G = c->n_q_heads / c->n_kv_heads;
   int cap = c->d_model;
   cap = std::max(cap, c->n_q_heads * c->head_dim);
   cap = std::max(cap, c->d_ffn);
-  cap = std::max(cap, (kBlock / 64) * G * (c->head_dim + 2));
+  cap = std::max(cap, kWaves * std::min(G, 4) * (c->head_dim + 2));
   return (int)align_up(cap, 4);
+}
+
+// [rows, cols] of block matrix m (wq wk wv wo w_gate w_up w_down)
+static void matrix_shape(const river_config *c, int m, long long *rows, long long *cols) {
+  const long long q = (long long)c->n_q_heads * c->head_dim, kv = (long long)c->n_kv_heads * c->head_dim;
+  const long long d = c->d_model, f = c->d_ffn;
+  const long long R[7] = {q, kv, kv, d, f, f, d}, C[7] = {d, d, d, q, d, d, f};
+  *rows = R[m];
+  *cols = C[m];
+}
+static size_t qsz_matrix_bytes(const river_config *c, int m) {
+  long long rows, cols;
+  matrix_shape(c, m, &rows, &cols);
+  const long long gpr = (cols + c->river_group - 1) / c->river_group;
+  return (size_t)(rows * gpr) * (c->dtype == RIVER_BF16 ? 4 : 8);
 }
 
 static Layout make_layout(const river_config *c) {
@@ -193,12 +273,13 @@ static Layout make_layout(const river_config *c) {
   y.hidden = take((size_t)(c->n_layers + 1) * c->d_model * 4);
   y.qbuf = take((size_t)c->n_q_heads * c->head_dim * 4);
   y.obuf = take((size_t)c->n_q_heads * c->head_dim * 4);
+  y.kvcur = take((size_t)2 * kvd * 4);
   y.h1 = take((size_t)c->d_model * 4);
   y.abuf = take((size_t)c->d_ffn * 4);
   y.logits = take((size_t)c->vocab * 4);
   y.part_o = take((size_t)c->n_kv_heads * kMaxSplits * G * c->head_dim * 4);
-  y.part_ml = take((size_t)c->n_kv_heads * kMaxSplits * G * sizeof(float2));
-  y.cos_part = take((size_t)kMaxGrid * 3 * 4);
+  y.part_ml = take((size_t)c->n_kv_heads * kMaxSplits * G * 2 * 4);
+  y.cos_part = take((size_t)kMaxGrid * 4 * 4);
   y.amax_val = take((size_t)kMaxGrid * 4);
   y.amax_idx = take((size_t)kMaxGrid * 4);
   y.state = take(sizeof(DevState));
@@ -206,6 +287,11 @@ static Layout make_layout(const river_config *c) {
   y.rec_exit = take((size_t)kRecords * 4);
   y.rec_sims = take((size_t)kRecords * c->n_layers * 4);
   y.layers = take((size_t)c->n_layers * sizeof(DevLayer));
+  // packed (scale, zero) pairs of every river matrix of every block
+  y.qsz_bytes = 0;
+  for (int m = 0; m < 7; ++m) y.qsz_bytes += align_up(qsz_matrix_bytes(c, m), 256);
+  y.qsz_bytes *= (size_t)c->n_layers;
+  y.qsz = take(y.qsz_bytes);
   y.total = off;
   return y;
 }
@@ -292,6 +378,7 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
 
   // river twins: a block's twin is usable only if all its 21 pointers are given
   std::vector<DevLayer> hl(L);
+  std::vector<const void *> hqs((size_t)L * 7, nullptr), hqz((size_t)L * 7, nullptr);
   x->have_river = q != nullptr;
   for (int l = 0; l < L; ++l) {
     DevLayer &d = hl[l];
@@ -300,11 +387,11 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
     d.w[0] = w->wq[l]; d.w[1] = w->wk[l]; d.w[2] = w->wv[l]; d.w[3] = w->wo[l];
     d.w[4] = w->w_gate[l]; d.w[5] = w->w_up[l]; d.w[6] = w->w_down[l];
     for (int m = 0; m < 7; ++m) {
-      d.qc[m] = nullptr; d.qs[m] = nullptr; d.qz[m] = nullptr;
+      d.qc[m] = nullptr; d.qsz[m] = nullptr;
       if (q && q->codes[m] && q->scale[m] && q->zero[m]) {
         d.qc[m] = (const uint8_t *)q->codes[m][l];
-        d.qs[m] = q->scale[m][l];
-        d.qz[m] = q->zero[m][l];
+        hqs[(size_t)l * 7 + m] = q->scale[m][l];
+        hqz[(size_t)l * 7 + m] = q->zero[m][l];
         if (((uintptr_t)d.qc[m]) % 16) {
           g_create_err = "misaligned (16 B) river codes";
           delete x;
@@ -317,7 +404,7 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   if (q)
     for (int l = std::max(cfg->min_exit_layer, 0); l < L; ++l)
       for (int m = 0; m < 7; ++m)
-        if (!hl[l].qc[m] || !hl[l].qs[m] || !hl[l].qz[m]) {
+        if (!hl[l].qc[m] || !hqs[(size_t)l * 7 + m] || !hqz[(size_t)l * 7 + m]) {
           g_create_err = "river twin missing for a block above min_exit_layer";
           delete x;
           return RIVER_EINVAL;
@@ -331,9 +418,9 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
     return RIVER_EHIP;
   }
   const int cus = prop.multiProcessorCount;
-  x->grid_persist = std::min(cus, kMaxGrid);
-  x->grid_gemv = std::min(2 * cus, kMaxGrid);
-  if (const char *e = getenv("RIVER_GRID_PERSIST")) x->grid_persist = std::max(1, std::min(atoi(e), cus));
+  // one workgroup per CU, a multiple of 8 (the device-wide barrier counts in 8 groups)
+  x->grid_persist = std::max(8, std::min(cus, kMaxGrid) / 8 * 8);
+  x->grid_gemv = x->grid_persist;
 
   Dev &D = x->dev;
   D.L = L; D.d = cfg->d_model; D.nq = cfg->n_q_heads; D.nkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
@@ -349,9 +436,10 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   D.rope = (const float2 *)(ws + lay.rope);
   D.hidden = (float *)(ws + lay.hidden);
   D.qbuf = (float *)(ws + lay.qbuf); D.obuf = (float *)(ws + lay.obuf);
+  D.kvcur = (float *)(ws + lay.kvcur);
   D.h1 = (float *)(ws + lay.h1); D.abuf = (float *)(ws + lay.abuf);
   D.logits = (float *)(ws + lay.logits);
-  D.part_o = (float *)(ws + lay.part_o); D.part_ml = (float2 *)(ws + lay.part_ml);
+  D.part_o = (float *)(ws + lay.part_o); D.part_ml = (float *)(ws + lay.part_ml);
   D.cos_part = (float *)(ws + lay.cos_part);
   D.amax_val = (float *)(ws + lay.amax_val); D.amax_idx = (int *)(ws + lay.amax_idx);
   D.st = (DevState *)(ws + lay.state);
@@ -378,6 +466,25 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   if ((e = hipMemcpyAsync(ws + lay.rope, rope.data(), rope.size() * sizeof(float2),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("rope upload", e);
+  // pack (scale, zero) pairs of every river matrix that was given into the workspace
+  {
+    size_t off = lay.qsz;
+    for (int l = 0; l < L; ++l)
+      for (int m = 0; m < 7; ++m) {
+        const size_t bytes = qsz_matrix_bytes(cfg, m);
+        if (hl[l].qc[m] && hqs[(size_t)l * 7 + m] && hqz[(size_t)l * 7 + m]) {
+          const long long n = (long long)(bytes / (cfg->dtype == RIVER_BF16 ? 4 : 8));
+          const unsigned nb = (unsigned)((n + 255) / 256);
+          if (cfg->dtype == RIVER_BF16)
+            k_pack_sz<1><<<dim3(nb), dim3(256), 0, x->stream>>>(hqs[(size_t)l * 7 + m], hqz[(size_t)l * 7 + m], ws + off, n);
+          else
+            k_pack_sz<0><<<dim3(nb), dim3(256), 0, x->stream>>>(hqs[(size_t)l * 7 + m], hqz[(size_t)l * 7 + m], ws + off, n);
+          hl[l].qsz[m] = ws + off;
+        }
+        off += align_up(bytes, 256);
+      }
+    if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) packing", e);
+  }
   if ((e = hipMemcpyAsync(ws + lay.layers, hl.data(), hl.size() * sizeof(DevLayer),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("layer table upload", e);
@@ -388,7 +495,7 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
     return fail("cache clear", e);
   if ((e = hipStreamSynchronize(x->stream)) != hipSuccess) return fail("create sync", e);
 
-  if (x->lds_bytes > 48 * 1024) {
+  {
     const int lb = (int)x->lds_bytes;
     const void *fns[] = {
         (const void *)k_qkv<0>, (const void *)k_qkv<1>, (const void *)k_attn<0>, (const void *)k_attn<1>,
@@ -415,13 +522,12 @@ static int launch_step(river_ctx *x, const StepArgs &A0) {
   if (x->cfg.exec_mode == RIVER_EXEC_PERSISTENT) {
     A.bar_base = x->bar_total;
     k_step_persistent<DT><<<dim3(x->grid_persist), blk, lds, s>>>(D, A);
-    x->bar_total += (unsigned long long)x->grid_persist * (1 + 5ull * D.L);
+    x->bar_total += 5ull * D.L;
   } else {
     const dim3 gg(x->grid_gemv);
-    k_embed<DT><<<dim3(8), blk, 0, s>>>(D, A);
     for (int l = 0; l < D.L; ++l) {
       k_qkv<DT><<<gg, blk, lds, s>>>(D, A, l);
-      k_attn<DT><<<dim3(std::min(D.nkv * A.n_splits, kMaxGrid)), blk, lds, s>>>(D, A, l);
+      k_attn<DT><<<gg, blk, lds, s>>>(D, A, l);
       k_oproj<DT><<<gg, blk, lds, s>>>(D, A, l);
       k_gateup<DT><<<gg, blk, lds, s>>>(D, A, l);
       k_down<DT><<<gg, blk, lds, s>>>(D, A, l);
@@ -440,7 +546,13 @@ static int enqueue(river_ctx *x, int token, int forced_e, int want_head, int rec
   A.want_head = want_head;
   A.rec_slot = rec_slot;
   const int T = x->pos + 1;
-  A.n_splits = std::max(1, std::min(kMaxSplits, (T + kPosPerSplit - 1) / kPosPerSplit));
+  // one split per wavefront-load of positions per wave, as far as there are workgroups for it
+  const int es = x->cfg.dtype == RIVER_BF16 ? 2 : 4;
+  const int pos_per_split = kWaves * (64 / (x->cfg.head_dim * es / 16));
+  const int G = x->cfg.n_q_heads / x->cfg.n_kv_heads;
+  const int vheads = x->cfg.n_kv_heads * (G > 4 ? G / 4 : 1);
+  const int max_splits = std::max(1, std::min(kMaxSplits, x->grid_persist / vheads));
+  A.n_splits = std::max(1, std::min(max_splits, (T + pos_per_split - 1) / pos_per_split));
   A.bar_base = 0;
   const int rc = x->cfg.dtype == RIVER_BF16 ? launch_step<1>(x, A) : launch_step<0>(x, A);
   if (rc == RIVER_OK) x->pos += 1;
