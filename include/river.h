@@ -161,7 +161,11 @@ enum {
   RIVER_DBG_HIDDEN = 0, /* fp32 [n_layers+1][d_model]: h(0..L) of the last token processed */
   RIVER_DBG_LOGITS = 1, /* fp32 [vocab] of the last step that ran the head */
   RIVER_DBG_KCACHE = 2, /* cache dtype [n_layers][max_seq][n_kv_heads*head_dim] */
-  RIVER_DBG_VCACHE = 3
+  RIVER_DBG_VCACHE = 3,
+  RIVER_DBG_TRACE = 4   /* uint64 [5*n_layers][2][workgroups] then [64]: 100 MHz device clock at which each
+                           workgroup arrived at / was released from each device-wide barrier of the last
+                           launch, then 64 marks inside the phases (PERSISTENT mode of a library built
+                           with -DRIVER_TRACE; zeros otherwise); bytes = (5*n_layers*2*workgroups + 64)*8 */
 };
 /* Synchronises and copies a device buffer to dst (HOST, `bytes` must equal its size). */
 int river_get_debug(river_ctx *ctx, int32_t what, void *dst, size_t bytes);

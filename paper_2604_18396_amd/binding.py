@@ -17,7 +17,7 @@ from .configs import MATRICES, ModelConfig
 
 RIVER_OK, RIVER_EINVAL, RIVER_ENOSPC, RIVER_ESTATE, RIVER_EHIP = 0, -1, -2, -3, -4
 EXEC_KERNELS, EXEC_PERSISTENT = 0, 1
-DBG_HIDDEN, DBG_LOGITS, DBG_KCACHE, DBG_VCACHE = 0, 1, 2, 3
+DBG_HIDDEN, DBG_LOGITS, DBG_KCACHE, DBG_VCACHE, DBG_TRACE = 0, 1, 2, 3, 4
 
 EXPORTS = ("river_quantize_w4", "river_workspace_bytes", "river_create", "river_prefill",
            "river_decode_step", "river_read_records", "river_rewind", "river_position",
@@ -60,10 +60,11 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
-        raise ImportError(f"{_build.LIB} is missing: build it first "
+    path = os.environ.get("RIVER_LIB_PATH", _build.LIB)      # e.g. the diagnostics build
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it first "
                           "(python -c 'import __graft_entry__ as g; g.build()')")
-    L = C.CDLL(_build.LIB)
+    L = C.CDLL(path)
     L.river_quantize_w4.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.river_workspace_bytes.argtypes = [C.POINTER(river_config)]
@@ -238,6 +239,14 @@ class River:
 
     def vcache(self) -> np.ndarray:
         return self._cache(DBG_VCACHE)
+
+    def trace(self, workgroups: int) -> np.ndarray:
+        """[5L, 2, workgroups] barrier arrive/release device times (diagnostics build only)."""
+        n = 5 * self.cfg.n_layers * 2 * workgroups
+        out = np.empty(n + 64, dtype=np.uint64)
+        self._check(load().river_get_debug(self._h, DBG_TRACE, out.ctypes.data, out.nbytes))
+        self.marks = out[n:].astype(np.int64)
+        return out[:n].reshape(5 * self.cfg.n_layers, 2, workgroups)
 
     def fill_cache(self, byte: int):
         self._check(load().river_fill_cache(self._h, byte))

@@ -23,13 +23,19 @@ def is_stale() -> bool:
             or any(os.path.getmtime(LIB) < os.path.getmtime(d) for d in DEPS))
 
 
-def build(force: bool = True) -> str:
-    if not force and not is_stale():
+TRACE_LIB = os.path.join(HERE, "libriver_trace.so")
+
+
+def build(force: bool = True, trace: bool = False) -> str:
+    """trace=True builds the diagnostics variant (per-barrier device timestamps)."""
+    out = TRACE_LIB if trace else LIB
+    if not force and not trace and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIB, SRC]
+    cmd = [hipcc, *HIPCC_FLAGS, *(["-DRIVER_TRACE"] if trace else []),
+           "-I", os.path.join(ROOT, "include"), "-o", out, SRC]
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

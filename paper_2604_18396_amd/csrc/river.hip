@@ -17,6 +17,9 @@
 using namespace river;
 
 // ------------------------------------------------------------------ kernels
+//
+// All kernels take the device descriptor by pointer (it lives in the workspace and is read
+// with scalar loads) and the per-step arguments by value.
 
 // One-kernel-per-phase mode.  The exit state travels between the kernels of a token in
 // DevState: the QKV kernel of block l derives it (every workgroup identically), workgroup 0
@@ -29,8 +32,9 @@ __device__ __forceinline__ Ctl load_ctl(const Dev &D, int l) {
 }
 
 template <int DT>
-__global__ __launch_bounds__(kBlock) void k_qkv(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_qkv(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
+  const Dev &D = *Dp;
   Ctl ctl;
   if (l == 0) {
     ctl = ctl_init(D, A);
@@ -48,87 +52,143 @@ __global__ __launch_bounds__(kBlock) void k_qkv(Dev D, StepArgs A, int l) {
   phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ __launch_bounds__(kBlock) void k_attn(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_attn(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
-  phase_attn<DT>(D, A, l, lds);
+  phase_attn<DT>(*Dp, A, l, lds, [] {}, [] {});
 }
 template <int DT>
-__global__ __launch_bounds__(kBlock) void k_oproj(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_oproj(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
+  const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, l);
   Regs<DT> pre;
   prefetch_phase<DT>(D, l, PH_O, ctl.river, pre);
   phase_oproj<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ __launch_bounds__(kBlock) void k_gateup(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_gateup(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
+  const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, l);
   Regs<DT> pre;
   prefetch_phase<DT>(D, l, PH_GU, ctl.river, pre);
   phase_gateup<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ __launch_bounds__(kBlock) void k_down(Dev D, StepArgs A, int l) {
+__global__ __launch_bounds__(kBlock) void k_down(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
+  const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, l);
   Regs<DT> pre;
   prefetch_phase<DT>(D, l, PH_DOWN, ctl.river, pre);
   phase_down<DT>(D, A, l, ctl.river, lds, pre);
 }
 template <int DT>
-__global__ __launch_bounds__(kBlock) void k_head(Dev D, StepArgs A) {
+__global__ __launch_bounds__(kBlock) void k_head(const Dev *Dp, StepArgs A) {
   extern __shared__ float lds[];
+  const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, D.L - 1);
   Regs<DT> pre;
   prefetch_head<DT>(D, pre);
   phase_head<DT>(D, A, ctl, lds, pre);
 }
 
-// One launch per token: all phases in order, device-wide barriers in between; the first
-// step of each phase's weights is issued between arriving at and waiting on the barrier
-// before it.  The number of barriers (5 L) is the same for every workgroup whatever the
-// exit state.
+#ifdef RIVER_TRACE
+// diagnostics build: every workgroup stamps the 100 MHz wall clock when it arrives at and
+// when it is released from each device-wide barrier of the last launch
+#define TRACE_ARRIVE() if (threadIdx.x == 0) D.trace[((k - A.bar_base - 1) * 2 + 0) * gridDim.x + blockIdx.x] = wall_clock64()
+#define TRACE_RELEASE() if (threadIdx.x == 0) D.trace[((k - A.bar_base - 1) * 2 + 1) * gridDim.x + blockIdx.x] = wall_clock64()
+#else
+#define TRACE_ARRIVE()
+#define TRACE_RELEASE()
+#endif
+
+// Persistent mode: one launch per token.  Each phase is a separate (not inlined) function
+// with its own register allocation.  The device-wide barrier that PRECEDES a phase is
+// executed inside that phase's function, and the phase's first weight loads are issued
+// between arriving at and waiting on it, so they are in flight while the workgroups
+// synchronise.  k is the index of that barrier (0: none, first phase of the launch).
+#ifndef RIVER_PSTEP_INLINE
+#define RIVER_PSTEP_INLINE __forceinline__
+#endif
+__device__ __forceinline__ int pack_ctl(const Ctl &c) { return (c.exit_pos << 1) | (c.river ? 1 : 0); }
+__device__ __forceinline__ Ctl unpack_ctl(int v) { Ctl c; c.river = v & 1; c.exit_pos = v >> 1; return c; }
+
 template <int DT>
-__global__ __launch_bounds__(kBlock) void k_step_persistent(Dev D, StepArgs A) {
-  extern __shared__ float lds[];
-  unsigned long long k = A.bar_base;
-  Ctl ctl = ctl_init(D, A);
-  record_init(D, A);
+__device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, int ctl_packed,
+                                      unsigned long long k, float *lds) {
+  const Dev &D = *Dp;
+  Ctl ctl = unpack_ctl(ctl_packed);
   Regs<DT> pre;
-  bool pre_river = ctl.river;
-  prefetch_phase<DT>(D, 0, PH_QKV, pre_river, pre);
-  for (int l = 0; l < D.L; ++l) {
-    if (l > 0) {
-      exit_test(D, A, l, ctl, lds);
-      if (ctl.river != pre_river) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
-    }
-    phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
-    barrier_arrive(D.st, ++k);
-    barrier_wait(D.st, k, D.spin_limit);
-    phase_attn<DT>(D, A, l, lds);
-    barrier_arrive(D.st, ++k);
-    prefetch_phase<DT>(D, l, PH_O, ctl.river, pre);
-    barrier_wait(D.st, k, D.spin_limit);
-    phase_oproj<DT>(D, A, l, ctl.river, lds, pre);
-    barrier_arrive(D.st, ++k);
-    prefetch_phase<DT>(D, l, PH_GU, ctl.river, pre);
-    barrier_wait(D.st, k, D.spin_limit);
-    phase_gateup<DT>(D, A, l, ctl.river, lds, pre);
-    barrier_arrive(D.st, ++k);
-    prefetch_phase<DT>(D, l, PH_DOWN, ctl.river, pre);
-    barrier_wait(D.st, k, D.spin_limit);
-    phase_down<DT>(D, A, l, ctl.river, lds, pre);
-    barrier_arrive(D.st, ++k);
-    if (l + 1 < D.L) {
-      pre_river = guess_river_after(A, ctl, l + 1);
-      prefetch_phase<DT>(D, l + 1, PH_QKV, pre_river, pre);
-    } else if (A.want_head) {
-      prefetch_head<DT>(D, pre);
-    }
-    barrier_wait(D.st, k, D.spin_limit);
+  // block l (1-based) has just run: what will block l + 1 run as, as far as known now
+  const bool guess = (l == 0) ? ctl.river : guess_river_after(A, ctl, l);
+  // (Every wavefront prefetches before the wait, the polling one too: its polls then queue
+  // behind its own loads, ~1 us, but issuing its share late costs the phase ~2.5 us.)
+  const bool poller = false;
+  if (l > 0) { barrier_arrive(D.st, k); TRACE_ARRIVE(); }
+  if (!poller) prefetch_phase<DT>(D, l, PH_QKV, guess, pre);
+  if (l > 0) {
+    barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+    if (poller) prefetch_phase<DT>(D, l, PH_QKV, guess, pre);
+    exit_test(D, A, l, ctl, lds);
+    if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
   }
-  if (A.want_head) phase_head<DT>(D, A, ctl, lds, pre);
+  phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
+  return pack_ctl(ctl);
+}
+template <int DT>
+__device__ RIVER_PSTEP_INLINE void pstep_attn(const Dev *Dp, StepArgs A, int l, unsigned long long k, float *lds) {
+  const Dev &D = *Dp;
+  phase_attn<DT>(D, A, l, lds, [&] { barrier_arrive(D.st, k); TRACE_ARRIVE(); },
+                 [&] { barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE(); });
+}
+template <int DT, int PH>
+__device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, bool river, unsigned long long k,
+                                        float *lds) {
+  const Dev &D = *Dp;
+  Regs<DT> pre;
+  const bool poller = false;                   // see pstep_qkv
+  barrier_arrive(D.st, k); TRACE_ARRIVE();
+  if (!poller) prefetch_phase<DT>(D, l, PH, river, pre);
+  barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+  if (poller) prefetch_phase<DT>(D, l, PH, river, pre);
+  if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre);
+  else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre);
+  else phase_down<DT>(D, A, l, river, lds, pre);
+}
+template <int DT>
+__device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl_packed, unsigned long long k,
+                                        float *lds) {
+  const Dev &D = *Dp;
+  const Ctl ctl = unpack_ctl(ctl_packed);
+  Regs<DT> pre;
+  const bool poller = false;                   // see pstep_qkv
+  barrier_arrive(D.st, k); TRACE_ARRIVE();
+  if (!poller) prefetch_head<DT>(D, pre);
+  barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+  if (poller) prefetch_head<DT>(D, pre);
+  phase_head<DT>(D, A, ctl, lds, pre);
+}
+
+// The number of barriers (5 L - 1, one more with the head) is the same for every workgroup
+// whatever the exit state.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void k_step_persistent(const Dev *Dp, StepArgs A) {
+  extern __shared__ float lds[];
+  const Dev &D = *Dp;
+  unsigned long long k = A.bar_base;
+  const int L = D.L;
+  record_init(D, A);
+  int ctl = pack_ctl(ctl_init(D, A));
+  for (int l = 0; l < L; ++l) {
+    ctl = pstep_qkv<DT>(Dp, A, l, ctl, l ? ++k : 0, lds);
+    const bool river = ctl & 1;
+    pstep_attn<DT>(Dp, A, l, ++k, lds);
+    pstep_gemv<DT, PH_O>(Dp, A, l, river, ++k, lds);
+    pstep_gemv<DT, PH_GU>(Dp, A, l, river, ++k, lds);
+    pstep_gemv<DT, PH_DOWN>(Dp, A, l, river, ++k, lds);
+  }
+  if (A.want_head) pstep_head<DT>(Dp, A, ctl, ++k, lds);
 }
 
 // Interleaves the river's scale and zero arrays into one (scale, zero) pair per group,
@@ -184,13 +244,14 @@ __global__ void k_fill_bytes(uint4 *p, size_t n16, uint32_t word) {
 
 struct Layout {
   size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part,
-      amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, qsz, total;
+      amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
 };
 
 struct river_ctx {
   river_config cfg;
-  Dev dev;
+  Dev dev;              // host copy of the descriptor
+  const Dev *dev_d;     // the same in the workspace
   Layout lay;
   char *ws;
   hipStream_t stream;
@@ -224,7 +285,7 @@ static bool valid_cfg(const river_config *c, std::string *why) {
   if (G != 1 && G != 2 && G % 4) return bad("query heads per kv head must be 1, 2 or a multiple of 4");
   if (c->n_kv_heads * (G > 4 ? G / 4 : 1) > kMaxKvHeads) return bad("too many kv heads");
   const int hd = c->head_dim;
-  if (hd < 32 || hd > 256 || (hd & (hd - 1))) return bad("head_dim must be a power of two in [32, 256]");
+  if (hd != 64 && hd != 128) return bad("head_dim must be 64 or 128");
   if (c->d_model % 16 || c->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
   if (c->vocab % 2) return bad("vocab must be even");
   if (c->min_exit_layer < 0 || c->min_exit_layer > c->n_layers) return bad("min_exit_layer out of range");
@@ -240,7 +301,7 @@ static int x_capacity(const river_config *c) {
   int cap = c->d_model;
   cap = std::max(cap, c->n_q_heads * c->head_dim);
   cap = std::max(cap, c->d_ffn);
-  cap = std::max(cap, kWaves * std::min(G, 4) * (c->head_dim + 2));
+  cap = std::max(cap, attn_lds_floats(c->head_dim, std::min(G, 4)));
   return (int)align_up(cap, 4);
 }
 
@@ -278,7 +339,7 @@ static Layout make_layout(const river_config *c) {
   y.abuf = take((size_t)c->d_ffn * 4);
   y.logits = take((size_t)c->vocab * 4);
   y.part_o = take((size_t)c->n_kv_heads * kMaxSplits * G * c->head_dim * 4);
-  y.part_ml = take((size_t)c->n_kv_heads * kMaxSplits * G * 2 * 4);
+  y.part_ml = take((size_t)c->n_kv_heads * kMaxSplits * G * 4 * 4);
   y.cos_part = take((size_t)kMaxGrid * 4 * 4);
   y.amax_val = take((size_t)kMaxGrid * 4);
   y.amax_idx = take((size_t)kMaxGrid * 4);
@@ -287,6 +348,8 @@ static Layout make_layout(const river_config *c) {
   y.rec_exit = take((size_t)kRecords * 4);
   y.rec_sims = take((size_t)kRecords * c->n_layers * 4);
   y.layers = take((size_t)c->n_layers * sizeof(DevLayer));
+  y.dev = take(sizeof(Dev));
+  y.trace = take(((size_t)5 * c->n_layers * 2 * kMaxGrid + 64) * 8);
   // packed (scale, zero) pairs of every river matrix of every block
   y.qsz_bytes = 0;
   for (int m = 0; m < 7; ++m) y.qsz_bytes += align_up(qsz_matrix_bytes(c, m), 256);
@@ -445,6 +508,7 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   D.st = (DevState *)(ws + lay.state);
   D.rec_token = (int *)(ws + lay.rec_token); D.rec_exit = (int *)(ws + lay.rec_exit);
   D.rec_sims = (float *)(ws + lay.rec_sims);
+  D.trace = (unsigned long long *)(ws + lay.trace);
   x->lds_bytes = ((size_t)D.xcap + 64) * sizeof(float);
 
   // RoPE table in double precision: angle = pos * base^(-2i/hd)
@@ -466,6 +530,9 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   if ((e = hipMemcpyAsync(ws + lay.rope, rope.data(), rope.size() * sizeof(float2),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("rope upload", e);
+  x->dev_d = (const Dev *)(ws + lay.dev);
+  if ((e = hipMemcpyAsync(ws + lay.dev, &x->dev, sizeof(Dev), hipMemcpyHostToDevice, x->stream)) != hipSuccess)
+    return fail("descriptor upload", e);
   // pack (scale, zero) pairs of every river matrix that was given into the workspace
   {
     size_t off = lay.qsz;
@@ -516,23 +583,24 @@ template <int DT>
 static int launch_step(river_ctx *x, const StepArgs &A0) {
   StepArgs A = A0;
   const Dev &D = x->dev;
+  const Dev *Dp = x->dev_d;
   const dim3 blk(x->block);
   const size_t lds = x->lds_bytes;
   hipStream_t s = x->stream;
   if (x->cfg.exec_mode == RIVER_EXEC_PERSISTENT) {
     A.bar_base = x->bar_total;
-    k_step_persistent<DT><<<dim3(x->grid_persist), blk, lds, s>>>(D, A);
-    x->bar_total += 5ull * D.L;
+    k_step_persistent<DT><<<dim3(x->grid_persist), blk, lds, s>>>(Dp, A);
+    x->bar_total += 5ull * D.L - 1 + (A.want_head ? 1 : 0);
   } else {
     const dim3 gg(x->grid_gemv);
     for (int l = 0; l < D.L; ++l) {
-      k_qkv<DT><<<gg, blk, lds, s>>>(D, A, l);
-      k_attn<DT><<<gg, blk, lds, s>>>(D, A, l);
-      k_oproj<DT><<<gg, blk, lds, s>>>(D, A, l);
-      k_gateup<DT><<<gg, blk, lds, s>>>(D, A, l);
-      k_down<DT><<<gg, blk, lds, s>>>(D, A, l);
+      k_qkv<DT><<<gg, blk, lds, s>>>(Dp, A, l);
+      k_attn<DT><<<gg, blk, lds, s>>>(Dp, A, l);
+      k_oproj<DT><<<gg, blk, lds, s>>>(Dp, A, l);
+      k_gateup<DT><<<gg, blk, lds, s>>>(Dp, A, l);
+      k_down<DT><<<gg, blk, lds, s>>>(Dp, A, l);
     }
-    if (A.want_head) k_head<DT><<<gg, blk, lds, s>>>(D, A);
+    if (A.want_head) k_head<DT><<<gg, blk, lds, s>>>(Dp, A);
   }
   HIP_TRY(x, hipGetLastError());
   return RIVER_OK;
@@ -547,8 +615,7 @@ static int enqueue(river_ctx *x, int token, int forced_e, int want_head, int rec
   A.rec_slot = rec_slot;
   const int T = x->pos + 1;
   // one split per wavefront-load of positions per wave, as far as there are workgroups for it
-  const int es = x->cfg.dtype == RIVER_BF16 ? 2 : 4;
-  const int pos_per_split = kWaves * (64 / (x->cfg.head_dim * es / 16));
+  const int pos_per_split = kAttnPosPerSplit;
   const int G = x->cfg.n_q_heads / x->cfg.n_kv_heads;
   const int vheads = x->cfg.n_kv_heads * (G > 4 ? G / 4 : 1);
   const int max_splits = std::max(1, std::min(kMaxSplits, x->grid_persist / vheads));
@@ -685,6 +752,7 @@ extern "C" int river_get_debug(river_ctx *x, int32_t what, void *dst, size_t byt
     case RIVER_DBG_LOGITS: src = (const char *)x->dev.logits; n = (size_t)x->cfg.vocab * 4; break;
     case RIVER_DBG_KCACHE: src = (const char *)x->dev.kcache; n = x->lay.cache_bytes; break;
     case RIVER_DBG_VCACHE: src = (const char *)x->dev.vcache; n = x->lay.cache_bytes; break;
+    case RIVER_DBG_TRACE: src = (const char *)x->dev.trace; n = ((size_t)5 * x->cfg.n_layers * 2 * x->grid_persist + 64) * 8; break;
     default: x->err = "unknown debug buffer"; return RIVER_EINVAL;
   }
   if (bytes != n) { x->err = "debug buffer size mismatch"; return RIVER_EINVAL; }

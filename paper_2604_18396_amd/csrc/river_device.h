@@ -69,13 +69,14 @@ struct Dev {
   float *abuf;                    // [ffn]
   float *logits;                  // [vocab]
   float *part_o;                  // [nkv][kMaxSplits][G][hd] unnormalised partial outputs
-  float *part_ml;                 // [nkv][kMaxSplits][G][2] (running max, sum)
+  float *part_ml;                 // [nkv][kMaxSplits][G][4] (running max, sum, -, -)
   float *cos_part;                // [kMaxGrid][4]
   float *amax_val;                // [kMaxGrid]
   int *amax_idx;                  // [kMaxGrid]
   DevState *st;
   int *rec_token, *rec_exit;      // [kRecords]
   float *rec_sims;                // [kRecords][L]
+  unsigned long long *trace;      // [5L][2][grid] barrier arrive / release times (RIVER_TRACE builds)
 };
 
 struct StepArgs {
@@ -119,6 +120,9 @@ template <> struct Store<0> {
     f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
     f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
   }
+  static __device__ __forceinline__ uint4 repack(const float (&f)[4]) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+  }
   static __device__ __forceinline__ SZ ldsz(const void *p, size_t i) {
     return make_float2(RIVER_GLOBAL(float, p)[2 * i], RIVER_GLOBAL(float, p)[2 * i + 1]);
   }
@@ -147,6 +151,13 @@ template <> struct Store<1> {
     f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
     f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
     f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xffff0000u);
+  }
+  // exact for values that are already bf16-representable
+  static __device__ __forceinline__ uint4 repack(const float (&f)[8]) {
+    return make_uint4((__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xffff0000u),
+                      (__float_as_uint(f[2]) >> 16) | (__float_as_uint(f[3]) & 0xffff0000u),
+                      (__float_as_uint(f[4]) >> 16) | (__float_as_uint(f[5]) & 0xffff0000u),
+                      (__float_as_uint(f[6]) >> 16) | (__float_as_uint(f[7]) & 0xffff0000u));
   }
   static __device__ __forceinline__ SZ ldsz(const void *p, size_t i) { return RIVER_GLOBAL(uint32_t, p)[i]; }
   static __device__ __forceinline__ SZ pack(float s, float z) {
@@ -655,6 +666,24 @@ __device__ __forceinline__ void run_phase(const Dev &D, int l, int ph, bool rive
   }
 }
 
+// diagnostics build: workgroup 0 stamps the 100 MHz wall clock at marked points of the
+// last block's phases (after the barrier stamps in Dev::trace)
+#ifdef RIVER_TRACE
+#define RIVER_MARK(D, id)                                                                    \
+  do {                                                                                        \
+    if (blockIdx.x == 0 && threadIdx.x == 0)                                                  \
+      (D).trace[(size_t)5 * (D).L * 2 * gridDim.x + (id)] = wall_clock64();                   \
+  } while (0)
+#define RIVER_MARK_SYNC(D, id)                                                               \
+  do {                                                                                        \
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                               \
+    RIVER_MARK(D, id);                                                                        \
+  } while (0)
+#else
+#define RIVER_MARK(D, id)
+#define RIVER_MARK_SYNC(D, id)
+#endif
+
 // ------------------------------------------------------------------ phases
 
 // Eq. 1 for block l1 = l (1-based) from the sums the down-projection phase of that block
@@ -736,155 +765,318 @@ __device__ __forceinline__ void phase_qkv(const Dev &D, const StepArgs &A, int l
   run_phase<DT>(D, l, PH_QKV, river, lds, pre, epi);
 }
 
-// a3: split-K GQA decode attention.  A workgroup owns (kv head, split): its wavefronts
-// stream that split's K and V rows once (16 bytes per lane, hd/EPL lanes per position)
-// and serve all G query heads of the group from registers, with an online softmax per
-// lane group.  Partials (max, sum, unnormalised output) are merged in a fixed order:
-// lane groups, wavefronts (through LDS), then splits (by the last workgroup of the kv
-// head to arrive), so the result is independent of timing.  The current position's K/V
-// come from the exchange buffer; older positions from the cache.
-template <int DT, int G>
-__device__ __forceinline__ void attn_items(const Dev &D, const StepArgs &A, int l, float *lds) {
-  constexpr int EPL = Store<DT>::EPL;
-  const int hd = D.hd, LPP = hd / EPL, PPW = 64 / LPP;
+// Sum over the 16 lanes of a DPP row; every lane gets the result.  DPP lane permutations
+// only (no LDS pipe traffic): two quad permutes, then the mirrors of a half row and of a
+// row, which after the previous steps hold the other half's sum.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v = dpp_add<0xB1>(v);      // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E>(v);      // quad_perm [2,3,0,1]
+  v = dpp_add<0x141>(v);     // row_half_mirror
+  v = dpp_add<0x140>(v);     // row_mirror
+  return v;
+}
+
+// a3: split-K GQA decode attention.  A workgroup owns (kv head, split).  Sixteen lanes
+// share a cached position (EL = hd/16 elements each), so a wavefront load covers 4
+// positions; kAttnRounds such loads of K and of V per lane are in flight at once, and the
+// first chunk is issued BEFORE the device-wide barrier in front of the phase (old cache rows
+// do not depend on this block's QKV).  All G query heads of the group are served from
+// registers.  Each lane group keeps an online softmax (base 2, the scores carry log2 e)
+// over its positions, rescaled once per chunk; the 4 x 8 lane groups of the workgroup then
+// meet in LDS and are merged in a fixed order, then the splits are merged by the last
+// workgroup of the head to arrive (partials fetched in batches of independent loads), so
+// the result is independent of timing.  With one split the workgroup writes the output
+// itself.  The current position's K/V come from the exchange buffer.
+constexpr int kAttnRounds = 4;
+constexpr int kAttnPosPerSplit = kWaves * 4 * kAttnRounds;   // positions one workgroup covers per chunk
+constexpr int kCombine = 8;
+constexpr float kNegBig = -1.0e30f;   // "no position yet": finite, so differences never give NaN
+
+// LDS floats of the merge area: per (wavefront, lane group) entry G*hd outputs and G*2
+// (max, sum).
+__host__ __device__ inline int attn_lds_floats(int hd, int g) { return kWaves * 4 * g * (hd + 2); }
+
+template <int DT, int EL> struct KV {                  // raw cache words of one lane: EL elements
+  static constexpr int NW = EL * (int)sizeof(typename Store<DT>::T) / 4;
+  uint32_t w[NW];
+  __device__ __forceinline__ void load(const char *p) {
+    if constexpr (NW == 2) {
+      const u32x2 v = *RIVER_GLOBAL(u32x2, p);
+      w[0] = v.x; w[1] = v.y;
+    } else {
+#pragma unroll
+      for (int i = 0; i < NW; i += 4) {
+        const u32x4 v = *RIVER_GLOBAL(u32x4, p + i * 4);
+        w[i] = v.x; w[i + 1] = v.y; w[i + 2] = v.z; w[i + 3] = v.w;
+      }
+    }
+  }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < NW; ++i) w[i] = 0;
+  }
+  __device__ __forceinline__ void unpack(float (&f)[EL]) const {
+    if constexpr (DT == 1) {
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        f[2 * i] = __uint_as_float(w[i] << 16);
+        f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NW; ++i) f[i] = __uint_as_float(w[i]);
+    }
+  }
+};
+
+template <int DT, int EL> struct KVChunk { KV<DT, EL> k[kAttnRounds], v[kAttnRounds]; };
+
+// Geometry of the item (virtual head, split) a workgroup serves.
+struct AttnItem { int vh, kvh, sp, p0, p1; };
+template <int G>
+__device__ __forceinline__ AttnItem attn_item(const Dev &D, const StepArgs &A, int item) {
   const int S = A.n_splits, T = A.pos + 1;
   const int chunk = (T + S - 1) / S;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  const int slot = lane / LPP, dl = lane % LPP;
+  const int npass = (D.nq / D.nkv) / G;
+  AttnItem it;
+  it.vh = item / S; it.sp = item % S;
+  it.kvh = it.vh / npass;
+  it.p0 = it.sp * chunk; it.p1 = min(T, it.p0 + chunk);
+  return it;
+}
+
+// Issue the loads of one chunk: positions pb + u*32 + slot for u < kAttnRounds (pb already
+// includes this wavefront's offset).  The current position is never read from the cache.
+template <int DT, int EL>
+__device__ __forceinline__ void attn_load_chunk(const Dev &D, const StepArgs &A, int l, const AttnItem &it,
+                                                int pb, KVChunk<DT, EL> &c) {
+  const int lane = threadIdx.x & 63, slot = lane >> 4, dl = lane & 15;
+  const int kvd = D.nkv * D.hd;
+  const size_t es = sizeof(typename Store<DT>::T);
+  const size_t base = ((size_t)l * D.max_seq * kvd + (size_t)it.kvh * D.hd + dl * EL) * es;
+#pragma unroll
+  for (int u = 0; u < kAttnRounds; ++u) {
+    const int p = pb + u * (kWaves * 4) + slot;
+    if (p < it.p1 && p != A.pos) {
+      const size_t off = base + (size_t)p * kvd * es;
+      c.k[u].load((const char *)D.kcache + off);
+      c.v[u].load((const char *)D.vcache + off);
+    } else {
+      c.k[u].zero();
+      c.v[u].zero();
+    }
+  }
+}
+
+// First chunk of the first item of this workgroup (if it has one).
+template <int DT, int G, int EL>
+__device__ __forceinline__ void attn_prefetch(const Dev &D, const StepArgs &A, int l, KVChunk<DT, EL> &c) {
+  const int npass = (D.nq / D.nkv) / G;
+  if ((int)blockIdx.x < D.nkv * npass * A.n_splits) {
+    const AttnItem it = attn_item<G>(D, A, blockIdx.x);
+    attn_load_chunk<DT, EL>(D, A, l, it, it.p0 + wave_in_wg() * 4, c);
+  }
+}
+
+template <int DT, int G, int EL>
+__device__ __forceinline__ void attn_items(const Dev &D, const StepArgs &A, int l, float *lds,
+                                           KVChunk<DT, EL> &cur) {
+  constexpr int RU = kAttnRounds;
+  constexpr int NENT = kWaves * 4;                   // lane groups per workgroup
+  const int hd = D.hd;                               // == 16 * EL
+  const int S = A.n_splits;
+  const int lane = threadIdx.x & 63, wv = wave_in_wg();
+  const int slot = lane >> 4, dl = lane & 15;
   const int kvd = D.nkv * hd;
-  const float inv = 1.0f / sqrtf((float)hd);
-  const float NEG = -INFINITY;
-  float *mo = lds;                          // merge area: per wavefront G * (hd + 2) floats
+  const float qs = 1.4426950408889634f / sqrtf((float)hd);    // log2(e) / sqrt(hd)
+  float *mo_o = lds;                                 // [NENT][G][hd]
+  float *mo_ml = lds + (size_t)NENT * G * hd;        // [NENT][G][2]
   // A kv head with more than 4 query heads is served as several "virtual" kv heads of G
   // query heads each (they stream the same K/V rows again).
   const int npass = (D.nq / D.nkv) / G;
   for (int item = blockIdx.x; item < D.nkv * npass * S; item += gridDim.x) {
-    const int vh = item / S, sp = item % S;   // virtual head: query heads vh*G .. vh*G+G-1
-    const int kvh = vh / npass;
-    const int p0 = sp * chunk, p1 = min(T, p0 + chunk);
-    float q[G][EPL], o[G][EPL], m[G], ls[G];
+    const AttnItem it = attn_item<G>(D, A, item);
+    int pb = it.p0 + wv * 4;
+    if (item != (int)blockIdx.x) attn_load_chunk<DT, EL>(D, A, l, it, pb, cur);   // not prefetched
+    RIVER_MARK(D, 0);
+    float q[G][EL], o[G][EL], m[G], ls[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      m[g] = NEG; ls[g] = 0.f;
+      m[g] = kNegBig; ls[g] = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; e += 4) {
-        const float4 t = sub4(D.qbuf, (vh * G + g) * hd + dl * EPL + e);
-        q[g][e] = t.x * inv; q[g][e + 1] = t.y * inv; q[g][e + 2] = t.z * inv; q[g][e + 3] = t.w * inv;
+      for (int e = 0; e < EL; e += 4) {
+        const float4 t = sub4(D.qbuf, (it.vh * G + g) * hd + dl * EL + e);
+        q[g][e] = t.x * qs; q[g][e + 1] = t.y * qs; q[g][e + 2] = t.z * qs; q[g][e + 3] = t.w * qs;
       }
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[g][e] = 0.f;
+      for (int e = 0; e < EL; ++e) o[g][e] = 0.f;
     }
-    const size_t es = sizeof(typename Store<DT>::T);
-    const char *Kb = (const char *)D.kcache + ((size_t)l * D.max_seq * kvd + (size_t)kvh * hd + dl * EPL) * es;
-    const char *Vb = (const char *)D.vcache + ((size_t)l * D.max_seq * kvd + (size_t)kvh * hd + dl * EPL) * es;
-    for (int pb = p0 + wv * PPW; pb < p1; pb += nw * PPW) {
-      const int p = pb + slot;
-      const bool ok = p < p1;
-      float kf[EPL], vf[EPL];
-      if (ok && p == A.pos) {
+    RIVER_MARK_SYNC(D, 5);
+    for (; pb < it.p1; pb += NENT * RU) {
+      // position by position: scores of the G heads, online softmax update, weighted V.
+      // This token's own K/V replaces the cache row of the current position.
 #pragma unroll
-        for (int e = 0; e < EPL; e += 4) {
-          const float4 tk = sub4(D.kvcur, kvh * hd + dl * EPL + e);
-          const float4 tv = sub4(D.kvcur, kvd + kvh * hd + dl * EPL + e);
-          kf[e] = tk.x; kf[e + 1] = tk.y; kf[e + 2] = tk.z; kf[e + 3] = tk.w;
-          vf[e] = tv.x; vf[e + 1] = tv.y; vf[e + 2] = tv.z; vf[e + 3] = tv.w;
+      for (int u = 0; u < RU; ++u) {
+        const int p = pb + u * NENT + slot;
+        const bool ok = p < it.p1, own = p == A.pos;
+        float kf[EL];
+        cur.k[u].unpack(kf);
+        if (own) {
+#pragma unroll
+          for (int e = 0; e < EL; e += 4) {
+            const float4 t = sub4(D.kvcur, it.kvh * hd + dl * EL + e);
+            kf[e] = t.x; kf[e + 1] = t.y; kf[e + 2] = t.z; kf[e + 3] = t.w;
+          }
         }
-      } else {
-        const size_t off = (size_t)(ok ? p : p0) * kvd * es;
-        const u32x4 kx = *RIVER_GLOBAL(u32x4, Kb + off), vx = *RIVER_GLOBAL(u32x4, Vb + off);
-        const uint4 kw = make_uint4(kx.x, kx.y, kx.z, kx.w), vw = make_uint4(vx.x, vx.y, vx.z, vx.w);
-        Store<DT>::unpack(kw, kf);
-        Store<DT>::unpack(vw, vf);
-      }
+        float cg[G], pg[G];
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float sc = 0.f;
+        for (int g = 0; g < G; ++g) {
+          float d = 0.f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) sc = fmaf(q[g][e], kf[e], sc);
-        for (int s = 1; s < LPP; s <<= 1) sc += __shfl_xor(sc, s);
-        if (ok) {
+          for (int e = 0; e < EL; ++e) d = fmaf(q[g][e], kf[e], d);
+          d = row16_sum(d);
+          const float sc = ok ? d : kNegBig;
           const float mn = fmaxf(m[g], sc);
-          const float corr = expf(m[g] - mn);       // exp(-inf) = 0 on the first position
-          const float pe = expf(sc - mn);
-          ls[g] = ls[g] * corr + pe;
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) o[g][e] = o[g][e] * corr + pe * vf[e];
+          cg[g] = __builtin_amdgcn_exp2f(m[g] - mn);              // <= 1; 1 while nothing seen
+          pg[g] = ok ? __builtin_amdgcn_exp2f(sc - mn) : 0.f;
+          ls[g] = fmaf(ls[g], cg[g], pg[g]);
           m[g] = mn;
         }
-      }
-    }
-    // merge the lane groups of this wavefront (fixed xor order); slot 0 ends with the total
-    for (int s = LPP; s < 64; s <<= 1) {
+        float vf[EL];
+        cur.v[u].unpack(vf);
+        if (own) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float m2 = __shfl_xor(m[g], s), l2 = __shfl_xor(ls[g], s);
-        const float mn = fmaxf(m[g], m2);
-        const float c1 = (m[g] == NEG) ? 0.f : expf(m[g] - mn);
-        const float c2 = (m2 == NEG) ? 0.f : expf(m2 - mn);
-        ls[g] = ls[g] * c1 + l2 * c2;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          const float o2 = __shfl_xor(o[g][e], s);
-          o[g][e] = o[g][e] * c1 + o2 * c2;
+          for (int e = 0; e < EL; e += 4) {
+            const float4 t = sub4(D.kvcur, kvd + it.kvh * hd + dl * EL + e);
+            vf[e] = t.x; vf[e + 1] = t.y; vf[e + 2] = t.z; vf[e + 3] = t.w;
+          }
         }
-        m[g] = mn;
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int e = 0; e < EL; ++e) o[g][e] = fmaf(o[g][e], cg[g], pg[g] * vf[e]);
+        // keep the positions apart: interleaving all of them costs > 100 more registers
+        __builtin_amdgcn_sched_barrier(0);
       }
+      if (pb + NENT * RU < it.p1) attn_load_chunk<DT, EL>(D, A, l, it, pb + NENT * RU, cur);
     }
-    lds_barrier();                      // merge area free (previous item fully consumed)
-    if (slot == 0) {
+    RIVER_MARK(D, 1);
+    lds_barrier();                        // merge area free (previous item fully consumed)
+    {
+      const int en = wv * 4 + slot;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float *w = mo + ((size_t)wv * G + g) * (hd + 2);
+        float *w = mo_o + ((size_t)en * G + g) * hd + dl * EL;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) w[2 + dl * EPL + e] = o[g][e];
-        if (dl == 0) { w[0] = m[g]; w[1] = ls[g]; }
+        for (int e = 0; e < EL; e += 4) *(float4 *)(w + e) = make_float4(o[g][e], o[g][e + 1], o[g][e + 2], o[g][e + 3]);
+        if (dl == 0) *(float2 *)(mo_ml + ((size_t)en * G + g) * 2) = make_float2(m[g], ls[g]);
       }
     }
+    RIVER_MARK(D, 2);
     lds_barrier();
-    // wavefronts -> one partial per (kv head, split, g), fixed order
+    RIVER_MARK(D, 3);
+    // lane groups of all wavefronts -> one partial per (head, split, g), fixed order
     for (int idx = threadIdx.x; idx < G * hd; idx += blockDim.x) {
       const int g = idx / hd, e = idx % hd;
-      float M = NEG;
-      for (int w = 0; w < nw; ++w) M = fmaxf(M, mo[((size_t)w * G + g) * (hd + 2)]);
-      float Lsum = 0.f, O = 0.f;
-      for (int w = 0; w < nw; ++w) {
-        const float *src = mo + ((size_t)w * G + g) * (hd + 2);
-        const float c = (src[0] == NEG) ? 0.f : expf(src[0] - M);
-        Lsum += src[1] * c;
-        O += src[2 + e] * c;
-      }
-      const size_t pi = ((size_t)vh * kMaxSplits + sp) * G + g;
-      pub(D.part_o + pi * hd + e, O);
-      if (e == 0) { pub(D.part_ml + pi * 2, M); pub(D.part_ml + pi * 2 + 1, Lsum); }
-    }
-    // splits -> final output, by whichever workgroup of this kv head finishes last
-    if (last_arriver(&D.st->attn_cnt[vh], (unsigned)S, lds_flag(D, lds))) {
-      for (int idx = threadIdx.x; idx < G * hd; idx += blockDim.x) {
-        const int g = idx / hd, e = idx % hd;
-        const size_t p_base = ((size_t)vh * kMaxSplits) * G + g;
-        float M = NEG;
-        for (int s2 = 0; s2 < S; ++s2) M = fmaxf(M, sub(D.part_ml + (p_base + (size_t)s2 * G) * 2));
-        float Lsum = 0.f, O = 0.f;
-        for (int s2 = 0; s2 < S; ++s2) {
-          const size_t pi = p_base + (size_t)s2 * G;
-          const float pm = sub(D.part_ml + pi * 2), pl = sub(D.part_ml + pi * 2 + 1);
-          const float c = (pm == NEG) ? 0.f : expf(pm - M);
-          Lsum += pl * c;
-          O += sub(D.part_o + pi * hd + e) * c;
+      float M = kNegBig, Lsum = 0.f, O = 0.f;
+#pragma unroll
+      for (int e0 = 0; e0 < NENT; e0 += 8) {                        // batches of 8 entries, running max
+        float2 ml[8];
+        float ov[8];
+        float mb = M;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          ml[j] = *(const float2 *)(mo_ml + ((size_t)(e0 + j) * G + g) * 2);
+          ov[j] = mo_o[((size_t)(e0 + j) * G + g) * hd + e];
+          mb = fmaxf(mb, ml[j].x);
         }
-        pub(D.obuf + (vh * G + g) * hd + e, O / Lsum);
+        const float cb = __builtin_amdgcn_exp2f(M - mb);
+        Lsum *= cb; O *= cb;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float c = __builtin_amdgcn_exp2f(ml[j].x - mb);     // entries that saw nothing have sum 0
+          Lsum = fmaf(ml[j].y, c, Lsum);
+          O = fmaf(ov[j], c, O);
+        }
+        M = mb;
+      }
+      if (S == 1) {
+        pub(D.obuf + (it.vh * G + g) * hd + e, O / Lsum);
+      } else {
+        const size_t pi = ((size_t)it.vh * kMaxSplits + it.sp) * G + g;
+        pub(D.part_o + pi * hd + e, O);
+        if (e == 0) { pub(D.part_ml + pi * 4, M); pub(D.part_ml + pi * 4 + 1, Lsum); }
+      }
+    }
+    RIVER_MARK(D, 4);
+    // splits -> final output, by whichever workgroup of this head finishes last
+    if (S > 1 && last_arriver(&D.st->attn_cnt[it.vh], (unsigned)S, lds_flag(D, lds))) {
+      for (int idx = threadIdx.x; idx < G * (hd >> 2); idx += blockDim.x) {
+        const int g = idx / (hd >> 2), e4 = (idx % (hd >> 2)) * 4;
+        const size_t p_base = ((size_t)it.vh * kMaxSplits) * G + g;
+        float M = kNegBig, Lsum = 0.f;
+        float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < S; s0 += kCombine) {
+          float4 ml[kCombine], po[kCombine];
+#pragma unroll
+          for (int j = 0; j < kCombine; ++j) {
+            const size_t pi = p_base + (size_t)min(s0 + j, S - 1) * G;
+            ml[j] = sub4(D.part_ml, (int)(pi * 4));
+            po[j] = sub4(D.part_o, (int)(pi * hd + e4));
+          }
+#pragma unroll
+          for (int j = 0; j < kCombine; ++j) {
+            const bool use = s0 + j < S;
+            const float pm = use ? ml[j].x : kNegBig;
+            const float mn = fmaxf(M, pm);
+            const float c1 = __builtin_amdgcn_exp2f(M - mn);
+            const float c2 = use ? __builtin_amdgcn_exp2f(pm - mn) : 0.f;
+            Lsum = Lsum * c1 + ml[j].y * c2;
+            O.x = O.x * c1 + po[j].x * c2; O.y = O.y * c1 + po[j].y * c2;
+            O.z = O.z * c1 + po[j].z * c2; O.w = O.w * c1 + po[j].w * c2;
+            M = mn;
+          }
+        }
+        float *dst = D.obuf + (it.vh * G + g) * hd + e4;
+        pub(dst, O.x / Lsum); pub(dst + 1, O.y / Lsum); pub(dst + 2, O.z / Lsum); pub(dst + 3, O.w / Lsum);
       }
     }
   }
 }
 
-template <int DT>
-__device__ __forceinline__ void phase_attn(const Dev &D, const StepArgs &A, int l, float *lds) {
-  switch (D.nq / D.nkv) {
-    case 1: attn_items<DT, 1>(D, A, l, lds); break;
-    case 2: attn_items<DT, 2>(D, A, l, lds); break;
-    default: attn_items<DT, 4>(D, A, l, lds); break;   // 4, or a multiple of 4 in passes
+// Dispatch on the two shape parameters that size register arrays: query heads per kv head
+// (1, 2, or multiples of 4 in passes of 4) and elements per lane (head_dim 64 or 128).
+// f is called as f(integral_constant G, integral_constant EL).
+template <int V> struct IC { static constexpr int value = V; };
+template <class F>
+__device__ __forceinline__ void attn_dispatch(const Dev &D, F f) {
+  const int gq = D.nq / D.nkv;
+  if (D.hd == 128) {
+    if (gq == 1) f(IC<1>(), IC<8>()); else if (gq == 2) f(IC<2>(), IC<8>()); else f(IC<4>(), IC<8>());
+  } else {
+    if (gq == 1) f(IC<1>(), IC<4>()); else if (gq == 2) f(IC<2>(), IC<4>()); else f(IC<4>(), IC<4>());
   }
+}
+
+// The attention phase with the device-wide barrier in front of it (k == 0: none, the
+// one-kernel-per-phase mode): the first K/V chunk is issued between arriving and waiting.
+template <int DT, class Arrive, class Wait>
+__device__ __forceinline__ void phase_attn(const Dev &D, const StepArgs &A, int l, float *lds,
+                                           Arrive arrive, Wait wait) {
+  attn_dispatch(D, [&](auto g, auto el) {
+    constexpr int G = decltype(g)::value, EL = decltype(el)::value;
+    KVChunk<DT, EL> c;
+    const bool poller = false;
+    arrive();
+    if (!poller) attn_prefetch<DT, G, EL>(D, A, l, c);
+    wait();
+    if (poller) attn_prefetch<DT, G, EL>(D, A, l, c);
+    attn_items<DT, G, EL>(D, A, l, lds, c);
+  });
 }
 
 // a4: h1 = h + W_o o

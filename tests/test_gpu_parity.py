@@ -255,6 +255,20 @@ def test_mid_shape_ragged_tiles(mode, cfg):
     pair.close()
 
 
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
+def test_long_context_many_splits(mode, cfg0):
+    """Attention over 1100+ cached positions: 9 splits, combined in two batches."""
+    say(f"long context {cfg0.name} mode={mode}")
+    cfg = cfg0.with_(max_seq=1200, tau=0.675)
+    w = inputs.make_weights(cfg, configs.C1.seed_weights)
+    pair = Pair(cfg, w, mode)
+    prompt = inputs.make_prompt(cfg.vocab, 1100, 91)
+    run_teacher_forced(pair, prompt, 6, label="long")
+    pair.compare_cache(1106)
+    pair.close()
+
+
 # ------------------------------------------------------------ API behaviour
 
 def test_async_steps_and_records_match_sync():
