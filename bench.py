@@ -135,9 +135,12 @@ def main():
     gbs = float(np.mean(bytes_river)) / (ms_river * 1e-3 / K) / 1e9
     gbs_dense = float(np.mean(bytes_dense)) / (ms_dense * 1e-3 / K) / 1e9
 
-    traffic = None
+    # HBM bytes per launch from the rocprofv3 counter runs recorded beside the package
+    traffic, traffic_detail = None, None
     if os.path.exists(MEASURED):
-        traffic = json.load(open(MEASURED)).get(f"{args.workload}:{args.mode}")
+        traffic_detail = json.load(open(MEASURED)).get(f"{args.workload}:{args.mode}")
+        if traffic_detail:
+            traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]
 
     out = {
         "metric": "decode tokens/s @batch1 (8B shape) w/ early exit; HBM GB/s as % of peak",
@@ -151,7 +154,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "k_step_persistent<1>" if args.mode == "persistent" else "all step kernels",
-                     "algorithmic_bytes_per_launch": float(np.mean(bytes_river))},
+                     "algorithmic_bytes_per_launch": float(np.mean(bytes_river)),
+                     "traffic_detail": traffic_detail},
         "dense": {"value": tok_s_dense, "unit": "tokens/s", "ms_per_step": ms_dense / K,
                   "achieved_GBps": gbs_dense, "frac": gbs_dense / HBM_PEAK_GBS},
         "speedup_vs_dense": tok_s / tok_s_dense,

@@ -1,0 +1,95 @@
+"""Parity at the benchmark's full shapes, in the launch configuration bench.py times
+(persistent mode, one workgroup per CU), on samples the oracle can compute:
+
+ * the whole 8B-shape model (32 blocks, 128256-row head) with a short prompt and a forced
+   exit schedule that covers backbone-only, river-mostly and mixed tokens;
+ * two 8B-shape blocks over a 520-token prompt: the attention phase at the benchmark's
+   context length (5 splits, cross-workgroup combine), with exits at both depths;
+ * the whole 1B-shape model with a 64-token prompt.
+
+The oracle needs about a second per 8B-shape token on 16 cores, which bounds the samples."""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from oracle import river_oracle as ro
+from paper_2604_18396_amd import binding, configs, inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def relerr(a, b):
+    return float(np.abs(np.asarray(a, np.float64) - b).max() / max(np.abs(b).max(), 1e-30))
+
+
+def run(cfg, seed, prompt, sched, label):
+    t0 = time.time()
+    w = inputs.make_weights(cfg, seed)
+    say(f"{label}: weights {time.time() - t0:.1f}s")
+    t0 = time.time()
+    o = ro.Oracle(cfg, w, ro.quantize_river(cfg, w))
+    dw = binding.upload_weights(w)
+    dr = binding.quantize_river(cfg, dw)
+    g = binding.River(cfg, dw, dr, exec_mode=binding.EXEC_PERSISTENT)
+    say(f"{label}: river built on both sides {time.time() - t0:.1f}s")
+    # the two quantisers must agree bit for bit on the real matrices too
+    for l in (0, cfg.n_layers - 1):
+        for m in ("wq", "w_down"):
+            co = o._keep[1][l][m][0]
+            assert bool((dr[l][m][0].cpu() == co).all()), f"river codes differ, block {l + 1} {m}"
+    t0 = time.time()
+    tok = o.prefill(prompt)
+    say(f"{label}: oracle prefill of {len(prompt)} tokens {time.time() - t0:.1f}s")
+    assert g.prefill(prompt) == tok
+    worst_h, worst_l = 0.0, 0.0
+    for i, e in enumerate(sched):
+        t0 = time.time()
+        to, eo, so = o.decode_step(tok, e)
+        tg, eg, sg = g.decode_step(tok, e)
+        assert eg == eo == e
+        ho, hg = o.hidden(), g.hidden()
+        eh = max(relerr(hg[l], ho[l]) for l in range(cfg.n_layers + 1))
+        el = relerr(g.logits(), o.logits())
+        worst_h, worst_l = max(worst_h, eh), max(worst_l, el)
+        say(f"{label}: step {i} exit {e}: hidden {eh:.2e} logits {el:.2e} ({time.time() - t0:.1f}s)")
+        assert eh <= TOL and el <= TOL
+        np.testing.assert_allclose(sg[:e], so[:e], atol=2e-4)
+        if tg != to:
+            lo = o.logits()
+            assert (lo[to] - lo[tg]) / np.abs(lo).max() <= TOL
+        tok = to
+    n = len(prompt) + len(sched)
+    for name, a, b in (("K", g.kcache(), o.kcache()), ("V", g.vcache(), o.vcache())):
+        for l in range(cfg.n_layers):
+            assert relerr(a[l, :n], b[l, :n]) <= TOL, f"{name} cache block {l + 1}"
+    g.close()
+    o.close()
+    return worst_h, worst_l
+
+
+def test_8b_shape_whole_model_sampled():
+    cfg = configs.LLAMA_8B.with_(max_seq=32)
+    prompt = inputs.make_prompt(cfg.vocab, 6, configs.C3.seed_prompt)
+    sched = [32, 8, 20, 13, 31]
+    run(cfg, configs.C3.seed_weights, prompt, sched, "8B")
+
+
+def test_8b_shape_blocks_at_benchmark_context():
+    cfg = configs.LLAMA_8B.with_(name="8b-2-blocks", n_layers=2, min_exit_layer=1, max_seq=544)
+    prompt = inputs.make_prompt(cfg.vocab, 520, configs.C3.seed_prompt)
+    run(cfg, configs.C3.seed_weights, prompt, [1, 2, 1, 2], "8B-ctx520")
+
+
+def test_1b_shape_whole_model():
+    cfg = configs.LLAMA_1B.with_(max_seq=96)
+    prompt = inputs.make_prompt(cfg.vocab, 64, configs.C2.seed_prompt)
+    sched = inputs.make_exit_schedule(cfg.n_layers, 8, configs.C2.seed_exits)
+    run(cfg, configs.C2.seed_weights, prompt, [int(e) for e in sched], "1B")
