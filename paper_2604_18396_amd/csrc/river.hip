@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kBlock) void k_qkv(const Dev *Dp, StepArgs A, int l
     D.st->slot_river[l & 1] = ctl.river;
     D.st->slot_exit[l & 1] = ctl.exit_pos;
   }
-  Regs<DT> pre;
+  Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);
   phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
 }
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kBlock) void k_oproj(const Dev *Dp, StepArgs A, int
   extern __shared__ float lds[];
   const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, l);
-  Regs<DT> pre;
+  Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_O, ctl.river, pre);
   phase_oproj<DT>(D, A, l, ctl.river, lds, pre);
 }
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kBlock) void k_gateup(const Dev *Dp, StepArgs A, in
   extern __shared__ float lds[];
   const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, l);
-  Regs<DT> pre;
+  Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_GU, ctl.river, pre);
   phase_gateup<DT>(D, A, l, ctl.river, lds, pre);
 }
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kBlock) void k_down(const Dev *Dp, StepArgs A, int 
   extern __shared__ float lds[];
   const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, l);
-  Regs<DT> pre;
+  Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_DOWN, ctl.river, pre);
   phase_down<DT>(D, A, l, ctl.river, lds, pre);
 }
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kBlock) void k_head(const Dev *Dp, StepArgs A) {
   extern __shared__ float lds[];
   const Dev &D = *Dp;
   const Ctl ctl = load_ctl(D, D.L - 1);
-  Regs<DT> pre;
+  Pre<DT> pre;
   prefetch_head<DT>(D, pre);
   phase_head<DT>(D, A, ctl, lds, pre);
 }
@@ -119,17 +119,17 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
                                       unsigned long long k, float *lds) {
   const Dev &D = *Dp;
   Ctl ctl = unpack_ctl(ctl_packed);
-  Regs<DT> pre;
+  Pre<DT> pre;
   // block l (1-based) has just run: what will block l + 1 run as, as far as known now
   const bool guess = (l == 0) ? ctl.river : guess_river_after(A, ctl, l);
-  // (Every wavefront prefetches before the wait, the polling one too: its polls then queue
-  // behind its own loads, ~1 us, but issuing its share late costs the phase ~2.5 us.)
-  const bool poller = false;
+  // Loads return in order, so the polls of the wavefront that polls the barrier queue behind
+  // its own prefetch: it issues only the first element before the wait, the second after.
+  const bool poller = wave_in_wg() == 0 && l > 0;
   if (l > 0) { barrier_arrive(D.st, k); TRACE_ARRIVE(); }
-  if (!poller) prefetch_phase<DT>(D, l, PH_QKV, guess, pre);
+  prefetch_phase<DT>(D, l, PH_QKV, guess, pre, poller ? 1 : 3);
   if (l > 0) {
     barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
-    if (poller) prefetch_phase<DT>(D, l, PH_QKV, guess, pre);
+    if (poller) prefetch_phase<DT>(D, l, PH_QKV, guess, pre, 2);
     exit_test(D, A, l, ctl, lds);
     if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
   }
@@ -146,12 +146,12 @@ template <int DT, int PH>
 __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, bool river, unsigned long long k,
                                         float *lds) {
   const Dev &D = *Dp;
-  Regs<DT> pre;
-  const bool poller = false;                   // see pstep_qkv
+  Pre<DT> pre;
+  const bool poller = wave_in_wg() == 0;       // see pstep_qkv
   barrier_arrive(D.st, k); TRACE_ARRIVE();
-  if (!poller) prefetch_phase<DT>(D, l, PH, river, pre);
+  prefetch_phase<DT>(D, l, PH, river, pre, poller ? 1 : 3);
   barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
-  if (poller) prefetch_phase<DT>(D, l, PH, river, pre);
+  if (poller) prefetch_phase<DT>(D, l, PH, river, pre, 2);
   if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre);
   else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre);
   else phase_down<DT>(D, A, l, river, lds, pre);
@@ -161,12 +161,12 @@ __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl
                                         float *lds) {
   const Dev &D = *Dp;
   const Ctl ctl = unpack_ctl(ctl_packed);
-  Regs<DT> pre;
-  const bool poller = false;                   // see pstep_qkv
+  Pre<DT> pre;
+  const bool poller = wave_in_wg() == 0;       // see pstep_qkv
   barrier_arrive(D.st, k); TRACE_ARRIVE();
-  if (!poller) prefetch_head<DT>(D, pre);
+  prefetch_head<DT>(D, pre, poller ? 1 : 3);
   barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
-  if (poller) prefetch_head<DT>(D, pre);
+  if (poller) prefetch_head<DT>(D, pre, 2);
   phase_head<DT>(D, A, ctl, lds, pre);
 }
 

@@ -499,46 +499,61 @@ template <int DT, int R, int CPL> struct W4 {
   }
 };
 
-// Runs all tasks of this wavefront (task ids wave_id(), + wave_count(), ...) of one GEMV
-// phase.  `cur` must already hold step 0 of the first task (issued by the caller, possibly
-// before the preceding barrier).  rows_of(task, Rows&) gives the rows of a task; epi(task,
-// acc) receives the R finished dot products (identical in all lanes).
+// The two register sets of the streaming pipeline.  The (task, step) pairs of a wavefront
+// form one sequence j = 0, 1, 2, ...: task wave_id() + (j / NS) * wave_count(), step j % NS.
+// Set a holds an even j, set b the following odd j; while one is consumed the other is in
+// flight, and both can be issued before the barrier in front of the phase.
+template <int DT> struct Pre {
+  Regs<DT> a, b;
+};
+
+// Issue element j of this wavefront's sequence into g (nothing if the sequence is shorter).
+template <class F, int DT, int R, class RowsOf>
+__device__ __forceinline__ void issue_seq(int j, int n_tasks, int cols, int group, Regs<DT> &g,
+                                          RowsOf rows_of) {
+  const int NS = F::steps(cols);
+  const int t = wave_id() + (j / NS) * wave_count();
+  if (t < n_tasks) {
+    Rows<R> rw;
+    rows_of(t, rw);
+    F::issue(g, rw, cols, group, j % NS);
+  }
+}
+
+// Runs all tasks of this wavefront of one GEMV phase.  pre.a / pre.b must already hold
+// elements 0 and 1 of the sequence (issued by the caller, possibly before the preceding
+// barrier).  rows_of(task, Rows&) gives the rows of a task; epi(task, acc) receives the R
+// finished dot products (identical in all lanes).
 template <class F, int DT, int R, class RowsOf, class Epi>
 __device__ __forceinline__ void stream_tasks(int n_tasks, int cols, int group, const float *xl,
-                                             Regs<DT> &cur, RowsOf rows_of, Epi epi) {
-  const int nw = wave_count();
-  int t = wave_id();
-  if (t >= n_tasks) return;
+                                             Pre<DT> &pre, RowsOf rows_of, Epi epi) {
+  const int nw = wave_count(), w = wave_id();
+  if (w >= n_tasks) return;
   const int NS = F::steps(cols);
-  Rows<R> rw;
-  rows_of(t, rw);
-  int s = 0;
+  const int J = ((n_tasks - w + nw - 1) / nw) * NS;      // length of this wavefront's sequence
   float acc[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0.f;
-  while (true) {
-    int s2 = s + 1, t2 = t;
-    if (s2 == NS) { s2 = 0; t2 = t + nw; }
-    const bool more = t2 < n_tasks;
-    Regs<DT> nxt;
-    Rows<R> rw2 = rw;
-    if (more) {
-      if (t2 != t) rows_of(t2, rw2);
-      F::issue(nxt, rw2, cols, group, s2);
-    }
-    F::fma(cur, cols, group, s, xl, acc);
-    if (s == NS - 1) {
+  int s = 0, t = w;                                       // step and task being consumed
+  auto consume = [&](Regs<DT> &g) {
+    F::fma(g, cols, group, s, xl, acc);
+    if (++s == NS) {
 #pragma unroll
       for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
       epi(t, acc);
 #pragma unroll
       for (int r = 0; r < R; ++r) acc[r] = 0.f;
+      s = 0;
+      t += nw;
     }
-    if (!more) break;
-    cur = nxt;
-    rw = rw2;
-    t = t2;
-    s = s2;
+  };
+  for (int j = 0; j < J; j += 2) {
+    consume(pre.a);
+    if (j + 2 < J) issue_seq<F, DT, R>(j + 2, n_tasks, cols, group, pre.a, rows_of);
+    if (j + 1 < J) {
+      consume(pre.b);
+      if (j + 3 < J) issue_seq<F, DT, R>(j + 3, n_tasks, cols, group, pre.b, rows_of);
+    }
   }
 }
 
@@ -620,24 +635,27 @@ __device__ __forceinline__ void phase_rows(const Dev &D, const DevLayer &Lw, int
   set_rows<DT, R>(rw, Lw, river, m, row, cols, D.group);
 }
 
-// Issue step 0 of this wavefront's first task of phase `ph` of block l (dense or river).
+// Issue the first two elements of this wavefront's sequence of phase `ph` of block l (dense
+// or river).  `which`: bit 0 = element 0 into g.a, bit 1 = element 1 into g.b.
 template <int DT>
-__device__ __forceinline__ void prefetch_phase(const Dev &D, int l, int ph, bool river, Regs<DT> &g) {
+__device__ __forceinline__ void prefetch_phase(const Dev &D, int l, int ph, bool river, Pre<DT> &g,
+                                               int which = 3) {
   const DevLayer &Lw = D.layers[l];
   const int cols = phase_cols(D, ph);
-  const int t = wave_id();
   if (!river) {
-    if (t < phase_tasks<kRD>(D, ph)) {
-      Rows<kRD> rw;
-      phase_rows<DT, kRD>(D, Lw, ph, false, t, rw);
-      Dense<DT, kRD>::issue(g, rw, cols, D.group, 0);
-    }
+    auto rows_of = [&](int t, Rows<kRD> &rw) { phase_rows<DT, kRD>(D, Lw, ph, false, t, rw); };
+    const int n = phase_tasks<kRD>(D, ph);
+    if (which & 1) issue_seq<Dense<DT, kRD>, DT, kRD>(0, n, cols, D.group, g.a, rows_of);
+    if (which & 2) issue_seq<Dense<DT, kRD>, DT, kRD>(1, n, cols, D.group, g.b, rows_of);
   } else {
-    if (t < phase_tasks<kRQ>(D, ph)) {
-      Rows<kRQ> rw;
-      phase_rows<DT, kRQ>(D, Lw, ph, true, t, rw);
-      if ((cols & 31) == 0) W4<DT, kRQ, 32>::issue(g, rw, cols, D.group, 0);
-      else W4<DT, kRQ, 16>::issue(g, rw, cols, D.group, 0);
+    auto rows_of = [&](int t, Rows<kRQ> &rw) { phase_rows<DT, kRQ>(D, Lw, ph, true, t, rw); };
+    const int n = phase_tasks<kRQ>(D, ph);
+    if ((cols & 31) == 0) {
+      if (which & 1) issue_seq<W4<DT, kRQ, 32>, DT, kRQ>(0, n, cols, D.group, g.a, rows_of);
+      if (which & 2) issue_seq<W4<DT, kRQ, 32>, DT, kRQ>(1, n, cols, D.group, g.b, rows_of);
+    } else {
+      if (which & 1) issue_seq<W4<DT, kRQ, 16>, DT, kRQ>(0, n, cols, D.group, g.a, rows_of);
+      if (which & 2) issue_seq<W4<DT, kRQ, 16>, DT, kRQ>(1, n, cols, D.group, g.b, rows_of);
     }
   }
 }
@@ -646,7 +664,7 @@ __device__ __forceinline__ void prefetch_phase(const Dev &D, int l, int ph, bool
 // is called for every pair of rows of a task (lane-uniform values).
 template <int DT, class Epi>
 __device__ __forceinline__ void run_phase(const Dev &D, int l, int ph, bool river, const float *xl,
-                                          Regs<DT> &pre, Epi epi) {
+                                          Pre<DT> &pre, Epi epi) {
   const DevLayer &Lw = D.layers[l];
   const int cols = phase_cols(D, ph);
   if (!river) {
@@ -727,7 +745,7 @@ __device__ __forceinline__ bool guess_river_after(const StepArgs &A, const Ctl &
 // the same slot for backbone and river ("identical KV Cache addressing scheme").  A task
 // owns rotation pairs (rows i and i + hd/2 of a head), so the rotation needs no exchange.
 template <int DT>
-__device__ __forceinline__ void phase_qkv(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Regs<DT> &pre) {
+__device__ __forceinline__ void phase_qkv(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   const DevLayer &Lw = D.layers[l];
   if (l == 0) {
     int tok = A.token >= 0 ? A.token : D.st->cur_token;
@@ -1081,7 +1099,7 @@ __device__ __forceinline__ void phase_attn(const Dev &D, const StepArgs &A, int 
 
 // a4: h1 = h + W_o o
 template <int DT>
-__device__ __forceinline__ void phase_oproj(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Regs<DT> &pre) {
+__device__ __forceinline__ void phase_oproj(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   stage_copy(D.obuf, D.nq * D.hd, lds);
   const float *hin = D.hidden + (size_t)l * D.d;
   const int lane = threadIdx.x & 63;
@@ -1096,7 +1114,7 @@ __device__ __forceinline__ void phase_oproj(const Dev &D, const StepArgs &A, int
 
 // a5: y = RMSNorm(h1) * g2; a = silu(W_g y) * (W_u y)
 template <int DT>
-__device__ __forceinline__ void phase_gateup(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Regs<DT> &pre) {
+__device__ __forceinline__ void phase_gateup(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   stage_norm<DT>(D.h1, D.layers[l].ffn_norm, D.d, D.eps, lds, lds_red(D, lds));
   const int lane = threadIdx.x & 63;
   auto epi = [&](int r, float g, float u) {
@@ -1110,7 +1128,7 @@ __device__ __forceinline__ void phase_gateup(const Dev &D, const StepArgs &A, in
 // reduction over workgroups and the exit decision are taken by every workgroup at the
 // start of the next block (exit_test), so no workgroup waits for another here.
 template <int DT>
-__device__ __forceinline__ void phase_down(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Regs<DT> &pre) {
+__device__ __forceinline__ void phase_down(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   stage_copy(D.abuf, D.ffn, lds);
   const float *hin = D.hidden + (size_t)l * D.d;
   float *hout = D.hidden + (size_t)(l + 1) * D.d;
@@ -1148,16 +1166,14 @@ __device__ __forceinline__ void head_rows(const Dev &D, int t, Rows<kRD> &rw) {
   }
 }
 template <int DT>
-__device__ __forceinline__ void prefetch_head(const Dev &D, Regs<DT> &g) {
-  const int t = wave_id();
-  if (t < (D.vocab + kRD - 1) / kRD) {
-    Rows<kRD> rw;
-    head_rows<DT>(D, t, rw);
-    Dense<DT, kRD>::issue(g, rw, D.d, D.group, 0);
-  }
+__device__ __forceinline__ void prefetch_head(const Dev &D, Pre<DT> &g, int which = 3) {
+  auto rows_of = [&](int t, Rows<kRD> &rw) { head_rows<DT>(D, t, rw); };
+  const int n = (D.vocab + kRD - 1) / kRD;
+  if (which & 1) issue_seq<Dense<DT, kRD>, DT, kRD>(0, n, D.d, D.group, g.a, rows_of);
+  if (which & 2) issue_seq<Dense<DT, kRD>, DT, kRD>(1, n, D.d, D.group, g.b, rows_of);
 }
 template <int DT>
-__device__ __forceinline__ void phase_head(const Dev &D, const StepArgs &A, const Ctl &ctl, float *lds, Regs<DT> &pre) {
+__device__ __forceinline__ void phase_head(const Dev &D, const StepArgs &A, const Ctl &ctl, float *lds, Pre<DT> &pre) {
   float *red = lds_red(D, lds);
   if (!ctl.river && A.rec_slot >= 0) {      // similarity of the last backbone block: recorded, never tested
     const float s = similarity_from_partials(D, red);
