@@ -51,7 +51,8 @@ enum { RIVER_F32 = 0, RIVER_BF16 = 1 };
 /* How one decode step is issued.  Both run the same device code.
  * KERNELS: one launch per phase (6 + 5 per block), no cross-workgroup waiting.
  * PERSISTENT: one launch per token; workgroups meet at device-wide barriers
- * whose waits are bounded by spin_limit. */
+ * whose waits are bounded by spin_limit.  Offered for RIVER_BF16 only:
+ * river_create and river_workspace_bytes refuse it for RIVER_F32. */
 enum { RIVER_EXEC_KERNELS = 0, RIVER_EXEC_PERSISTENT = 1 };
 
 typedef struct {

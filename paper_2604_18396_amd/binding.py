@@ -87,7 +87,14 @@ def load():
     return L
 
 
-def make_config(cfg: ModelConfig, exec_mode: int = EXEC_PERSISTENT, spin_limit: int = 0) -> river_config:
+def default_exec_mode(cfg: ModelConfig) -> int:
+    """One launch per token where the library offers it (bf16), else one launch per phase."""
+    return EXEC_PERSISTENT if cfg.dtype == 1 else EXEC_KERNELS
+
+
+def make_config(cfg: ModelConfig, exec_mode: int | None = None, spin_limit: int = 0) -> river_config:
+    if exec_mode is None:
+        exec_mode = default_exec_mode(cfg)
     return river_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
                         cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps, cfg.dtype, 1, cfg.max_seq,
                         cfg.min_exit_layer, cfg.tau, 4, cfg.river_group, exec_mode, spin_limit)
@@ -130,7 +137,7 @@ class River:
     """One decode context (river_create .. river_destroy)."""
 
     def __init__(self, cfg: ModelConfig, dev_weights: dict, dev_river: list | None,
-                 exec_mode: int = EXEC_PERSISTENT, spin_limit: int = 0):
+                 exec_mode: int | None = None, spin_limit: int = 0):
         L = load()
         self.cfg = cfg
         self._c = make_config(cfg, exec_mode, spin_limit)
@@ -254,7 +261,7 @@ class River:
 
 # The C entry points under their own names (the class above is the same calls with
 # the context kept in an object).
-def river_create(cfg, dev_weights, dev_river, exec_mode=EXEC_PERSISTENT, spin_limit=0) -> River:
+def river_create(cfg, dev_weights, dev_river, exec_mode=None, spin_limit=0) -> River:
     return River(cfg, dev_weights, dev_river, exec_mode, spin_limit)
 
 

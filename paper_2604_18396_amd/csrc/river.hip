@@ -24,7 +24,7 @@ using namespace river;
 // One-kernel-per-phase mode.  The exit state travels between the kernels of a token in
 // DevState: the QKV kernel of block l derives it (every workgroup identically), workgroup 0
 // stores it in slot l & 1, the other kernels of the block read that slot.
-__device__ __forceinline__ Ctl load_ctl(const Dev &D, int l) {
+__device__ __forceinline__ Ctl load_ctl(DevRef D, int l) {
   Ctl c;
   c.river = D.st->slot_river[l & 1] != 0;
   c.exit_pos = D.st->slot_exit[l & 1];
@@ -34,7 +34,7 @@ __device__ __forceinline__ Ctl load_ctl(const Dev &D, int l) {
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_qkv(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   Ctl ctl;
   if (l == 0) {
     ctl = ctl_init(D, A);
@@ -54,12 +54,12 @@ __global__ __launch_bounds__(kBlock) void k_qkv(const Dev *Dp, StepArgs A, int l
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_attn(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
-  phase_attn<DT>(*Dp, A, l, lds, [] {}, [] {});
+  phase_attn<DT>(*RIVER_CONSTANT(Dev, Dp), A, l, lds, [] {}, [] {});
 }
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_oproj(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   const Ctl ctl = load_ctl(D, l);
   Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_O, ctl.river, pre);
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kBlock) void k_oproj(const Dev *Dp, StepArgs A, int
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_gateup(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   const Ctl ctl = load_ctl(D, l);
   Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_GU, ctl.river, pre);
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kBlock) void k_gateup(const Dev *Dp, StepArgs A, in
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_down(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   const Ctl ctl = load_ctl(D, l);
   Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_DOWN, ctl.river, pre);
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kBlock) void k_down(const Dev *Dp, StepArgs A, int 
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_head(const Dev *Dp, StepArgs A) {
   extern __shared__ float lds[];
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   const Ctl ctl = load_ctl(D, D.L - 1);
   Pre<DT> pre;
   prefetch_head<DT>(D, pre);
@@ -117,19 +117,15 @@ __device__ __forceinline__ Ctl unpack_ctl(int v) { Ctl c; c.river = v & 1; c.exi
 template <int DT>
 __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, int ctl_packed,
                                       unsigned long long k, float *lds) {
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   Ctl ctl = unpack_ctl(ctl_packed);
   Pre<DT> pre;
   // block l (1-based) has just run: what will block l + 1 run as, as far as known now
   const bool guess = (l == 0) ? ctl.river : guess_river_after(A, ctl, l);
-  // Loads return in order, so the polls of the wavefront that polls the barrier queue behind
-  // its own prefetch: it issues only the first element before the wait, the second after.
-  const bool poller = wave_in_wg() == 0 && l > 0;
   if (l > 0) { barrier_arrive(D.st, k); TRACE_ARRIVE(); }
-  prefetch_phase<DT>(D, l, PH_QKV, guess, pre, poller ? 1 : 3);
+  prefetch_phase<DT>(D, l, PH_QKV, guess, pre);
   if (l > 0) {
     barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
-    if (poller) prefetch_phase<DT>(D, l, PH_QKV, guess, pre, 2);
     exit_test(D, A, l, ctl, lds);
     if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
   }
@@ -138,20 +134,18 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
 }
 template <int DT>
 __device__ RIVER_PSTEP_INLINE void pstep_attn(const Dev *Dp, StepArgs A, int l, unsigned long long k, float *lds) {
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   phase_attn<DT>(D, A, l, lds, [&] { barrier_arrive(D.st, k); TRACE_ARRIVE(); },
                  [&] { barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE(); });
 }
 template <int DT, int PH>
 __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, bool river, unsigned long long k,
                                         float *lds) {
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   Pre<DT> pre;
-  const bool poller = wave_in_wg() == 0;       // see pstep_qkv
   barrier_arrive(D.st, k); TRACE_ARRIVE();
-  prefetch_phase<DT>(D, l, PH, river, pre, poller ? 1 : 3);
+  prefetch_phase<DT>(D, l, PH, river, pre);
   barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
-  if (poller) prefetch_phase<DT>(D, l, PH, river, pre, 2);
   if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre);
   else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre);
   else phase_down<DT>(D, A, l, river, lds, pre);
@@ -159,14 +153,12 @@ __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, 
 template <int DT>
 __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl_packed, unsigned long long k,
                                         float *lds) {
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   const Ctl ctl = unpack_ctl(ctl_packed);
   Pre<DT> pre;
-  const bool poller = wave_in_wg() == 0;       // see pstep_qkv
   barrier_arrive(D.st, k); TRACE_ARRIVE();
-  prefetch_head<DT>(D, pre, poller ? 1 : 3);
+  prefetch_head<DT>(D, pre);
   barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
-  if (poller) prefetch_head<DT>(D, pre, 2);
   phase_head<DT>(D, A, ctl, lds, pre);
 }
 
@@ -175,7 +167,7 @@ __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_step_persistent(const Dev *Dp, StepArgs A) {
   extern __shared__ float lds[];
-  const Dev &D = *Dp;
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
   unsigned long long k = A.bar_base;
   const int L = D.L;
   record_init(D, A);
@@ -282,14 +274,14 @@ static bool valid_cfg(const river_config *c, std::string *why) {
   if (c->river_group < 32 || c->river_group % 32) return bad("river_group must be a multiple of 32");
   if (c->n_q_heads % c->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
   const int G = c->n_q_heads / c->n_kv_heads;
-  if (G != 1 && G != 2 && G % 4) return bad("query heads per kv head must be 1, 2 or a multiple of 4");
-  if (c->n_kv_heads * (G > 4 ? G / 4 : 1) > kMaxKvHeads) return bad("too many kv heads");
   const int hd = c->head_dim;
   if (hd != 64 && hd != 128) return bad("head_dim must be 64 or 128");
   if (c->d_model % 16 || c->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
   if (c->vocab % 2) return bad("vocab must be even");
   if (c->min_exit_layer < 0 || c->min_exit_layer > c->n_layers) return bad("min_exit_layer out of range");
   if (c->exec_mode != RIVER_EXEC_KERNELS && c->exec_mode != RIVER_EXEC_PERSISTENT) return bad("bad exec_mode");
+  if (c->exec_mode == RIVER_EXEC_PERSISTENT && c->dtype != RIVER_BF16)
+    return bad("RIVER_EXEC_PERSISTENT is available for RIVER_BF16 only; use RIVER_EXEC_KERNELS for RIVER_F32");
   if (c->spin_limit < 0) return bad("negative spin_limit");
   if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return bad("bad rope_base / rms_eps");
   return true;
@@ -301,7 +293,7 @@ static int x_capacity(const river_config *c) {
   int cap = c->d_model;
   cap = std::max(cap, c->n_q_heads * c->head_dim);
   cap = std::max(cap, c->d_ffn);
-  cap = std::max(cap, attn_lds_floats(c->head_dim, std::min(G, 4)));
+  cap = std::max(cap, attn_lds_floats(c->head_dim));
   return (int)align_up(cap, 4);
 }
 
@@ -338,8 +330,8 @@ static Layout make_layout(const river_config *c) {
   y.h1 = take((size_t)c->d_model * 4);
   y.abuf = take((size_t)c->d_ffn * 4);
   y.logits = take((size_t)c->vocab * 4);
-  y.part_o = take((size_t)c->n_kv_heads * kMaxSplits * G * c->head_dim * 4);
-  y.part_ml = take((size_t)c->n_kv_heads * kMaxSplits * G * 4 * 4);
+  y.part_o = take((size_t)c->n_q_heads * kMaxSplits * c->head_dim * 4);
+  y.part_ml = take((size_t)c->n_q_heads * kMaxSplits * 4 * 4);
   y.cos_part = take((size_t)kMaxGrid * 4 * 4);
   y.amax_val = take((size_t)kMaxGrid * 4);
   y.amax_idx = take((size_t)kMaxGrid * 4);
@@ -588,9 +580,15 @@ static int launch_step(river_ctx *x, const StepArgs &A0) {
   const size_t lds = x->lds_bytes;
   hipStream_t s = x->stream;
   if (x->cfg.exec_mode == RIVER_EXEC_PERSISTENT) {
-    A.bar_base = x->bar_total;
-    k_step_persistent<DT><<<dim3(x->grid_persist), blk, lds, s>>>(Dp, A);
-    x->bar_total += 5ull * D.L - 1 + (A.want_head ? 1 : 0);
+    // bf16 only (river_create refuses the combination with fp32)
+    if constexpr (DT == 1) {
+      A.bar_base = x->bar_total;
+      k_step_persistent<DT><<<dim3(x->grid_persist), blk, lds, s>>>(Dp, A);
+      x->bar_total += 5ull * D.L - 1 + (A.want_head ? 1 : 0);
+    } else {
+      x->err = "RIVER_EXEC_PERSISTENT is available for RIVER_BF16 only";
+      return RIVER_EINVAL;
+    }
   } else {
     const dim3 gg(x->grid_gemv);
     for (int l = 0; l < D.L; ++l) {
@@ -614,12 +612,9 @@ static int enqueue(river_ctx *x, int token, int forced_e, int want_head, int rec
   A.want_head = want_head;
   A.rec_slot = rec_slot;
   const int T = x->pos + 1;
-  // one split per wavefront-load of positions per wave, as far as there are workgroups for it
-  const int pos_per_split = kAttnPosPerSplit;
-  const int G = x->cfg.n_q_heads / x->cfg.n_kv_heads;
-  const int vheads = x->cfg.n_kv_heads * (G > 4 ? G / 4 : 1);
-  const int max_splits = std::max(1, std::min(kMaxSplits, x->grid_persist / vheads));
-  A.n_splits = std::max(1, std::min(max_splits, (T + pos_per_split - 1) / pos_per_split));
+  // one workgroup per (query head, split); splits as far as there are workgroups for them
+  const int max_splits = std::max(1, std::min(kMaxSplits, x->grid_persist / x->cfg.n_q_heads));
+  A.n_splits = std::max(1, std::min(max_splits, (T + kAttnPosPerSplit - 1) / kAttnPosPerSplit));
   A.bar_base = 0;
   const int rc = x->cfg.dtype == RIVER_BF16 ? launch_step<1>(x, A) : launch_step<0>(x, A);
   if (rc == RIVER_OK) x->pos += 1;

@@ -30,8 +30,7 @@ constexpr int kBlock = 512;        // threads per workgroup (8 wavefronts), one 
 constexpr int kWaves = kBlock / 64;
 constexpr int kNL = 8;             // 16-byte loads per lane per step
 constexpr int kMaxGrid = 512;      // upper bound on workgroups per launch (partial-result arrays)
-constexpr int kMaxSplits = 32;     // split-K factor of decode attention
-constexpr int kMaxKvHeads = 64;
+constexpr int kMaxSplits = 8;     // split-K factor of decode attention
 constexpr int kRecords = 4096;     // ring of per-step records
 
 enum { M_WQ = 0, M_WK, M_WV, M_WO, M_GATE, M_UP, M_DOWN };
@@ -51,7 +50,6 @@ struct DevState {
   int cur_token;                  // token produced by the last head phase
   int slot_river[2], slot_exit[2];// exit state of the current token, by block parity (one-kernel-per-phase mode)
   unsigned int head_cnt;
-  unsigned int attn_cnt[kMaxKvHeads];
 };
 
 struct Dev {
@@ -68,8 +66,8 @@ struct Dev {
   float *h1;                      // [d]
   float *abuf;                    // [ffn]
   float *logits;                  // [vocab]
-  float *part_o;                  // [nkv][kMaxSplits][G][hd] unnormalised partial outputs
-  float *part_ml;                 // [nkv][kMaxSplits][G][4] (running max, sum, -, -)
+  float *part_o;                  // [nq][kMaxSplits][hd] unnormalised partial outputs
+  float *part_ml;                 // [nq][kMaxSplits][4] (running max, sum, -, -)
   float *cos_part;                // [kMaxGrid][4]
   float *amax_val;                // [kMaxGrid]
   int *amax_idx;                  // [kMaxGrid]
@@ -88,6 +86,15 @@ struct StepArgs {
   int n_splits;       // split-K factor for this step's attention
   unsigned long long bar_base;   // device-wide barriers completed before this launch
 };
+
+// The descriptor and the per-block weight tables are written once (at creation) and only
+// read by kernels.  Device code reads them through the constant address space: scalar
+// loads that the compiler may repeat or move freely, instead of vector loads it must order
+// against the kernels' own stores.
+#define RIVER_CONSTANT(T, p) ((const __attribute__((address_space(4))) T *)(p))
+typedef const __attribute__((address_space(4))) Dev &DevRef;
+typedef const __attribute__((address_space(4))) DevLayer &LayerRef;
+__device__ __forceinline__ LayerRef layer_of(DevRef D, int l) { return *RIVER_CONSTANT(DevLayer, D.layers + l); }
 
 // Exit state of the current token, identical in every workgroup (each derives it from the
 // same published sums in the same order).
@@ -309,8 +316,8 @@ __device__ __forceinline__ bool last_arriver(unsigned int *cnt, unsigned int exp
 
 // [0, xcap) staged vector (or the attention merge area), [xcap, xcap+32) reduction
 // scratch, [xcap+32] last-arriver flag.
-__device__ __forceinline__ float *lds_red(const Dev &D, float *lds) { return lds + D.xcap; }
-__device__ __forceinline__ int *lds_flag(const Dev &D, float *lds) { return (int *)(lds + D.xcap + 32); }
+__device__ __forceinline__ float *lds_red(DevRef D, float *lds) { return lds + D.xcap; }
+__device__ __forceinline__ int *lds_flag(DevRef D, float *lds) { return (int *)(lds + D.xcap + 32); }
 
 // wave-uniform by construction; readfirstlane tells the compiler, so that task indices and
 // row pointers live in scalar registers
@@ -347,7 +354,7 @@ __device__ __forceinline__ void stage_norm(const float *h, const void *gain, int
 // Same, the source being row `tok` of the embedding table (block 1 of a token); also
 // publishes h(0) (each workgroup a slice) for the residual adds and the similarity.
 template <int DT>
-__device__ __forceinline__ void stage_norm_embed(const Dev &D, int tok, const void *gain, float *xl,
+__device__ __forceinline__ void stage_norm_embed(DevRef D, int tok, const void *gain, float *xl,
                                                  float *red) {
   const int n = D.d;
   float ss = 0.f;
@@ -373,6 +380,8 @@ __device__ __forceinline__ void stage_copy(const float *src, int n, float *xl) {
 
 // ------------------------------------------------- weight streaming engine
 
+template <int V> struct IC { static constexpr int value = V; };   // compile-time value as a tag
+
 // Registers of one step: kNL lane loads (codes or dense weights) and, for river rows,
 // the (scale, zero) pair of the group each lane load falls in.
 template <int DT> struct Regs {
@@ -386,17 +395,17 @@ template <int R> struct Rows {
   const char *sz[R];       // (scale, zero) row (river only)
 };
 
-// Dense format: a step covers R rows x U = kNL / R column granules of 64 lanes x 16 bytes.
-template <int DT, int R> struct Dense {
-  static constexpr int U = kNL / R;
+// Dense format: a step covers R rows x U column granules of 64 lanes x 16 bytes (R*U <= kNL).
+template <int DT, int R, int U> struct Dense {
+  static_assert(R * U <= kNL, "a step holds at most kNL lane loads");
   static constexpr int EPL = Store<DT>::EPL;
   static __device__ __forceinline__ int steps(int cols) {
     const int row_bytes = cols * (int)sizeof(typename Store<DT>::T);
     return (row_bytes + U * 1024 - 1) / (U * 1024);
   }
-  static __device__ __forceinline__ void issue(Regs<DT> &g, const Rows<R> &rw, int cols, int group, int step) {
+  static __device__ __forceinline__ void issue(Regs<DT> &g, const Rows<R> &rw, int cols, int group, int step,
+                                               int lane) {
     const int row_bytes = cols * (int)sizeof(typename Store<DT>::T);
-    const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int off = (step * U + u) * 1024 + lane * 16;
@@ -406,8 +415,7 @@ template <int DT, int R> struct Dense {
     }
   }
   static __device__ __forceinline__ void fma(const Regs<DT> &g, int cols, int group, int step,
-                                             const float *xl, float (&acc)[R]) {
-    const int lane = threadIdx.x & 63;
+                                             const float *xl, float (&acc)[R], int lane) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int c = ((step * U + u) * 64 + lane) * EPL;
@@ -435,13 +443,13 @@ template <int DT, int R> struct Dense {
 // group.  Per lane load the sum over its columns is factored as
 // scale * (sum code*x - zero * sum x).  group % CPL == 0, so a lane load never straddles
 // a group.
-template <int DT, int R, int CPL> struct W4 {
-  static constexpr int U = kNL / R;
+template <int DT, int R, int U, int CPL> struct W4 {
+  static_assert(R * U <= kNL, "a step holds at most kNL lane loads");
   static __device__ __forceinline__ int steps(int cols) {
     return (cols + U * 64 * CPL - 1) / (U * 64 * CPL);
   }
-  static __device__ __forceinline__ void issue(Regs<DT> &g, const Rows<R> &rw, int cols, int group, int step) {
-    const int lane = threadIdx.x & 63;
+  static __device__ __forceinline__ void issue(Regs<DT> &g, const Rows<R> &rw, int cols, int group, int step,
+                                               int lane) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int c = ((step * U + u) * 64 + lane) * CPL;
@@ -472,8 +480,7 @@ template <int DT, int R, int CPL> struct W4 {
     return a;
   }
   static __device__ __forceinline__ void fma(const Regs<DT> &g, int cols, int group, int step,
-                                             const float *xl, float (&acc)[R]) {
-    const int lane = threadIdx.x & 63;
+                                             const float *xl, float (&acc)[R], int lane) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int c = ((step * U + u) * 64 + lane) * CPL;
@@ -503,20 +510,30 @@ template <int DT, int R, int CPL> struct W4 {
 // form one sequence j = 0, 1, 2, ...: task wave_id() + (j / NS) * wave_count(), step j % NS.
 // Set a holds an even j, set b the following odd j; while one is consumed the other is in
 // flight, and both can be issued before the barrier in front of the phase.
+// `lane` is the lane id passed through an empty asm: with all phases of all blocks inlined
+// into one kernel the compiler would otherwise derive every lane-offset variant once at
+// kernel entry and keep (spill) them all; this way they are re-derived per phase.
+__device__ __forceinline__ int fresh_lane() {
+  int t = threadIdx.x & 63;
+  asm volatile("" : "+v"(t));
+  return t;
+}
 template <int DT> struct Pre {
   Regs<DT> a, b;
+  int lane;
+  __device__ __forceinline__ Pre() : lane(fresh_lane()) {}
 };
 
 // Issue element j of this wavefront's sequence into g (nothing if the sequence is shorter).
 template <class F, int DT, int R, class RowsOf>
 __device__ __forceinline__ void issue_seq(int j, int n_tasks, int cols, int group, Regs<DT> &g,
-                                          RowsOf rows_of) {
+                                          int lane, RowsOf rows_of) {
   const int NS = F::steps(cols);
   const int t = wave_id() + (j / NS) * wave_count();
   if (t < n_tasks) {
     Rows<R> rw;
     rows_of(t, rw);
-    F::issue(g, rw, cols, group, j % NS);
+    F::issue(g, rw, cols, group, j % NS, lane);
   }
 }
 
@@ -536,7 +553,7 @@ __device__ __forceinline__ void stream_tasks(int n_tasks, int cols, int group, c
   for (int r = 0; r < R; ++r) acc[r] = 0.f;
   int s = 0, t = w;                                       // step and task being consumed
   auto consume = [&](Regs<DT> &g) {
-    F::fma(g, cols, group, s, xl, acc);
+    F::fma(g, cols, group, s, xl, acc, pre.lane);
     if (++s == NS) {
 #pragma unroll
       for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
@@ -549,139 +566,143 @@ __device__ __forceinline__ void stream_tasks(int n_tasks, int cols, int group, c
   };
   for (int j = 0; j < J; j += 2) {
     consume(pre.a);
-    if (j + 2 < J) issue_seq<F, DT, R>(j + 2, n_tasks, cols, group, pre.a, rows_of);
+    if (j + 2 < J) issue_seq<F, DT, R>(j + 2, n_tasks, cols, group, pre.a, pre.lane, rows_of);
     if (j + 1 < J) {
       consume(pre.b);
-      if (j + 3 < J) issue_seq<F, DT, R>(j + 3, n_tasks, cols, group, pre.b, rows_of);
+      if (j + 3 < J) issue_seq<F, DT, R>(j + 3, n_tasks, cols, group, pre.b, pre.lane, rows_of);
     }
   }
 }
-
-// Row pointers of a task from (matrix, row) pairs.
-template <int DT, int R>
-__device__ __forceinline__ void set_rows(Rows<R> &rw, const DevLayer &Lw, bool river, const int (&m)[R],
-                                         const int (&row)[R], int cols, int group) {
-  if (!river) {
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      rw.p[r] = (const char *)Lw.w[m[r]] + (size_t)row[r] * cols * sizeof(typename Store<DT>::T);
-      rw.sz[r] = nullptr;
-    }
-  } else {
-    const int gpr = (cols + group - 1) / group;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      rw.p[r] = (const char *)Lw.qc[m[r]] + (size_t)row[r] * (cols >> 1);
-      rw.sz[r] = (const char *)Lw.qsz[m[r]] + (size_t)row[r] * gpr * sizeof(typename Store<DT>::SZ);
-    }
-  }
-}
-
-// Rows per task: 2 for dense rows (2 x 8 granules per step), 4 for river rows.
-constexpr int kRD = 2, kRQ = 4;
 
 // ------------------------------------------------- task -> rows, per phase
 
 enum { PH_QKV = 0, PH_O, PH_GU, PH_DOWN };
 
-// number of tasks of a phase for R rows per task
-template <int R>
-__device__ __forceinline__ int phase_tasks(const Dev &D, int ph) {
-  switch (ph) {
-    case PH_QKV: return (D.nq + 2 * D.nkv) * (D.hd >> 1) * 2 / R;   // rotation pairs (2 rows each)
-    case PH_O: return D.d / R;
-    case PH_GU: return D.ffn * 2 / R;                               // (gate, up) row pairs
-    default: return D.d / R;
-  }
+// Every GEMV phase works on a linear row space:
+//   QKV   n in [0, qd + 2 kvd): rows of W_q, then W_k, then W_v
+//   O     n in [0, d)
+//   GU    n in [0, 2 ffn): n = 2 i is gate row i, n = 2 i + 1 is up row i
+//   DOWN  n in [0, d)
+// A task is R consecutive rows; R and the column granules per step U are chosen per phase
+// and format so that (for the 8B shape) the tasks divide evenly over the 2048 wavefronts
+// and a step fills the load slots:   dense  QKV 1x8  O 1x8  GU 2x4  DOWN 2x4
+//                                    river  QKV 3x2  O 2x2  GU 2x2  DOWN 1x7
+template <int PH, bool RIVER> struct Shape;
+template <> struct Shape<PH_QKV, false> { static constexpr int R = 1, U = 8; };
+template <> struct Shape<PH_O, false> { static constexpr int R = 1, U = 8; };
+template <> struct Shape<PH_GU, false> { static constexpr int R = 2, U = 4; };
+template <> struct Shape<PH_DOWN, false> { static constexpr int R = 2, U = 4; };
+template <> struct Shape<PH_QKV, true> { static constexpr int R = 3, U = 2; };
+template <> struct Shape<PH_O, true> { static constexpr int R = 2, U = 2; };
+template <> struct Shape<PH_GU, true> { static constexpr int R = 2, U = 2; };
+template <> struct Shape<PH_DOWN, true> { static constexpr int R = 1, U = 7; };
+
+__device__ __forceinline__ int phase_nrows(DevRef D, int ph) {
+  return ph == PH_QKV ? (D.nq + 2 * D.nkv) * D.hd : ph == PH_GU ? 2 * D.ffn : D.d;
 }
-__device__ __forceinline__ int phase_cols(const Dev &D, int ph) {
+__device__ __forceinline__ int phase_cols(DevRef D, int ph) {
   return ph == PH_O ? D.nq * D.hd : ph == PH_DOWN ? D.ffn : D.d;
 }
 
-// QKV pair index -> matrix, head, first row
-__device__ __forceinline__ void qkv_pair(const Dev &D, int pair, int &m, int &hh, int &i) {
-  const int half = D.hd >> 1;
-  const int head = pair / half;
-  i = pair % half;
-  if (head < D.nq) { m = M_WQ; hh = head; }
-  else if (head < D.nq + D.nkv) { m = M_WK; hh = head - D.nq; }
-  else { m = M_WV; hh = head - D.nq - D.nkv; }
-}
-
-template <int DT, int R>
-__device__ __forceinline__ void phase_rows(const Dev &D, const DevLayer &Lw, int ph, bool river, int t,
-                                           Rows<R> &rw) {
-  int m[R], row[R];
-  const int cols = phase_cols(D, ph);
-  if (ph == PH_QKV) {
-    const int half = D.hd >> 1;
-#pragma unroll
-    for (int k = 0; k < R / 2; ++k) {
-      int mm, hh, i;
-      qkv_pair(D, t * (R / 2) + k, mm, hh, i);
-      m[2 * k] = mm; m[2 * k + 1] = mm;
-      row[2 * k] = hh * D.hd + i; row[2 * k + 1] = hh * D.hd + i + half;
-    }
-  } else if (ph == PH_GU) {
-#pragma unroll
-    for (int k = 0; k < R / 2; ++k) {
-      m[2 * k] = M_GATE; m[2 * k + 1] = M_UP;
-      row[2 * k] = t * (R / 2) + k; row[2 * k + 1] = t * (R / 2) + k;
-    }
+// linear row n of a phase -> matrix and row in it
+template <int PH>
+__device__ __forceinline__ void phase_row(DevRef D, int n, int &m, int &row) {
+  if (PH == PH_QKV) {
+    const int qd = D.nq * D.hd, kvd = D.nkv * D.hd;
+    if (n < qd) { m = M_WQ; row = n; }
+    else if (n < qd + kvd) { m = M_WK; row = n - qd; }
+    else { m = M_WV; row = n - qd - kvd; }
+  } else if (PH == PH_GU) {
+    m = (n & 1) ? M_UP : M_GATE;
+    row = n >> 1;
   } else {
-#pragma unroll
-    for (int r = 0; r < R; ++r) { m[r] = ph == PH_O ? M_WO : M_DOWN; row[r] = t * R + r; }
+    m = PH == PH_O ? M_WO : M_DOWN;
+    row = n;
   }
-  set_rows<DT, R>(rw, Lw, river, m, row, cols, D.group);
 }
 
-// Issue the first two elements of this wavefront's sequence of phase `ph` of block l (dense
-// or river).  `which`: bit 0 = element 0 into g.a, bit 1 = element 1 into g.b.
-template <int DT>
-__device__ __forceinline__ void prefetch_phase(const Dev &D, int l, int ph, bool river, Pre<DT> &g,
-                                               int which = 3) {
-  const DevLayer &Lw = D.layers[l];
-  const int cols = phase_cols(D, ph);
-  if (!river) {
-    auto rows_of = [&](int t, Rows<kRD> &rw) { phase_rows<DT, kRD>(D, Lw, ph, false, t, rw); };
-    const int n = phase_tasks<kRD>(D, ph);
-    if (which & 1) issue_seq<Dense<DT, kRD>, DT, kRD>(0, n, cols, D.group, g.a, rows_of);
-    if (which & 2) issue_seq<Dense<DT, kRD>, DT, kRD>(1, n, cols, D.group, g.b, rows_of);
-  } else {
-    auto rows_of = [&](int t, Rows<kRQ> &rw) { phase_rows<DT, kRQ>(D, Lw, ph, true, t, rw); };
-    const int n = phase_tasks<kRQ>(D, ph);
-    if ((cols & 31) == 0) {
-      if (which & 1) issue_seq<W4<DT, kRQ, 32>, DT, kRQ>(0, n, cols, D.group, g.a, rows_of);
-      if (which & 2) issue_seq<W4<DT, kRQ, 32>, DT, kRQ>(1, n, cols, D.group, g.b, rows_of);
+// Row pointers of task t (rows t*R .. t*R+R-1, clamped to the last row of the phase).
+template <int DT, int PH, bool RIVER, int R>
+__device__ __forceinline__ void phase_rows(DevRef D, LayerRef Lw, int t, Rows<R> &rw) {
+  const int cols = phase_cols(D, PH), last = phase_nrows(D, PH) - 1;
+  const int gpr = (cols + D.group - 1) / D.group;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    int m, row;
+    phase_row<PH>(D, min(t * R + r, last), m, row);
+    if (!RIVER) {
+      rw.p[r] = (const char *)Lw.w[m] + (size_t)row * cols * sizeof(typename Store<DT>::T);
+      rw.sz[r] = nullptr;
     } else {
-      if (which & 1) issue_seq<W4<DT, kRQ, 16>, DT, kRQ>(0, n, cols, D.group, g.a, rows_of);
-      if (which & 2) issue_seq<W4<DT, kRQ, 16>, DT, kRQ>(1, n, cols, D.group, g.b, rows_of);
+      rw.p[r] = (const char *)Lw.qc[m] + (size_t)row * (cols >> 1);
+      rw.sz[r] = (const char *)Lw.qsz[m] + (size_t)row * gpr * sizeof(typename Store<DT>::SZ);
     }
   }
 }
 
-// Run a block phase over the staged vector; epi2(row-slot k, task, acc[2k], acc[2k+1])
-// is called for every pair of rows of a task (lane-uniform values).
-template <int DT, class Epi>
-__device__ __forceinline__ void run_phase(const Dev &D, int l, int ph, bool river, const float *xl,
-                                          Pre<DT> &pre, Epi epi) {
-  const DevLayer &Lw = D.layers[l];
-  const int cols = phase_cols(D, ph);
+// f(Format type tag) is called with the streaming format of (PH, river, column count).
+template <class F> struct Tag { typedef F type; };
+template <int DT, int PH, class Fn>
+__device__ __forceinline__ void with_format(DevRef D, bool river, Fn f) {
   if (!river) {
-    auto rows_of = [&](int t, Rows<kRD> &rw) { phase_rows<DT, kRD>(D, Lw, ph, false, t, rw); };
-    auto e = [&](int t, float (&acc)[kRD]) { epi(t, acc[0], acc[1]); };
-    stream_tasks<Dense<DT, kRD>, DT, kRD>(phase_tasks<kRD>(D, ph), cols, D.group, xl, pre, rows_of, e);
+    f(Tag<Dense<DT, Shape<PH, false>::R, Shape<PH, false>::U>>(), IC<false>(), IC<Shape<PH, false>::R>());
+  } else if ((phase_cols(D, PH) & 31) == 0) {
+    f(Tag<W4<DT, Shape<PH, true>::R, Shape<PH, true>::U, 32>>(), IC<true>(), IC<Shape<PH, true>::R>());
   } else {
-    auto rows_of = [&](int t, Rows<kRQ> &rw) { phase_rows<DT, kRQ>(D, Lw, ph, true, t, rw); };
-    auto e = [&](int t, float (&acc)[kRQ]) {
-      epi(2 * t, acc[0], acc[1]);
-      epi(2 * t + 1, acc[2], acc[3]);
-    };
-    if ((cols & 31) == 0)
-      stream_tasks<W4<DT, kRQ, 32>, DT, kRQ>(phase_tasks<kRQ>(D, ph), cols, D.group, xl, pre, rows_of, e);
-    else
-      stream_tasks<W4<DT, kRQ, 16>, DT, kRQ>(phase_tasks<kRQ>(D, ph), cols, D.group, xl, pre, rows_of, e);
+    f(Tag<W4<DT, Shape<PH, true>::R, Shape<PH, true>::U, 16>>(), IC<true>(), IC<Shape<PH, true>::R>());
   }
+}
+
+// Issue the first two elements of this wavefront's sequence of phase PH of block l (dense
+// or river).  `which`: bit 0 = element 0 into g.a, bit 1 = element 1 into g.b.
+template <int DT, int PH>
+__device__ __forceinline__ void prefetch_phase_t(DevRef D, int l, bool river, Pre<DT> &g, int which) {
+  LayerRef Lw = layer_of(D, l);
+  with_format<DT, PH>(D, river, [&](auto ftag, auto rv, auto rr) {
+    typedef typename decltype(ftag)::type F;
+    constexpr bool RV = decltype(rv)::value;
+    constexpr int R = decltype(rr)::value;
+    auto rows_of = [&](int t, Rows<R> &rw) { phase_rows<DT, PH, RV, R>(D, Lw, t, rw); };
+    const int n = (phase_nrows(D, PH) + R - 1) / R, cols = phase_cols(D, PH);
+    if (which & 1) issue_seq<F, DT, R>(0, n, cols, D.group, g.a, g.lane, rows_of);
+    if (which & 2) issue_seq<F, DT, R>(1, n, cols, D.group, g.b, g.lane, rows_of);
+  });
+}
+template <int DT>
+__device__ __forceinline__ void prefetch_phase(DevRef D, int l, int ph, bool river, Pre<DT> &g,
+                                               int which = 3) {
+  switch (ph) {
+    case PH_QKV: prefetch_phase_t<DT, PH_QKV>(D, l, river, g, which); break;
+    case PH_O: prefetch_phase_t<DT, PH_O>(D, l, river, g, which); break;
+    case PH_GU: prefetch_phase_t<DT, PH_GU>(D, l, river, g, which); break;
+    default: prefetch_phase_t<DT, PH_DOWN>(D, l, river, g, which); break;
+  }
+}
+
+// Run phase PH of block l over the staged vector.  epi(n0, acc) is called once per task with
+// its first linear row n0 and the R finished dot products (lane-uniform); rows >= the row
+// count of the phase (a ragged last task) must be ignored by it.
+template <int DT, int PH, class Epi>
+__device__ __forceinline__ void run_phase(DevRef D, int l, bool river, const float *xl,
+                                          Pre<DT> &pre, Epi epi) {
+  LayerRef Lw = layer_of(D, l);
+  with_format<DT, PH>(D, river, [&](auto ftag, auto rv, auto rr) {
+    typedef typename decltype(ftag)::type F;
+    constexpr bool RV = decltype(rv)::value;
+    constexpr int R = decltype(rr)::value;
+    auto rows_of = [&](int t, Rows<R> &rw) { phase_rows<DT, PH, RV, R>(D, Lw, t, rw); };
+    auto e = [&](int t, float (&acc)[R]) { epi(t * R, acc); };
+    stream_tasks<F, DT, R>((phase_nrows(D, PH) + R - 1) / R, phase_cols(D, PH), D.group, xl, pre, rows_of, e);
+  });
+}
+
+// value of acc[lane] for lane < R (register arrays cannot be indexed by a lane id)
+template <int R>
+__device__ __forceinline__ float pick(const float (&acc)[R], int lane) {
+  float v = acc[0];
+#pragma unroll
+  for (int r = 1; r < R; ++r) v = lane == r ? acc[r] : v;
+  return v;
 }
 
 // diagnostics build: workgroup 0 stamps the 100 MHz wall clock at marked points of the
@@ -706,7 +727,7 @@ __device__ __forceinline__ void run_phase(const Dev &D, int l, int ph, bool rive
 
 // Eq. 1 for block l1 = l (1-based) from the sums the down-projection phase of that block
 // published; every workgroup computes the same value in the same order.  Returns s.
-__device__ __forceinline__ float similarity_from_partials(const Dev &D, float *red) {
+__device__ __forceinline__ float similarity_from_partials(DevRef D, float *red) {
   float pab = 0.f, paa = 0.f, pbb = 0.f;
   for (int i = threadIdx.x; i < (int)gridDim.x; i += blockDim.x) {
     const float4 v = sub4(D.cos_part, i * 4);
@@ -723,7 +744,7 @@ __device__ __forceinline__ float similarity_from_partials(const Dev &D, float *r
 
 // Exit test after backbone block l1 (1-based), Eq. 1: first hit at or above L_s, never at
 // L, strict '>'; a forced exit position overrides the threshold.
-__device__ __forceinline__ void exit_test(const Dev &D, const StepArgs &A, int l1, Ctl &ctl, float *lds) {
+__device__ __forceinline__ void exit_test(DevRef D, const StepArgs &A, int l1, Ctl &ctl, float *lds) {
   if (ctl.river) return;
   const float s = similarity_from_partials(D, lds_red(D, lds));
   if (blockIdx.x == 0 && threadIdx.x == 0 && A.rec_slot >= 0)
@@ -740,13 +761,13 @@ __device__ __forceinline__ bool guess_river_after(const StepArgs &A, const Ctl &
   return ctl.river || A.forced_e == l1;
 }
 
-// a0 + a1 + a2: (block 1: h(0) = E[token]); x = RMSNorm(h) * g1; [q;k;v] = W x; RoPE on
-// q, k at this position; k, v rounded to the cache dtype and stored in slot (l, pos) --
-// the same slot for backbone and river ("identical KV Cache addressing scheme").  A task
-// owns rotation pairs (rows i and i + hd/2 of a head), so the rotation needs no exchange.
+// a0 + a1: (block 1: h(0) = E[token]); x = RMSNorm(h) * g1; [q;k;v] = W x, published raw.
+// RoPE, the rounding of k, v to the cache dtype and the write of slot (l, pos) happen in the
+// attention phase (a2 there), which frees the row-to-wavefront assignment here: single rows,
+// three per wavefront at the 8B shape, instead of rotation pairs (one and a half).
 template <int DT>
-__device__ __forceinline__ void phase_qkv(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
-  const DevLayer &Lw = D.layers[l];
+__device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+  LayerRef Lw = layer_of(D, l);
   if (l == 0) {
     int tok = A.token >= 0 ? A.token : D.st->cur_token;
     tok = min(max(tok, 0), D.vocab - 1);       // a NaN-poisoned argmax must not index out of range
@@ -754,33 +775,18 @@ __device__ __forceinline__ void phase_qkv(const Dev &D, const StepArgs &A, int l
   } else {
     stage_norm<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, lds, lds_red(D, lds));
   }
-  const int half = D.hd >> 1;
-  const int kvd = D.nkv * D.hd;
-  const int lane = threadIdx.x & 63;
-  auto epi = [&](int pair, float a, float b) {
-    if (lane != 0) return;
-    int m, hh, i;
-    qkv_pair(D, pair, m, hh, i);
-    if (m != M_WV) {
-      const size_t ri = ((size_t)A.pos * half + i) * 2;
-      const float2 cs = make_float2(RIVER_GLOBAL(float, D.rope)[ri], RIVER_GLOBAL(float, D.rope)[ri + 1]);
-      const float ra = a * cs.x - b * cs.y, rb = a * cs.y + b * cs.x;
-      a = ra; b = rb;
-    }
-    if (m == M_WQ) {
-      pub(D.qbuf + hh * D.hd + i, a);
-      pub(D.qbuf + hh * D.hd + i + half, b);
-    } else {
-      void *cache = (m == M_WK) ? D.kcache : D.vcache;
-      const size_t base = ((size_t)l * D.max_seq + A.pos) * kvd + (size_t)hh * D.hd;
-      Store<DT>::st(cache, base + i, a);             // for later tokens (later launches)
-      Store<DT>::st(cache, base + i + half, b);
-      float *cur = D.kvcur + (m == M_WK ? 0 : kvd) + hh * D.hd;
-      pub(cur + i, Store<DT>::rnd(a));               // for this token's attention
-      pub(cur + i + half, Store<DT>::rnd(b));
+  const int qd = D.nq * D.hd, nrows = qd + 2 * D.nkv * D.hd;
+  const int lane = pre.lane;
+  auto epi = [&](int n0, auto &acc) {
+    constexpr int R = sizeof(acc) / sizeof(float);
+    const int n = n0 + lane;
+    if (lane < R && n < nrows) {
+      const float v = pick<R>(acc, lane);
+      if (n < qd) pub(D.qbuf + n, v);
+      else pub(D.kvcur + (n - qd), v);          // [k (kvd); v (kvd)]
     }
   };
-  run_phase<DT>(D, l, PH_QKV, river, lds, pre, epi);
+  run_phase<DT, PH_QKV>(D, l, river, lds, pre, epi);
 }
 
 // Sum over the 16 lanes of a DPP row; every lane gets the result.  DPP lane permutations
@@ -798,25 +804,39 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
-// a3: split-K GQA decode attention.  A workgroup owns (kv head, split).  Sixteen lanes
-// share a cached position (EL = hd/16 elements each), so a wavefront load covers 4
-// positions; kAttnRounds such loads of K and of V per lane are in flight at once, and the
-// first chunk is issued BEFORE the device-wide barrier in front of the phase (old cache rows
-// do not depend on this block's QKV).  All G query heads of the group are served from
-// registers.  Each lane group keeps an online softmax (base 2, the scores carry log2 e)
-// over its positions, rescaled once per chunk; the 4 x 8 lane groups of the workgroup then
-// meet in LDS and are merged in a fixed order, then the splits are merged by the last
-// workgroup of the head to arrive (partials fetched in batches of independent loads), so
-// the result is independent of timing.  With one split the workgroup writes the output
-// itself.  The current position's K/V come from the exchange buffer.
-constexpr int kAttnRounds = 4;
-constexpr int kAttnPosPerSplit = kWaves * 4 * kAttnRounds;   // positions one workgroup covers per chunk
-constexpr int kCombine = 8;
-constexpr float kNegBig = -1.0e30f;   // "no position yet": finite, so differences never give NaN
+// a2 for the 16 lanes that share one head vector (lane dl holds elements dl*EL .. dl*EL+EL-1):
+// the rotation partner i +- hd/2 of every element sits in lane dl ^ 8 at the same register
+// index, so one DPP row rotation by 8 fetches it.  cs[e] = (cos, sin) of pair (dl & 7)*EL + e.
+template <int EL>
+__device__ __forceinline__ void rope_rotate(float (&x)[EL], const float2 (&cs)[EL], bool upper) {
+#pragma unroll
+  for (int e = 0; e < EL; ++e) {
+    const float o = __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x[e]), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+    // lower half: x c - o s;  upper half: x c + o s   (o = the partner element)
+    x[e] = upper ? o * cs[e].y + x[e] * cs[e].x : x[e] * cs[e].x - o * cs[e].y;
+  }
+}
 
-// LDS floats of the merge area: per (wavefront, lane group) entry G*hd outputs and G*2
-// (max, sum).
-__host__ __device__ inline int attn_lds_floats(int hd, int g) { return kWaves * 4 * g * (hd + 2); }
+// a3: split-K decode attention, one workgroup per (query head, split).  Sixteen lanes
+// share a cached position (EL = hd/16 elements each), so a wavefront load covers 4
+// positions and the workgroup's 32 lane groups 32 positions; a chunk is RU such rounds.
+// Two chunks are in flight per lane; both are issued BEFORE the device-wide barrier in
+// front of the phase (old cache rows do not depend on this block's QKV) and re-issued
+// alternately while the other is consumed.  The query heads of a kv head run in different
+// workgroups of the same XCD (item index = kv head + nkv * ...; consecutive workgroup ids
+// go round the XCDs), so the repeated K/V reads meet in that XCD's L2.  Each lane group
+// keeps an online softmax (base 2, the scores carry log2 e) rescaled once per chunk; the
+// four lane groups of a wavefront are merged with lane exchanges, the eight wavefronts in
+// LDS in a fixed order, and the splits (if more than one) by the consumer, in split order
+// -- the result is independent of timing.
+// This token's own K/V come from the exchange buffer and seed the running softmax of the
+// lane group that owns the current position.
+constexpr int kAttnPosPerSplit = 512;   // positions a workgroup should cover before the host adds a split
+constexpr float kNegBig = -1.0e30f;     // "no position yet": finite, so differences never give NaN
+
+// LDS floats of the merge area: per wavefront hd outputs and (max, sum).
+__host__ __device__ inline int attn_lds_floats(int hd) { return kWaves * (hd + 2); }
 
 template <int DT, int EL> struct KV {                  // raw cache words of one lane: EL elements
   static constexpr int NW = EL * (int)sizeof(typename Store<DT>::T) / 4;
@@ -837,6 +857,25 @@ template <int DT, int EL> struct KV {                  // raw cache words of one
 #pragma unroll
     for (int i = 0; i < NW; ++i) w[i] = 0;
   }
+  // round EL values to the cache dtype (nearest even)
+  __device__ __forceinline__ void from(const float (&f)[EL]) {
+    if constexpr (DT == 1) {
+#pragma unroll
+      for (int i = 0; i < NW; ++i)
+        w[i] = (uint32_t)Store<1>::rne(f[2 * i]) | ((uint32_t)Store<1>::rne(f[2 * i + 1]) << 16);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NW; ++i) w[i] = __float_as_uint(f[i]);
+    }
+  }
+  __device__ __forceinline__ void store(char *p) const {
+    if constexpr (NW == 2) {
+      *(uint2 *)p = make_uint2(w[0], w[1]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NW; i += 4) *(uint4 *)(p + i * 4) = make_uint4(w[i], w[i + 1], w[i + 2], w[i + 3]);
+    }
+  }
   __device__ __forceinline__ void unpack(float (&f)[EL]) const {
     if constexpr (DT == 1) {
 #pragma unroll
@@ -851,34 +890,49 @@ template <int DT, int EL> struct KV {                  // raw cache words of one
   }
 };
 
-template <int DT, int EL> struct KVChunk { KV<DT, EL> k[kAttnRounds], v[kAttnRounds]; };
+// Rounds per chunk: 64 registers of K and V per chunk (two chunks are held), at most 8.
+template <int DT, int EL> struct AttnShape {
+  static constexpr int NW = KV<DT, EL>::NW;
+  static constexpr int RU = 32 / NW > 8 ? 8 : 32 / NW;
+  static constexpr int NENT = kWaves * 4;              // lane groups per workgroup
+  static constexpr int CH = NENT * RU;                 // positions per chunk
+};
+template <int DT, int EL> struct KVChunk {
+  KV<DT, EL> k[AttnShape<DT, EL>::RU], v[AttnShape<DT, EL>::RU];
+};
+template <int DT, int EL> struct AttnPre {             // what is fetched ahead of the barrier
+  KVChunk<DT, EL> a, b;
+  float2 cs[EL];                                       // RoPE (cos, sin) of the current position
+};
 
-// Geometry of the item (virtual head, split) a workgroup serves.
-struct AttnItem { int vh, kvh, sp, p0, p1; };
-template <int G>
-__device__ __forceinline__ AttnItem attn_item(const Dev &D, const StepArgs &A, int item) {
+// Geometry of the item (query head, split) a workgroup serves.
+struct AttnItem { int h, kvh, sp, p0, p1; };
+__device__ __forceinline__ AttnItem attn_item(DevRef D, const StepArgs &A, int item) {
   const int S = A.n_splits, T = A.pos + 1;
   const int chunk = (T + S - 1) / S;
-  const int npass = (D.nq / D.nkv) / G;
+  const int gq = D.nq / D.nkv;
   AttnItem it;
-  it.vh = item / S; it.sp = item % S;
-  it.kvh = it.vh / npass;
+  it.kvh = item % D.nkv;
+  const int r = item / D.nkv;
+  it.h = it.kvh * gq + r % gq;
+  it.sp = r / gq;
   it.p0 = it.sp * chunk; it.p1 = min(T, it.p0 + chunk);
   return it;
 }
 
-// Issue the loads of one chunk: positions pb + u*32 + slot for u < kAttnRounds (pb already
-// includes this wavefront's offset).  The current position is never read from the cache.
+// Issue the loads of one chunk: positions pb + u*32 + slot for u < RU (pb already includes
+// this wavefront's offset).  The current position is never read from the cache.
 template <int DT, int EL>
-__device__ __forceinline__ void attn_load_chunk(const Dev &D, const StepArgs &A, int l, const AttnItem &it,
-                                                int pb, KVChunk<DT, EL> &c) {
-  const int lane = threadIdx.x & 63, slot = lane >> 4, dl = lane & 15;
+__device__ __forceinline__ void attn_load_chunk(DevRef D, const StepArgs &A, int l, const AttnItem &it,
+                                                int pb, int lane, KVChunk<DT, EL> &c) {
+  typedef AttnShape<DT, EL> SH;
+  const int slot = lane >> 4, dl = lane & 15;
   const int kvd = D.nkv * D.hd;
   const size_t es = sizeof(typename Store<DT>::T);
   const size_t base = ((size_t)l * D.max_seq * kvd + (size_t)it.kvh * D.hd + dl * EL) * es;
 #pragma unroll
-  for (int u = 0; u < kAttnRounds; ++u) {
-    const int p = pb + u * (kWaves * 4) + slot;
+  for (int u = 0; u < SH::RU; ++u) {
+    const int p = pb + u * SH::NENT + slot;
     if (p < it.p1 && p != A.pos) {
       const size_t off = base + (size_t)p * kvd * es;
       c.k[u].load((const char *)D.kcache + off);
@@ -890,237 +944,280 @@ __device__ __forceinline__ void attn_load_chunk(const Dev &D, const StepArgs &A,
   }
 }
 
-// First chunk of the first item of this workgroup (if it has one).
-template <int DT, int G, int EL>
-__device__ __forceinline__ void attn_prefetch(const Dev &D, const StepArgs &A, int l, KVChunk<DT, EL> &c) {
-  const int npass = (D.nq / D.nkv) / G;
-  if ((int)blockIdx.x < D.nkv * npass * A.n_splits) {
-    const AttnItem it = attn_item<G>(D, A, blockIdx.x);
-    attn_load_chunk<DT, EL>(D, A, l, it, it.p0 + wave_in_wg() * 4, c);
+// What does not depend on this block's QKV, for item `item` of this workgroup: the first
+// two chunks of cached K/V and the rotation table row of the current position.
+template <int DT, int EL>
+__device__ __forceinline__ void attn_prefetch(DevRef D, const StepArgs &A, int l, int item, int lane,
+                                              AttnPre<DT, EL> &c) {
+  typedef AttnShape<DT, EL> SH;
+  if (item < D.nq * A.n_splits) {
+    const int dl = lane & 15;
+    const float *rt = (const float *)D.rope + ((size_t)A.pos * (D.hd >> 1) + (dl & 7) * EL) * 2;
+#pragma unroll
+    for (int e = 0; e < EL; e += 2) {
+      const f32x4 t = *RIVER_GLOBAL(f32x4, rt + e * 2);
+      c.cs[e] = make_float2(t.x, t.y); c.cs[e + 1] = make_float2(t.z, t.w);
+    }
+    const AttnItem it = attn_item(D, A, item);
+    const int pb = it.p0 + wave_in_wg() * 4;
+    attn_load_chunk<DT, EL>(D, A, l, it, pb, lane, c.a);
+    attn_load_chunk<DT, EL>(D, A, l, it, pb + SH::CH, lane, c.b);
   }
 }
 
-template <int DT, int G, int EL>
-__device__ __forceinline__ void attn_items(const Dev &D, const StepArgs &A, int l, float *lds,
-                                           KVChunk<DT, EL> &cur) {
-  constexpr int RU = kAttnRounds;
-  constexpr int NENT = kWaves * 4;                   // lane groups per workgroup
+// Merge the S <= kMaxSplits published split partials of query head h, elements e4 .. e4+3,
+// in split order (independent of timing); all loads go out before the first is used.
+__device__ __forceinline__ float4 combine_splits(DevRef D, int S, int h, int e4) {
+  const size_t p_base = (size_t)h * kMaxSplits;
+  float4 ml[kMaxSplits], po[kMaxSplits];
+#pragma unroll
+  for (int j = 0; j < kMaxSplits; ++j) {
+    if (j < S) {                                       // uniform
+      ml[j] = sub4(D.part_ml, (int)((p_base + j) * 4));
+      po[j] = sub4(D.part_o, (int)((p_base + j) * D.hd + e4));
+    } else {
+      ml[j] = po[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  float M = kNegBig;
+#pragma unroll
+  for (int j = 0; j < kMaxSplits; ++j) M = fmaxf(M, j < S ? ml[j].x : kNegBig);
+  float Lsum = 0.f;
+  float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int j = 0; j < kMaxSplits; ++j) {
+    const float cj = j < S ? __builtin_amdgcn_exp2f(ml[j].x - M) : 0.f;
+    Lsum = fmaf(ml[j].y, cj, Lsum);
+    O.x = fmaf(po[j].x, cj, O.x); O.y = fmaf(po[j].y, cj, O.y);
+    O.z = fmaf(po[j].z, cj, O.z); O.w = fmaf(po[j].w, cj, O.w);
+  }
+  return make_float4(O.x / Lsum, O.y / Lsum, O.z / Lsum, O.w / Lsum);
+}
+
+// Stage the attention output for the output projection: a copy of the finished vector
+// (one split), or the merge of the split partials, done by every workgroup for itself --
+// that costs the consumers some more loads but no extra hand-over between workgroups.
+__device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, float *xl) {
+  const int S = A.n_splits, n = D.nq * D.hd;
+  if (S == 1) {
+    stage_copy(D.obuf, n, xl);
+    return;
+  }
+  lds_barrier();
+  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4)
+    *(float4 *)(xl + i) = combine_splits(D, S, i / D.hd, i % D.hd);
+  lds_barrier();
+}
+
+template <int DT, int EL>
+__device__ __forceinline__ void attn_items(DevRef D, const StepArgs &A, int l, float *lds, int lane,
+                                           AttnPre<DT, EL> &c) {
+  typedef AttnShape<DT, EL> SH;
+  constexpr int RU = SH::RU, NENT = SH::NENT, CH = SH::CH;
   const int hd = D.hd;                               // == 16 * EL
   const int S = A.n_splits;
-  const int lane = threadIdx.x & 63, wv = wave_in_wg();
+  const int wv = wave_in_wg();
   const int slot = lane >> 4, dl = lane & 15;
   const int kvd = D.nkv * hd;
   const float qs = 1.4426950408889634f / sqrtf((float)hd);    // log2(e) / sqrt(hd)
-  float *mo_o = lds;                                 // [NENT][G][hd]
-  float *mo_ml = lds + (size_t)NENT * G * hd;        // [NENT][G][2]
-  // A kv head with more than 4 query heads is served as several "virtual" kv heads of G
-  // query heads each (they stream the same K/V rows again).
-  const int npass = (D.nq / D.nkv) / G;
-  for (int item = blockIdx.x; item < D.nkv * npass * S; item += gridDim.x) {
-    const AttnItem it = attn_item<G>(D, A, item);
+  float *mo_o = lds;                                 // [kWaves][hd]
+  float *mo_ml = lds + (size_t)kWaves * hd;          // [kWaves][2]
+  for (int item = blockIdx.x; item < D.nq * S; item += gridDim.x) {
+    const AttnItem it = attn_item(D, A, item);
     int pb = it.p0 + wv * 4;
-    if (item != (int)blockIdx.x) attn_load_chunk<DT, EL>(D, A, l, it, pb, cur);   // not prefetched
+    if (item != (int)blockIdx.x) attn_prefetch<DT, EL>(D, A, l, item, lane, c);   // not fetched ahead
     RIVER_MARK(D, 0);
-    float q[G][EL], o[G][EL], m[G], ls[G];
+    // q of the head and this token's own k, v (one lane group of the split that holds the
+    // current position): a2's rotation at this position, then k, v rounded to the cache
+    // dtype.  The first query head of a kv head also stores them in slot (l, pos) -- the
+    // same slot for backbone and river -- for the tokens to come.  The own position then
+    // seeds that lane group's running softmax, so the loop over cached positions has no
+    // special case.
+    const bool own = A.pos >= it.p0 && A.pos < it.p1 && ((A.pos - it.p0) & (NENT - 1)) == wv * 4 + slot;
+    float q[EL], o[EL], m, ls;
+    float kf0[EL], vf0[EL];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      m[g] = kNegBig; ls[g] = 0.f;
+    for (int e = 0; e < EL; e += 4) {
+      const float4 t = sub4(D.qbuf, it.h * hd + dl * EL + e);
+      q[e] = t.x; q[e + 1] = t.y; q[e + 2] = t.z; q[e + 3] = t.w;
+    }
+    if (own) {
 #pragma unroll
       for (int e = 0; e < EL; e += 4) {
-        const float4 t = sub4(D.qbuf, (it.vh * G + g) * hd + dl * EL + e);
-        q[g][e] = t.x * qs; q[g][e + 1] = t.y * qs; q[g][e + 2] = t.z * qs; q[g][e + 3] = t.w * qs;
+        const float4 t = sub4(D.kvcur, it.kvh * hd + dl * EL + e);
+        kf0[e] = t.x; kf0[e + 1] = t.y; kf0[e + 2] = t.z; kf0[e + 3] = t.w;
+        const float4 u = sub4(D.kvcur, kvd + it.kvh * hd + dl * EL + e);
+        vf0[e] = u.x; vf0[e + 1] = u.y; vf0[e + 2] = u.z; vf0[e + 3] = u.w;
       }
+    }
+    rope_rotate<EL>(q, c.cs, dl >= 8);
 #pragma unroll
-      for (int e = 0; e < EL; ++e) o[g][e] = 0.f;
+    for (int e = 0; e < EL; ++e) q[e] *= qs;
+    m = kNegBig; ls = 0.f;
+#pragma unroll
+    for (int e = 0; e < EL; ++e) o[e] = 0.f;
+    if (own) {
+      rope_rotate<EL>(kf0, c.cs, dl >= 8);
+      KV<DT, EL> tk, tv;
+      tk.from(kf0); tk.unpack(kf0);
+      tv.from(vf0); tv.unpack(vf0);
+      if (it.h % (D.nq / D.nkv) == 0) {
+        // byte offset of this lane's elements in cache slot (l, pos) of the kv head
+        const size_t slot_off = (((size_t)l * D.max_seq + A.pos) * kvd + (size_t)it.kvh * hd + dl * EL) *
+                                sizeof(typename Store<DT>::T);
+        tk.store((char *)D.kcache + slot_off);
+        tv.store((char *)D.vcache + slot_off);
+      }
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) d = fmaf(q[e], kf0[e], d);
+      m = row16_sum(d);
+      ls = 1.f;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) o[e] = vf0[e];
     }
     RIVER_MARK_SYNC(D, 5);
-    for (; pb < it.p1; pb += NENT * RU) {
-      // position by position: scores of the G heads, online softmax update, weighted V.
-      // This token's own K/V replaces the cache row of the current position.
+    // one chunk: scores of its RU positions, one rescale, then the weighted V rows
+    auto consume = [&](const KVChunk<DT, EL> &ck, int pbase) {
+      float sc[RU];
+      float mn = m;
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
-        const int p = pb + u * NENT + slot;
-        const bool ok = p < it.p1, own = p == A.pos;
+        const int p = pbase + u * NENT + slot;
+        const bool ok = p < it.p1 && p != A.pos;       // the own position is already in (m, ls, o)
         float kf[EL];
-        cur.k[u].unpack(kf);
-        if (own) {
+        ck.k[u].unpack(kf);
+        float d = 0.f;
 #pragma unroll
-          for (int e = 0; e < EL; e += 4) {
-            const float4 t = sub4(D.kvcur, it.kvh * hd + dl * EL + e);
-            kf[e] = t.x; kf[e + 1] = t.y; kf[e + 2] = t.z; kf[e + 3] = t.w;
-          }
-        }
-        float cg[G], pg[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float d = 0.f;
-#pragma unroll
-          for (int e = 0; e < EL; ++e) d = fmaf(q[g][e], kf[e], d);
-          d = row16_sum(d);
-          const float sc = ok ? d : kNegBig;
-          const float mn = fmaxf(m[g], sc);
-          cg[g] = __builtin_amdgcn_exp2f(m[g] - mn);              // <= 1; 1 while nothing seen
-          pg[g] = ok ? __builtin_amdgcn_exp2f(sc - mn) : 0.f;
-          ls[g] = fmaf(ls[g], cg[g], pg[g]);
-          m[g] = mn;
-        }
-        float vf[EL];
-        cur.v[u].unpack(vf);
-        if (own) {
-#pragma unroll
-          for (int e = 0; e < EL; e += 4) {
-            const float4 t = sub4(D.kvcur, kvd + it.kvh * hd + dl * EL + e);
-            vf[e] = t.x; vf[e + 1] = t.y; vf[e + 2] = t.z; vf[e + 3] = t.w;
-          }
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-          for (int e = 0; e < EL; ++e) o[g][e] = fmaf(o[g][e], cg[g], pg[g] * vf[e]);
-        // keep the positions apart: interleaving all of them costs > 100 more registers
-        __builtin_amdgcn_sched_barrier(0);
+        for (int e = 0; e < EL; ++e) d = fmaf(q[e], kf[e], d);
+        d = row16_sum(d);
+        sc[u] = ok ? d : kNegBig;
+        mn = fmaxf(mn, sc[u]);
       }
-      if (pb + NENT * RU < it.p1) attn_load_chunk<DT, EL>(D, A, l, it, pb + NENT * RU, cur);
+      const float cg = __builtin_amdgcn_exp2f(m - mn);    // <= 1; 1 while nothing seen
+      ls *= cg;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) o[e] *= cg;
+      m = mn;
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const float pg = sc[u] > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(sc[u] - mn) : 0.f;
+        ls += pg;
+        float vf[EL];
+        ck.v[u].unpack(vf);
+#pragma unroll
+        for (int e = 0; e < EL; ++e) o[e] = fmaf(pg, vf[e], o[e]);
+      }
+    };
+    for (; pb < it.p1; pb += 2 * CH) {
+      consume(c.a, pb);
+      if (pb + 2 * CH < it.p1) attn_load_chunk<DT, EL>(D, A, l, it, pb + 2 * CH, lane, c.a);
+      if (pb + CH < it.p1) {
+        consume(c.b, pb + CH);
+        if (pb + 3 * CH < it.p1) attn_load_chunk<DT, EL>(D, A, l, it, pb + 3 * CH, lane, c.b);
+      }
     }
     RIVER_MARK(D, 1);
+    // the four lane groups of the wavefront -> one (lanes 16, 32 apart hold the same elements)
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float m2 = __shfl_xor(m, off), l2 = __shfl_xor(ls, off);
+      const float mn = fmaxf(m, m2);
+      const float c1 = __builtin_amdgcn_exp2f(m - mn), c2 = __builtin_amdgcn_exp2f(m2 - mn);
+      ls = ls * c1 + l2 * c2;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) o[e] = o[e] * c1 + __shfl_xor(o[e], off) * c2;
+      m = mn;
+    }
     lds_barrier();                        // merge area free (previous item fully consumed)
-    {
-      const int en = wv * 4 + slot;
+    if (slot == 0) {
+      float *w = mo_o + wv * hd + dl * EL;
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float *w = mo_o + ((size_t)en * G + g) * hd + dl * EL;
-#pragma unroll
-        for (int e = 0; e < EL; e += 4) *(float4 *)(w + e) = make_float4(o[g][e], o[g][e + 1], o[g][e + 2], o[g][e + 3]);
-        if (dl == 0) *(float2 *)(mo_ml + ((size_t)en * G + g) * 2) = make_float2(m[g], ls[g]);
-      }
+      for (int e = 0; e < EL; e += 4) *(float4 *)(w + e) = make_float4(o[e], o[e + 1], o[e + 2], o[e + 3]);
+      if (dl == 0) *(float2 *)(mo_ml + wv * 2) = make_float2(m, ls);
     }
     RIVER_MARK(D, 2);
     lds_barrier();
     RIVER_MARK(D, 3);
-    // lane groups of all wavefronts -> one partial per (head, split, g), fixed order
-    for (int idx = threadIdx.x; idx < G * hd; idx += blockDim.x) {
-      const int g = idx / hd, e = idx % hd;
-      float M = kNegBig, Lsum = 0.f, O = 0.f;
+    // the wavefronts -> one partial per (head, split), fixed order
+    if ((int)threadIdx.x < hd) {
+      const int e = threadIdx.x;
+      float2 ml[kWaves];
+      float ov[kWaves];
+      float M = kNegBig;
 #pragma unroll
-      for (int e0 = 0; e0 < NENT; e0 += 8) {                        // batches of 8 entries, running max
-        float2 ml[8];
-        float ov[8];
-        float mb = M;
+      for (int j = 0; j < kWaves; ++j) {
+        ml[j] = *(const float2 *)(mo_ml + j * 2);
+        ov[j] = mo_o[j * hd + e];
+        M = fmaxf(M, ml[j].x);
+      }
+      float Lsum = 0.f, O = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          ml[j] = *(const float2 *)(mo_ml + ((size_t)(e0 + j) * G + g) * 2);
-          ov[j] = mo_o[((size_t)(e0 + j) * G + g) * hd + e];
-          mb = fmaxf(mb, ml[j].x);
-        }
-        const float cb = __builtin_amdgcn_exp2f(M - mb);
-        Lsum *= cb; O *= cb;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float c = __builtin_amdgcn_exp2f(ml[j].x - mb);     // entries that saw nothing have sum 0
-          Lsum = fmaf(ml[j].y, c, Lsum);
-          O = fmaf(ov[j], c, O);
-        }
-        M = mb;
+      for (int j = 0; j < kWaves; ++j) {
+        const float cj = __builtin_amdgcn_exp2f(ml[j].x - M);       // entries that saw nothing have sum 0
+        Lsum = fmaf(ml[j].y, cj, Lsum);
+        O = fmaf(ov[j], cj, O);
       }
       if (S == 1) {
-        pub(D.obuf + (it.vh * G + g) * hd + e, O / Lsum);
+        pub(D.obuf + it.h * hd + e, O / Lsum);
       } else {
-        const size_t pi = ((size_t)it.vh * kMaxSplits + it.sp) * G + g;
+        const size_t pi = (size_t)it.h * kMaxSplits + it.sp;
         pub(D.part_o + pi * hd + e, O);
         if (e == 0) { pub(D.part_ml + pi * 4, M); pub(D.part_ml + pi * 4 + 1, Lsum); }
       }
     }
     RIVER_MARK(D, 4);
-    // splits -> final output, by whichever workgroup of this head finishes last
-    if (S > 1 && last_arriver(&D.st->attn_cnt[it.vh], (unsigned)S, lds_flag(D, lds))) {
-      for (int idx = threadIdx.x; idx < G * (hd >> 2); idx += blockDim.x) {
-        const int g = idx / (hd >> 2), e4 = (idx % (hd >> 2)) * 4;
-        const size_t p_base = ((size_t)it.vh * kMaxSplits) * G + g;
-        float M = kNegBig, Lsum = 0.f;
-        float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int s0 = 0; s0 < S; s0 += kCombine) {
-          float4 ml[kCombine], po[kCombine];
-#pragma unroll
-          for (int j = 0; j < kCombine; ++j) {
-            const size_t pi = p_base + (size_t)min(s0 + j, S - 1) * G;
-            ml[j] = sub4(D.part_ml, (int)(pi * 4));
-            po[j] = sub4(D.part_o, (int)(pi * hd + e4));
-          }
-#pragma unroll
-          for (int j = 0; j < kCombine; ++j) {
-            const bool use = s0 + j < S;
-            const float pm = use ? ml[j].x : kNegBig;
-            const float mn = fmaxf(M, pm);
-            const float c1 = __builtin_amdgcn_exp2f(M - mn);
-            const float c2 = use ? __builtin_amdgcn_exp2f(pm - mn) : 0.f;
-            Lsum = Lsum * c1 + ml[j].y * c2;
-            O.x = O.x * c1 + po[j].x * c2; O.y = O.y * c1 + po[j].y * c2;
-            O.z = O.z * c1 + po[j].z * c2; O.w = O.w * c1 + po[j].w * c2;
-            M = mn;
-          }
-        }
-        float *dst = D.obuf + (it.vh * G + g) * hd + e4;
-        pub(dst, O.x / Lsum); pub(dst + 1, O.y / Lsum); pub(dst + 2, O.z / Lsum); pub(dst + 3, O.w / Lsum);
-      }
-    }
   }
 }
 
-// Dispatch on the two shape parameters that size register arrays: query heads per kv head
-// (1, 2, or multiples of 4 in passes of 4) and elements per lane (head_dim 64 or 128).
-// f is called as f(integral_constant G, integral_constant EL).
-template <int V> struct IC { static constexpr int value = V; };
-template <class F>
-__device__ __forceinline__ void attn_dispatch(const Dev &D, F f) {
-  const int gq = D.nq / D.nkv;
-  if (D.hd == 128) {
-    if (gq == 1) f(IC<1>(), IC<8>()); else if (gq == 2) f(IC<2>(), IC<8>()); else f(IC<4>(), IC<8>());
-  } else {
-    if (gq == 1) f(IC<1>(), IC<4>()); else if (gq == 2) f(IC<2>(), IC<4>()); else f(IC<4>(), IC<4>());
-  }
-}
-
-// The attention phase with the device-wide barrier in front of it (k == 0: none, the
-// one-kernel-per-phase mode): the first K/V chunk is issued between arriving and waiting.
+// The attention phase with the device-wide barrier in front of it (in the one-kernel-per-
+// phase mode arrive and wait do nothing): what can be fetched ahead is issued between
+// arriving and waiting.  Register arrays are sized by the elements per lane (head_dim 64
+// or 128).
 template <int DT, class Arrive, class Wait>
-__device__ __forceinline__ void phase_attn(const Dev &D, const StepArgs &A, int l, float *lds,
+__device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, float *lds,
                                            Arrive arrive, Wait wait) {
-  attn_dispatch(D, [&](auto g, auto el) {
-    constexpr int G = decltype(g)::value, EL = decltype(el)::value;
-    KVChunk<DT, EL> c;
-    const bool poller = false;
+  const int lane = fresh_lane();
+  auto run = [&](auto el) {
+    constexpr int EL = decltype(el)::value;
+    AttnPre<DT, EL> c;
     arrive();
-    if (!poller) attn_prefetch<DT, G, EL>(D, A, l, c);
+    attn_prefetch<DT, EL>(D, A, l, blockIdx.x, lane, c);
     wait();
-    if (poller) attn_prefetch<DT, G, EL>(D, A, l, c);
-    attn_items<DT, G, EL>(D, A, l, lds, c);
-  });
+    attn_items<DT, EL>(D, A, l, lds, lane, c);
+  };
+  if (D.hd == 128) run(IC<8>()); else run(IC<4>());
 }
 
 // a4: h1 = h + W_o o
 template <int DT>
-__device__ __forceinline__ void phase_oproj(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
-  stage_copy(D.obuf, D.nq * D.hd, lds);
+__device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+  stage_attn_out(D, A, lds);
   const float *hin = D.hidden + (size_t)l * D.d;
-  const int lane = threadIdx.x & 63;
-  auto epi = [&](int k, float a, float b) {
-    if (lane < 2) {
-      const int r = 2 * k + lane;
-      pub(D.h1 + r, sub(hin + r) + (lane ? b : a));
-    }
+  const int lane = pre.lane;
+  auto epi = [&](int n0, auto &acc) {
+    constexpr int R = sizeof(acc) / sizeof(float);
+    const int n = n0 + lane;
+    if (lane < R && n < D.d) pub(D.h1 + n, sub(hin + n) + pick<R>(acc, lane));
   };
-  run_phase<DT>(D, l, PH_O, river, lds, pre, epi);
+  run_phase<DT, PH_O>(D, l, river, lds, pre, epi);
 }
 
-// a5: y = RMSNorm(h1) * g2; a = silu(W_g y) * (W_u y)
+// a5: y = RMSNorm(h1) * g2; a = silu(W_g y) * (W_u y); rows come as (gate i, up i) pairs
 template <int DT>
-__device__ __forceinline__ void phase_gateup(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
-  stage_norm<DT>(D.h1, D.layers[l].ffn_norm, D.d, D.eps, lds, lds_red(D, lds));
-  const int lane = threadIdx.x & 63;
-  auto epi = [&](int r, float g, float u) {
-    if (lane == 0) pub(D.abuf + r, g / (1.0f + expf(-g)) * u);
+__device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+  stage_norm<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lds, lds_red(D, lds));
+  const int lane = pre.lane;
+  auto epi = [&](int n0, auto &acc) {
+    constexpr int R = sizeof(acc) / sizeof(float);
+    static_assert(R % 2 == 0, "gate/up tasks hold whole (gate, up) pairs");
+    float gv = acc[0], uv = acc[1];
+#pragma unroll
+    for (int k = 1; k < R / 2; ++k) { gv = lane == k ? acc[2 * k] : gv; uv = lane == k ? acc[2 * k + 1] : uv; }
+    const int i = (n0 >> 1) + lane;
+    if (lane < R / 2 && i < D.ffn) pub(D.abuf + i, gv / (1.0f + expf(-gv)) * uv);
   };
-  run_phase<DT>(D, l, PH_GU, river, lds, pre, epi);
+  run_phase<DT, PH_GU>(D, l, river, lds, pre, epi);
 }
 
 // a6: h2 = h1 + W_d a, published as h(l+1); on backbone blocks also the three sums of
@@ -1128,22 +1225,23 @@ __device__ __forceinline__ void phase_gateup(const Dev &D, const StepArgs &A, in
 // reduction over workgroups and the exit decision are taken by every workgroup at the
 // start of the next block (exit_test), so no workgroup waits for another here.
 template <int DT>
-__device__ __forceinline__ void phase_down(const Dev &D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+__device__ __forceinline__ void phase_down(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   stage_copy(D.abuf, D.ffn, lds);
   const float *hin = D.hidden + (size_t)l * D.d;
   float *hout = D.hidden + (size_t)(l + 1) * D.d;
-  const int lane = threadIdx.x & 63;
+  const int lane = pre.lane;
   float ab = 0.f, aa = 0.f, bb = 0.f;
-  auto epi = [&](int k, float a, float b) {
-    if (lane < 2) {
-      const int r = 2 * k + lane;
-      const float h0 = sub(hin + r);
-      const float h2 = sub(D.h1 + r) + (lane ? b : a);
-      pub(hout + r, h2);
+  auto epi = [&](int n0, auto &acc) {
+    constexpr int R = sizeof(acc) / sizeof(float);
+    const int n = n0 + lane;
+    if (lane < R && n < D.d) {
+      const float h0 = sub(hin + n);
+      const float h2 = sub(D.h1 + n) + pick<R>(acc, lane);
+      pub(hout + n, h2);
       ab = fmaf(h0, h2, ab); aa = fmaf(h0, h0, aa); bb = fmaf(h2, h2, bb);
     }
   };
-  run_phase<DT>(D, l, PH_DOWN, river, lds, pre, epi);
+  run_phase<DT, PH_DOWN>(D, l, river, lds, pre, epi);
   if (river) return;                    // river blocks take no exit test
   float *red = lds_red(D, lds);
   ab = block_sum(ab, red); aa = block_sum(aa, red); bb = block_sum(bb, red);
@@ -1156,8 +1254,9 @@ __device__ __forceinline__ void phase_down(const Dev &D, const StepArgs &A, int 
 
 // a9 + a10: logits = W_head RMSNorm(h(L)) * g_f; greedy token (lowest index on ties);
 // the step's record.
+constexpr int kRD = 2, kUD = 4;      // LM head: two rows x four granules per step
 template <int DT>
-__device__ __forceinline__ void head_rows(const Dev &D, int t, Rows<kRD> &rw) {
+__device__ __forceinline__ void head_rows(DevRef D, int t, Rows<kRD> &rw) {
 #pragma unroll
   for (int r = 0; r < kRD; ++r) {
     rw.p[r] = (const char *)D.lm_head +
@@ -1166,21 +1265,21 @@ __device__ __forceinline__ void head_rows(const Dev &D, int t, Rows<kRD> &rw) {
   }
 }
 template <int DT>
-__device__ __forceinline__ void prefetch_head(const Dev &D, Pre<DT> &g, int which = 3) {
+__device__ __forceinline__ void prefetch_head(DevRef D, Pre<DT> &g, int which = 3) {
   auto rows_of = [&](int t, Rows<kRD> &rw) { head_rows<DT>(D, t, rw); };
   const int n = (D.vocab + kRD - 1) / kRD;
-  if (which & 1) issue_seq<Dense<DT, kRD>, DT, kRD>(0, n, D.d, D.group, g.a, rows_of);
-  if (which & 2) issue_seq<Dense<DT, kRD>, DT, kRD>(1, n, D.d, D.group, g.b, rows_of);
+  if (which & 1) issue_seq<Dense<DT, kRD, kUD>, DT, kRD>(0, n, D.d, D.group, g.a, g.lane, rows_of);
+  if (which & 2) issue_seq<Dense<DT, kRD, kUD>, DT, kRD>(1, n, D.d, D.group, g.b, g.lane, rows_of);
 }
 template <int DT>
-__device__ __forceinline__ void phase_head(const Dev &D, const StepArgs &A, const Ctl &ctl, float *lds, Pre<DT> &pre) {
+__device__ __forceinline__ void phase_head(DevRef D, const StepArgs &A, const Ctl &ctl, float *lds, Pre<DT> &pre) {
   float *red = lds_red(D, lds);
   if (!ctl.river && A.rec_slot >= 0) {      // similarity of the last backbone block: recorded, never tested
     const float s = similarity_from_partials(D, red);
     if (blockIdx.x == 0 && threadIdx.x == 0) D.rec_sims[(size_t)A.rec_slot * D.L + (D.L - 1)] = s;
   }
   stage_norm<DT>(D.hidden + (size_t)D.L * D.d, D.final_norm, D.d, D.eps, lds, red);
-  const int lane = threadIdx.x & 63;
+  const int lane = pre.lane;
   float best = -INFINITY;
   int besti = 0x7fffffff;
   auto rows_of = [&](int t, Rows<kRD> &rw) { head_rows<DT>(D, t, rw); };
@@ -1194,7 +1293,7 @@ __device__ __forceinline__ void phase_head(const Dev &D, const StepArgs &A, cons
       }
     }
   };
-  stream_tasks<Dense<DT, kRD>, DT, kRD>((D.vocab + kRD - 1) / kRD, D.d, D.group, lds, pre, rows_of, epi);
+  stream_tasks<Dense<DT, kRD, kUD>, DT, kRD>((D.vocab + kRD - 1) / kRD, D.d, D.group, lds, pre, rows_of, epi);
   block_argmax(best, besti, red);
   if (threadIdx.x == 0) {
     pub(D.amax_val + blockIdx.x, best);
@@ -1217,7 +1316,7 @@ __device__ __forceinline__ void phase_head(const Dev &D, const StepArgs &A, cons
 }
 
 // Start-of-token state: exit position 0 (everything in the river) only when forced.
-__device__ __forceinline__ Ctl ctl_init(const Dev &D, const StepArgs &A) {
+__device__ __forceinline__ Ctl ctl_init(DevRef D, const StepArgs &A) {
   Ctl c;
   c.river = (A.forced_e == 0);
   c.exit_pos = c.river ? 0 : D.L;
@@ -1225,7 +1324,7 @@ __device__ __forceinline__ Ctl ctl_init(const Dev &D, const StepArgs &A) {
 }
 
 // NaN in the record for blocks that run as river twins (no similarity there).
-__device__ __forceinline__ void record_init(const Dev &D, const StepArgs &A) {
+__device__ __forceinline__ void record_init(DevRef D, const StepArgs &A) {
   if (blockIdx.x == 0 && A.rec_slot >= 0)
     for (int i = threadIdx.x; i < D.L; i += blockDim.x)
       D.rec_sims[(size_t)A.rec_slot * D.L + i] = __uint_as_float(0x7fc00000u);

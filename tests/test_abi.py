@@ -38,6 +38,12 @@ def test_host_side_validation_needs_no_gpu():
     bad = binding.make_config(configs.TINY.with_(river_group=24))
     assert lib.river_workspace_bytes(ctypes.byref(bad)) == 0
     assert lib.river_workspace_bytes(None) == 0
+    # the one-launch mode is offered for bf16 only
+    bad = binding.make_config(configs.TINY, exec_mode=binding.EXEC_PERSISTENT)
+    assert lib.river_workspace_bytes(ctypes.byref(bad)) == 0
+    ok = binding.make_config(configs.TINY.with_(dtype=configs.DTYPE_BF16), exec_mode=binding.EXEC_PERSISTENT)
+    assert lib.river_workspace_bytes(ctypes.byref(ok)) > 0
+    bad = binding.make_config(configs.TINY.with_(river_group=24))
     h = ctypes.c_void_p()
     assert lib.river_create(ctypes.byref(bad), None, None, None, 0, None, ctypes.byref(h)) == binding.RIVER_EINVAL
     assert b"river_group" in lib.river_last_error(None)

@@ -22,6 +22,15 @@ MODES = [binding.EXEC_KERNELS, binding.EXEC_PERSISTENT]
 MODE_IDS = ["kernels", "persistent"]
 
 TINY_BF16 = configs.TINY.with_(name="tiny-bf16", dtype=configs.DTYPE_BF16)
+TINY_BOTH = [configs.TINY, TINY_BF16]
+
+
+def needs_mode(cfg, mode):
+    """The one-launch mode is switched off for fp32 in the library (river_create refuses it):
+    its fp32 instantiation once faulted on the GPU at the mid shape and no cause could be
+    shown, so that combination stays off the GPU; fp32 is covered in the kernels mode."""
+    if mode == binding.EXEC_PERSISTENT and cfg.dtype == configs.DTYPE_F32:
+        pytest.skip("one-launch mode is bf16-only: unexplained GPU fault of its fp32 instantiation")
 # spans several wavefront tiles with ragged tails: 2816 columns = 1 full + 1 partial
 # 2048-code wave load, vocab not a multiple of the 4-row task, 3 splits of attention
 MID = configs.ModelConfig("mid-bf16", 3, 1024, 8, 2, 128, 2816, 1002, 500000.0, 1e-5,
@@ -137,9 +146,11 @@ def test_river_construction_bit_exact(dtype):
 
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("tau", [0.9, 0.675, 0.52])
-def test_c1_threshold_mode(mode, tau):
-    say(f"C1 threshold tau={tau} mode={mode}")
-    cfg = configs.TINY.with_(tau=tau)
+@pytest.mark.parametrize("cfg0", TINY_BOTH, ids=lambda c: c.name)
+def test_c1_threshold_mode(mode, tau, cfg0):
+    needs_mode(cfg0, mode)
+    say(f"C1 threshold {cfg0.name} tau={tau} mode={mode}")
+    cfg = cfg0.with_(tau=tau)
     w = inputs.make_weights(cfg, configs.C1.seed_weights)
     pair = Pair(cfg, w, mode)
     prompt = inputs.make_prompt(cfg.vocab, configs.C1.prompt_len, configs.C1.seed_prompt)
@@ -155,6 +166,7 @@ def test_c1_threshold_mode(mode, tau):
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
 def test_forced_mixed_schedule_all_depths(mode, cfg0):
+    needs_mode(cfg0, mode)
     say(f"forced schedule {cfg0.name} mode={mode}")
     cfg = cfg0.with_(min_exit_layer=0)
     w = inputs.make_weights(cfg, 21)
@@ -167,11 +179,13 @@ def test_forced_mixed_schedule_all_depths(mode, cfg0):
 
 
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
-def test_never_exit_equals_dense_bitwise(mode):
+@pytest.mark.parametrize("cfg0", TINY_BOTH, ids=lambda c: c.name)
+def test_never_exit_equals_dense_bitwise(mode, cfg0):
     """tau >= 1 and exit forced at L run no river block: logits identical to a context
     that has no river at all."""
-    say(f"never-exit mode={mode}")
-    cfg = configs.TINY
+    needs_mode(cfg0, mode)
+    say(f"never-exit {cfg0.name} mode={mode}")
+    cfg = cfg0
     w = inputs.make_weights(cfg, configs.C1.seed_weights)
     dw = binding.upload_weights(w)
     dr = binding.quantize_river(cfg, dw)
@@ -197,6 +211,7 @@ def test_never_exit_equals_dense_bitwise(mode):
 def test_lossless_river_equals_dense(mode, cfg0):
     """Block matrices on the 4-bit grid: the twin equals the backbone, so any schedule
     reproduces the dense run (traversal + shared cache slots, no quantisation error)."""
+    needs_mode(cfg0, mode)
     say(f"lossless river {cfg0.name} mode={mode}")
     cfg = cfg0.with_(min_exit_layer=1)
     w = grid_model(cfg, 31)
@@ -221,11 +236,13 @@ def test_lossless_river_equals_dense(mode, cfg0):
 
 
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
-def test_kv_canary_every_slot_written(mode):
+@pytest.mark.parametrize("cfg0", TINY_BOTH, ids=lambda c: c.name)
+def test_kv_canary_every_slot_written(mode, cfg0):
     """Intrinsic KV integrity: with the cache pre-filled with NaN, every slot (l, p < pos)
     is finite after the run (backbone or river wrote it) and no slot beyond pos was touched."""
-    say(f"KV canary mode={mode}")
-    cfg = configs.TINY.with_(tau=0.52)
+    needs_mode(cfg0, mode)
+    say(f"KV canary {cfg0.name} mode={mode}")
+    cfg = cfg0.with_(tau=0.52)
     w = inputs.make_weights(cfg, configs.C1.seed_weights)
     pair = Pair(cfg, w, mode)
     pair.g.fill_cache(0xFF)
@@ -244,10 +261,11 @@ def test_kv_canary_every_slot_written(mode):
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("cfg", [MID, MID_F32], ids=lambda c: c.name)
 def test_mid_shape_ragged_tiles(mode, cfg):
+    needs_mode(cfg, mode)
     say(f"mid shape {cfg.name} mode={mode}")
     w = inputs.make_weights(cfg, 77)
     pair = Pair(cfg, w, mode)
-    prompt = inputs.make_prompt(cfg.vocab, 130, 78)          # 3 attention splits, ragged
+    prompt = inputs.make_prompt(cfg.vocab, 130, 78)          # every wavefront of the attention workgroups busy, ragged
     sched = [1, 3, 2, 3, 1, 2, 3, 3, 1, 2]
     exits = run_teacher_forced(pair, prompt, len(sched), sched, cfg.name)
     assert exits == sched
@@ -258,7 +276,8 @@ def test_mid_shape_ragged_tiles(mode, cfg):
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
 def test_long_context_many_splits(mode, cfg0):
-    """Attention over 1100+ cached positions: 9 splits, combined in two batches."""
+    """Attention over 1100+ cached positions: 3 splits of 2 chunks, merged by the consumer."""
+    needs_mode(cfg0, mode)
     say(f"long context {cfg0.name} mode={mode}")
     cfg = cfg0.with_(max_seq=1200, tau=0.675)
     w = inputs.make_weights(cfg, configs.C1.seed_weights)
@@ -273,7 +292,7 @@ def test_long_context_many_splits(mode, cfg0):
 
 def test_async_steps_and_records_match_sync():
     say("async records")
-    cfg = configs.TINY.with_(tau=0.675)
+    cfg = TINY_BF16.with_(tau=0.675)                 # bf16: the one-launch mode
     w = inputs.make_weights(cfg, configs.C1.seed_weights)
     dw = binding.upload_weights(w)
     dr = binding.quantize_river(cfg, dw)
@@ -341,7 +360,7 @@ def test_barrier_wait_is_bounded():
     """A spin limit of one poll makes device-wide waits give up at once: the kernel must
     still run to completion and the host must report the time-out, not hang."""
     say("bounded barrier wait")
-    cfg = configs.TINY
+    cfg = TINY_BF16
     w = inputs.make_weights(cfg, 3)
     dw = binding.upload_weights(w)
     g = binding.River(cfg.with_(tau=2.0), dw, None, exec_mode=binding.EXEC_PERSISTENT, spin_limit=1)
