@@ -123,9 +123,10 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
   // block l (1-based) has just run: what will block l + 1 run as, as far as known now
   const bool guess = (l == 0) ? ctl.river : guess_river_after(A, ctl, l);
   if (l > 0) { barrier_arrive(D.st, k); TRACE_ARRIVE(); }
-  prefetch_phase<DT>(D, l, PH_QKV, guess, pre);
+  prefetch_phase<DT>(D, l, PH_QKV, guess, pre, l > 0 ? 0 : 2);
   if (l > 0) {
     barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+    prefetch_phase<DT>(D, l, PH_QKV, guess, pre, 1);
     exit_test(D, A, l, ctl, lds);
     if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
   }
@@ -144,8 +145,9 @@ __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, 
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
   Pre<DT> pre;
   barrier_arrive(D.st, k); TRACE_ARRIVE();
-  prefetch_phase<DT>(D, l, PH, river, pre);
+  prefetch_phase<DT>(D, l, PH, river, pre, 0);
   barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+  prefetch_phase<DT>(D, l, PH, river, pre, 1);
   if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre);
   else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre);
   else phase_down<DT>(D, A, l, river, lds, pre);
@@ -157,8 +159,9 @@ __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl
   const Ctl ctl = unpack_ctl(ctl_packed);
   Pre<DT> pre;
   barrier_arrive(D.st, k); TRACE_ARRIVE();
-  prefetch_head<DT>(D, pre);
+  prefetch_head<DT>(D, pre, 0);
   barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+  prefetch_head<DT>(D, pre, 1);
   phase_head<DT>(D, A, ctl, lds, pre);
 }
 
@@ -294,7 +297,8 @@ static int x_capacity(const river_config *c) {
   cap = std::max(cap, c->n_q_heads * c->head_dim);
   cap = std::max(cap, c->d_ffn);
   cap = std::max(cap, attn_lds_floats(c->head_dim));
-  return (int)align_up(cap, 4);
+  // the staged vector is stored granule-wise (64 lanes x up to 32 columns): whole granules
+  return (int)align_up(cap, 2048);
 }
 
 // [rows, cols] of block matrix m (wq wk wv wo w_gate w_up w_down)

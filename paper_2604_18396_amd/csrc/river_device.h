@@ -327,26 +327,38 @@ __device__ __forceinline__ int wave_count() { return gridDim.x * (blockDim.x >> 
 
 // -------------------------------------------------------------- staging x
 
-// xl[0..n) = h * rsqrt(mean(h^2) + eps) * gain   (fused RMSNorm prologue); h published
-// by other workgroups, n % 4 == 0.
+// The staged vector is not stored in column order.  A lane of the streaming engine owns a
+// run of P = 2^lp consecutive columns per lane load (4 or 8 dense elements, 16 or 32
+// codes) and reads them as P/4 float4; in column order the 64 lanes of a wavefront would
+// hit the same few LDS banks (lane stride P floats).  So, within each granule of 64 P
+// columns, float4 number q of every lane's run is stored lane after lane:
+//   column c -> granule base + (e / 4) * 256 + lane * 4 + e % 4,  lane = (c % 64P) / P, e = c % P
+// and a wavefront's read of float4 q covers 1 KB of consecutive addresses.
+__device__ __forceinline__ int x_slot(int c, int lp) {
+  const int P = 1 << lp;
+  return ((c >> (6 + lp)) << (6 + lp)) + (((c & (P - 1)) >> 2) << 8) + (((c >> lp) & 63) << 2) + (c & 3);
+}
+
+// xl = h * rsqrt(mean(h^2) + eps) * gain   (fused RMSNorm prologue), stored for runs of
+// 2^lp; h published by other workgroups, n % 4 == 0.
 template <int DT>
-__device__ __forceinline__ void stage_norm(const float *h, const void *gain, int n, float eps,
+__device__ __forceinline__ void stage_norm(const float *h, const void *gain, int n, float eps, int lp,
                                            float *xl, float *red) {
   float ss = 0.f;
   for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) {
     const float4 v = sub4(h, i);
-    *(float4 *)(xl + i) = v;
+    *(float4 *)(xl + x_slot(i, lp)) = v;
     ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
   }
   const float tot = block_sum(ss, red);
   const float r = 1.0f / sqrtf(tot / (float)n + eps);
   for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) {
-    float4 v = *(float4 *)(xl + i);
+    float4 v = *(float4 *)(xl + x_slot(i, lp));
     v.x = v.x * r * Store<DT>::ld(gain, i);
     v.y = v.y * r * Store<DT>::ld(gain, i + 1);
     v.z = v.z * r * Store<DT>::ld(gain, i + 2);
     v.w = v.w * r * Store<DT>::ld(gain, i + 3);
-    *(float4 *)(xl + i) = v;
+    *(float4 *)(xl + x_slot(i, lp)) = v;
   }
   lds_barrier();
 }
@@ -354,13 +366,13 @@ __device__ __forceinline__ void stage_norm(const float *h, const void *gain, int
 // Same, the source being row `tok` of the embedding table (block 1 of a token); also
 // publishes h(0) (each workgroup a slice) for the residual adds and the similarity.
 template <int DT>
-__device__ __forceinline__ void stage_norm_embed(DevRef D, int tok, const void *gain, float *xl,
+__device__ __forceinline__ void stage_norm_embed(DevRef D, int tok, const void *gain, int lp, float *xl,
                                                  float *red) {
   const int n = D.d;
   float ss = 0.f;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     const float v = Store<DT>::ld(D.tok_emb, (size_t)tok * n + i);
-    xl[i] = v;
+    xl[x_slot(i, lp)] = v;
     ss += v * v;
   }
   const int per = (n + gridDim.x - 1) / gridDim.x;
@@ -368,13 +380,13 @@ __device__ __forceinline__ void stage_norm_embed(DevRef D, int tok, const void *
     pub(D.hidden + i, Store<DT>::ld(D.tok_emb, (size_t)tok * n + i));
   const float tot = block_sum(ss, red);
   const float r = 1.0f / sqrtf(tot / (float)n + D.eps);
-  for (int i = threadIdx.x; i < n; i += blockDim.x) xl[i] = xl[i] * r * Store<DT>::ld(gain, i);
+  for (int i = threadIdx.x; i < n; i += blockDim.x) xl[x_slot(i, lp)] = xl[x_slot(i, lp)] * r * Store<DT>::ld(gain, i);
   lds_barrier();
 }
 
-__device__ __forceinline__ void stage_copy(const float *src, int n, float *xl) {
+__device__ __forceinline__ void stage_copy(const float *src, int n, int lp, float *xl) {
   lds_barrier();
-  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) *(float4 *)(xl + i) = sub4(src, i);
+  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) *(float4 *)(xl + x_slot(i, lp)) = sub4(src, i);
   lds_barrier();
 }
 
@@ -399,37 +411,40 @@ template <int R> struct Rows {
 template <int DT, int R, int U> struct Dense {
   static_assert(R * U <= kNL, "a step holds at most kNL lane loads");
   static constexpr int EPL = Store<DT>::EPL;
+  static constexpr int SUB = (R * U * 2 <= kNL) ? 2 : 1;      // steps that fit one register set
   static __device__ __forceinline__ int steps(int cols) {
     const int row_bytes = cols * (int)sizeof(typename Store<DT>::T);
     return (row_bytes + U * 1024 - 1) / (U * 1024);
   }
-  static __device__ __forceinline__ void issue(Regs<DT> &g, const Rows<R> &rw, int cols, int group, int step,
-                                               int lane) {
+  // `base`: first load slot of the register set to use (0, or kNL/2 for the second half)
+  static __device__ __forceinline__ void issue(Regs<DT> &g, int base, const Rows<R> &rw, int cols, int group,
+                                               int step, int lane) {
     const int row_bytes = cols * (int)sizeof(typename Store<DT>::T);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int off = (step * U + u) * 1024 + lane * 16;
 #pragma unroll
       for (int r = 0; r < R; ++r)
-        g.w[r * U + u] = off < row_bytes ? ld_stream16(rw.p[r] + off) : make_uint4(0, 0, 0, 0);
+        g.w[base + r * U + u] = off < row_bytes ? ld_stream16(rw.p[r] + off) : make_uint4(0, 0, 0, 0);
     }
   }
-  static __device__ __forceinline__ void fma(const Regs<DT> &g, int cols, int group, int step,
+  static __device__ __forceinline__ void fma(const Regs<DT> &g, int base, int cols, int group, int step,
                                              const float *xl, float (&acc)[R], int lane) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int c = ((step * U + u) * 64 + lane) * EPL;
+      const int gb = (step * U + u) * 64 * EPL;            // granule base; see x_slot
+      const int c = gb + lane * EPL;
       if (c < cols) {
         float x[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; e += 4) {
-          const float4 t = *(const float4 *)(xl + c + e);
+          const float4 t = *(const float4 *)(xl + gb + e * 64 + lane * 4);
           x[e] = t.x; x[e + 1] = t.y; x[e + 2] = t.z; x[e + 3] = t.w;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           float f[EPL];
-          Store<DT>::unpack(g.w[r * U + u], f);
+          Store<DT>::unpack(g.w[base + r * U + u], f);
 #pragma unroll
           for (int e = 0; e < EPL; ++e) acc[r] = fmaf(f[e], x[e], acc[r]);
         }
@@ -445,11 +460,12 @@ template <int DT, int R, int U> struct Dense {
 // a group.
 template <int DT, int R, int U, int CPL> struct W4 {
   static_assert(R * U <= kNL, "a step holds at most kNL lane loads");
+  static constexpr int SUB = (R * U * 2 <= kNL) ? 2 : 1;      // steps that fit one register set
   static __device__ __forceinline__ int steps(int cols) {
     return (cols + U * 64 * CPL - 1) / (U * 64 * CPL);
   }
-  static __device__ __forceinline__ void issue(Regs<DT> &g, const Rows<R> &rw, int cols, int group, int step,
-                                               int lane) {
+  static __device__ __forceinline__ void issue(Regs<DT> &g, int base, const Rows<R> &rw, int cols, int group,
+                                               int step, int lane) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int c = ((step * U + u) * 64 + lane) * CPL;
@@ -457,11 +473,11 @@ template <int DT, int R, int U, int CPL> struct W4 {
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         if (c < cols) {
-          g.w[r * U + u] = CPL == 32 ? ld_stream16(rw.p[r] + (c >> 1)) : ld_stream8(rw.p[r] + (c >> 1));
-          g.sz[r * U + u] = Store<DT>::ldsz(rw.sz[r], gi);
+          g.w[base + r * U + u] = CPL == 32 ? ld_stream16(rw.p[r] + (c >> 1)) : ld_stream8(rw.p[r] + (c >> 1));
+          g.sz[base + r * U + u] = Store<DT>::ldsz(rw.sz[r], gi);
         } else {
-          g.w[r * U + u] = make_uint4(0, 0, 0, 0);
-          g.sz[r * U + u] = Store<DT>::pack(0.f, 0.f);
+          g.w[base + r * U + u] = make_uint4(0, 0, 0, 0);
+          g.sz[base + r * U + u] = Store<DT>::pack(0.f, 0.f);
         }
       }
     }
@@ -479,26 +495,27 @@ template <int DT, int R, int U, int CPL> struct W4 {
     a = fmaf((float)(hi >> 24), x[7], a);
     return a;
   }
-  static __device__ __forceinline__ void fma(const Regs<DT> &g, int cols, int group, int step,
+  static __device__ __forceinline__ void fma(const Regs<DT> &g, int base, int cols, int group, int step,
                                              const float *xl, float (&acc)[R], int lane) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int c = ((step * U + u) * 64 + lane) * CPL;
+      const int gb = (step * U + u) * 64 * CPL;            // granule base; see x_slot
+      const int c = gb + lane * CPL;
       if (c < cols) {
         float x[CPL];
         float sx = 0.f;
 #pragma unroll
         for (int e = 0; e < CPL; e += 4) {
-          const float4 t = *(const float4 *)(xl + c + e);
+          const float4 t = *(const float4 *)(xl + gb + e * 64 + lane * 4);
           x[e] = t.x; x[e + 1] = t.y; x[e + 2] = t.z; x[e + 3] = t.w;
           sx += (t.x + t.y) + (t.z + t.w);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          const uint4 &w = g.w[r * U + u];
+          const uint4 &w = g.w[base + r * U + u];
           float aq = dot8(w.x, x) + dot8(w.y, x + 8);
           if constexpr (CPL == 32) aq += dot8(w.z, x + 16) + dot8(w.w, x + 24);
-          const float s = Store<DT>::scale(g.sz[r * U + u]), z = Store<DT>::zero(g.sz[r * U + u]);
+          const float s = Store<DT>::scale(g.sz[base + r * U + u]), z = Store<DT>::zero(g.sz[base + r * U + u]);
           acc[r] = fmaf(s, aq - z * sx, acc[r]);
         }
       }
@@ -508,8 +525,10 @@ template <int DT, int R, int U, int CPL> struct W4 {
 
 // The two register sets of the streaming pipeline.  The (task, step) pairs of a wavefront
 // form one sequence j = 0, 1, 2, ...: task wave_id() + (j / NS) * wave_count(), step j % NS.
-// Set a holds an even j, set b the following odd j; while one is consumed the other is in
-// flight, and both can be issued before the barrier in front of the phase.
+// An element occupies one "slot": a whole register set, or half of one for formats whose
+// step needs at most kNL / 2 loads (F::SUB == 2) -- then four elements are in flight
+// instead of two, for the same registers.  While one slot is consumed the others are in
+// flight, and all of them can be issued before the barrier in front of the phase.
 // `lane` is the lane id passed through an empty asm: with all phases of all blocks inlined
 // into one kernel the compiler would otherwise derive every lane-offset variant once at
 // kernel entry and keep (spill) them all; this way they are re-derived per phase.
@@ -520,30 +539,52 @@ __device__ __forceinline__ int fresh_lane() {
 }
 template <int DT> struct Pre {
   Regs<DT> a, b;
+  float rh[2], r1[2];      // residual inputs of this wavefront's first two tasks (O, down phases)
   int lane;
   __device__ __forceinline__ Pre() : lane(fresh_lane()) {}
 };
 
-// Issue element j of this wavefront's sequence into g (nothing if the sequence is shorter).
+// Issue element j of this wavefront's sequence into slot j % (2 * F::SUB) (nothing if the
+// sequence is shorter).
 template <class F, int DT, int R, class RowsOf>
-__device__ __forceinline__ void issue_seq(int j, int n_tasks, int cols, int group, Regs<DT> &g,
-                                          int lane, RowsOf rows_of) {
+__device__ __forceinline__ void issue_seq(int j, int slot, int n_tasks, int cols, int group, Pre<DT> &pre,
+                                          RowsOf rows_of) {
   const int NS = F::steps(cols);
   const int t = wave_id() + (j / NS) * wave_count();
   if (t < n_tasks) {
     Rows<R> rw;
     rows_of(t, rw);
-    F::issue(g, rw, cols, group, j % NS, lane);
+    F::issue(slot < F::SUB ? pre.a : pre.b, (slot % F::SUB) * (kNL / F::SUB), rw, cols, group, j % NS, pre.lane);
   }
 }
+// The first elements into their slots.  part 0: the slots to fill before the barrier in
+// front of the phase; part 1: the rest, issued once the barrier has been passed (a larger
+// burst in flight delays the polls of the barrier itself); part 2: all.
+#ifndef RIVER_EARLY_SLOTS
+#define RIVER_EARLY_SLOTS 4
+#endif
+template <class F, int DT, int R, class RowsOf>
+__device__ __forceinline__ void issue_first(int part, int n_tasks, int cols, int group, Pre<DT> &pre,
+                                            RowsOf rows_of) {
+  constexpr int NSLOT = 2 * F::SUB;
+#ifdef RIVER_POLLER_LATE
+  const int EARLY = wave_in_wg() == 0 ? 0 : (RIVER_EARLY_SLOTS < NSLOT ? RIVER_EARLY_SLOTS : NSLOT);
+#else
+  constexpr int EARLY = RIVER_EARLY_SLOTS < NSLOT ? RIVER_EARLY_SLOTS : NSLOT;
+#endif
+#pragma unroll
+  for (int q = 0; q < NSLOT; ++q)
+    if (part == 2 || (part == 0) == (q < EARLY)) issue_seq<F, DT, R>(q, q, n_tasks, cols, group, pre, rows_of);
+}
 
-// Runs all tasks of this wavefront of one GEMV phase.  pre.a / pre.b must already hold
-// elements 0 and 1 of the sequence (issued by the caller, possibly before the preceding
-// barrier).  rows_of(task, Rows&) gives the rows of a task; epi(task, acc) receives the R
-// finished dot products (identical in all lanes).
+// Runs all tasks of this wavefront of one GEMV phase.  The slots must already hold the first
+// elements of the sequence (issue_first, called by the caller, possibly before the
+// preceding barrier).  rows_of(task, Rows&) gives the rows of a task; epi(task, acc)
+// receives the R finished dot products (identical in all lanes).
 template <class F, int DT, int R, class RowsOf, class Epi>
 __device__ __forceinline__ void stream_tasks(int n_tasks, int cols, int group, const float *xl,
                                              Pre<DT> &pre, RowsOf rows_of, Epi epi) {
+  constexpr int NSLOT = 2 * F::SUB;
   const int nw = wave_count(), w = wave_id();
   if (w >= n_tasks) return;
   const int NS = F::steps(cols);
@@ -552,24 +593,22 @@ __device__ __forceinline__ void stream_tasks(int n_tasks, int cols, int group, c
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0.f;
   int s = 0, t = w;                                       // step and task being consumed
-  auto consume = [&](Regs<DT> &g) {
-    F::fma(g, cols, group, s, xl, acc, pre.lane);
-    if (++s == NS) {
+  for (int j = 0; j < J; j += NSLOT) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
-      epi(t, acc);
+    for (int q = 0; q < NSLOT; ++q) {
+      if (j + q < J) {
+        F::fma(q < F::SUB ? pre.a : pre.b, (q % F::SUB) * (kNL / F::SUB), cols, group, s, xl, acc, pre.lane);
+        if (++s == NS) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) acc[r] = 0.f;
-      s = 0;
-      t += nw;
-    }
-  };
-  for (int j = 0; j < J; j += 2) {
-    consume(pre.a);
-    if (j + 2 < J) issue_seq<F, DT, R>(j + 2, n_tasks, cols, group, pre.a, pre.lane, rows_of);
-    if (j + 1 < J) {
-      consume(pre.b);
-      if (j + 3 < J) issue_seq<F, DT, R>(j + 3, n_tasks, cols, group, pre.b, pre.lane, rows_of);
+          for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
+          epi(t, acc);
+#pragma unroll
+          for (int r = 0; r < R; ++r) acc[r] = 0.f;
+          s = 0;
+          t += nw;
+        }
+        if (j + q + NSLOT < J) issue_seq<F, DT, R>(j + q + NSLOT, q, n_tasks, cols, group, pre, rows_of);
+      }
     }
   }
 }
@@ -597,6 +636,11 @@ template <> struct Shape<PH_O, true> { static constexpr int R = 2, U = 2; };
 template <> struct Shape<PH_GU, true> { static constexpr int R = 2, U = 2; };
 template <> struct Shape<PH_DOWN, true> { static constexpr int R = 1, U = 7; };
 
+// log2 of the columns a lane owns per lane load in the format a phase runs in (x_slot)
+template <int DT>
+__device__ __forceinline__ int run_log2(bool river, int cols) {
+  return !river ? (Store<DT>::EPL == 8 ? 3 : 2) : ((cols & 31) == 0 ? 5 : 4);
+}
 __device__ __forceinline__ int phase_nrows(DevRef D, int ph) {
   return ph == PH_QKV ? (D.nq + 2 * D.nkv) * D.hd : ph == PH_GU ? 2 * D.ffn : D.d;
 }
@@ -653,10 +697,10 @@ __device__ __forceinline__ void with_format(DevRef D, bool river, Fn f) {
   }
 }
 
-// Issue the first two elements of this wavefront's sequence of phase PH of block l (dense
-// or river).  `which`: bit 0 = element 0 into g.a, bit 1 = element 1 into g.b.
+// Issue the first elements of this wavefront's sequence of phase PH of block l (dense or
+// river), one per slot.
 template <int DT, int PH>
-__device__ __forceinline__ void prefetch_phase_t(DevRef D, int l, bool river, Pre<DT> &g, int which) {
+__device__ __forceinline__ void prefetch_phase_t(DevRef D, int l, bool river, Pre<DT> &g, int part) {
   LayerRef Lw = layer_of(D, l);
   with_format<DT, PH>(D, river, [&](auto ftag, auto rv, auto rr) {
     typedef typename decltype(ftag)::type F;
@@ -664,18 +708,29 @@ __device__ __forceinline__ void prefetch_phase_t(DevRef D, int l, bool river, Pr
     constexpr int R = decltype(rr)::value;
     auto rows_of = [&](int t, Rows<R> &rw) { phase_rows<DT, PH, RV, R>(D, Lw, t, rw); };
     const int n = (phase_nrows(D, PH) + R - 1) / R, cols = phase_cols(D, PH);
-    if (which & 1) issue_seq<F, DT, R>(0, n, cols, D.group, g.a, g.lane, rows_of);
-    if (which & 2) issue_seq<F, DT, R>(1, n, cols, D.group, g.b, g.lane, rows_of);
+    issue_first<F, DT, R>(part, n, cols, D.group, g, rows_of);
+    // The residual inputs of the phases that add to the hidden state (h for O and down, h1
+    // for down) were published at least one barrier ago: fetch them for the first two tasks
+    // now, so that the epilogue does not wait for them.
+    if ((PH == PH_O || PH == PH_DOWN) && part != 1) {
+      const float *hin = D.hidden + (size_t)l * D.d;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int row = (wave_id() + j * wave_count()) * R + g.lane;
+        const bool ok = g.lane < R && row < D.d;
+        g.rh[j] = ok ? sub(hin + row) : 0.f;
+        if (PH == PH_DOWN) g.r1[j] = ok ? sub(D.h1 + row) : 0.f;
+      }
+    }
   });
 }
 template <int DT>
-__device__ __forceinline__ void prefetch_phase(DevRef D, int l, int ph, bool river, Pre<DT> &g,
-                                               int which = 3) {
+__device__ __forceinline__ void prefetch_phase(DevRef D, int l, int ph, bool river, Pre<DT> &g, int part = 2) {
   switch (ph) {
-    case PH_QKV: prefetch_phase_t<DT, PH_QKV>(D, l, river, g, which); break;
-    case PH_O: prefetch_phase_t<DT, PH_O>(D, l, river, g, which); break;
-    case PH_GU: prefetch_phase_t<DT, PH_GU>(D, l, river, g, which); break;
-    default: prefetch_phase_t<DT, PH_DOWN>(D, l, river, g, which); break;
+    case PH_QKV: prefetch_phase_t<DT, PH_QKV>(D, l, river, g, part); break;
+    case PH_O: prefetch_phase_t<DT, PH_O>(D, l, river, g, part); break;
+    case PH_GU: prefetch_phase_t<DT, PH_GU>(D, l, river, g, part); break;
+    default: prefetch_phase_t<DT, PH_DOWN>(D, l, river, g, part); break;
   }
 }
 
@@ -767,14 +822,17 @@ __device__ __forceinline__ bool guess_river_after(const StepArgs &A, const Ctl &
 // three per wavefront at the 8B shape, instead of rotation pairs (one and a half).
 template <int DT>
 __device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+  RIVER_MARK(D, 16);
   LayerRef Lw = layer_of(D, l);
   if (l == 0) {
     int tok = A.token >= 0 ? A.token : D.st->cur_token;
     tok = min(max(tok, 0), D.vocab - 1);       // a NaN-poisoned argmax must not index out of range
-    stage_norm_embed<DT>(D, tok, Lw.attn_norm, lds, lds_red(D, lds));
+    stage_norm_embed<DT>(D, tok, Lw.attn_norm, run_log2<DT>(river, D.d), lds, lds_red(D, lds));
   } else {
-    stage_norm<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, lds, lds_red(D, lds));
+    stage_norm<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, run_log2<DT>(river, D.d), lds,
+                   lds_red(D, lds));
   }
+  RIVER_MARK(D, 17);
   const int qd = D.nq * D.hd, nrows = qd + 2 * D.nkv * D.hd;
   const int lane = pre.lane;
   auto epi = [&](int n0, auto &acc) {
@@ -787,6 +845,7 @@ __device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bo
     }
   };
   run_phase<DT, PH_QKV>(D, l, river, lds, pre, epi);
+  RIVER_MARK(D, 18);
 }
 
 // Sum over the 16 lanes of a DPP row; every lane gets the result.  DPP lane permutations
@@ -997,15 +1056,15 @@ __device__ __forceinline__ float4 combine_splits(DevRef D, int S, int h, int e4)
 // Stage the attention output for the output projection: a copy of the finished vector
 // (one split), or the merge of the split partials, done by every workgroup for itself --
 // that costs the consumers some more loads but no extra hand-over between workgroups.
-__device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, float *xl) {
+__device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, int lp, float *xl) {
   const int S = A.n_splits, n = D.nq * D.hd;
   if (S == 1) {
-    stage_copy(D.obuf, n, xl);
+    stage_copy(D.obuf, n, lp, xl);
     return;
   }
   lds_barrier();
   for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4)
-    *(float4 *)(xl + i) = combine_splits(D, S, i / D.hd, i % D.hd);
+    *(float4 *)(xl + x_slot(i, lp)) = combine_splits(D, S, i / D.hd, i % D.hd);
   lds_barrier();
 }
 
@@ -1192,21 +1251,31 @@ __device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, f
 // a4: h1 = h + W_o o
 template <int DT>
 __device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
-  stage_attn_out(D, A, lds);
+  RIVER_MARK(D, 20);
+  stage_attn_out(D, A, run_log2<DT>(river, D.nq * D.hd), lds);
+  RIVER_MARK(D, 21);
   const float *hin = D.hidden + (size_t)l * D.d;
   const int lane = pre.lane;
+  int ord = 0;                          // ordinal of the task among this wavefront's
   auto epi = [&](int n0, auto &acc) {
     constexpr int R = sizeof(acc) / sizeof(float);
     const int n = n0 + lane;
-    if (lane < R && n < D.d) pub(D.h1 + n, sub(hin + n) + pick<R>(acc, lane));
+    if (lane < R && n < D.d) {
+      const float h0 = ord == 0 ? pre.rh[0] : ord == 1 ? pre.rh[1] : sub(hin + n);
+      pub(D.h1 + n, h0 + pick<R>(acc, lane));
+    }
+    ++ord;
   };
   run_phase<DT, PH_O>(D, l, river, lds, pre, epi);
+  RIVER_MARK(D, 22);
 }
 
 // a5: y = RMSNorm(h1) * g2; a = silu(W_g y) * (W_u y); rows come as (gate i, up i) pairs
 template <int DT>
 __device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
-  stage_norm<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lds, lds_red(D, lds));
+  RIVER_MARK(D, 24);
+  stage_norm<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, run_log2<DT>(river, D.d), lds, lds_red(D, lds));
+  RIVER_MARK(D, 25);
   const int lane = pre.lane;
   auto epi = [&](int n0, auto &acc) {
     constexpr int R = sizeof(acc) / sizeof(float);
@@ -1218,6 +1287,7 @@ __device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l,
     if (lane < R / 2 && i < D.ffn) pub(D.abuf + i, gv / (1.0f + expf(-gv)) * uv);
   };
   run_phase<DT, PH_GU>(D, l, river, lds, pre, epi);
+  RIVER_MARK(D, 26);
 }
 
 // a6: h2 = h1 + W_d a, published as h(l+1); on backbone blocks also the three sums of
@@ -1226,22 +1296,28 @@ __device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l,
 // start of the next block (exit_test), so no workgroup waits for another here.
 template <int DT>
 __device__ __forceinline__ void phase_down(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
-  stage_copy(D.abuf, D.ffn, lds);
+  RIVER_MARK(D, 28);
+  stage_copy(D.abuf, D.ffn, run_log2<DT>(river, D.ffn), lds);
+  RIVER_MARK(D, 29);
   const float *hin = D.hidden + (size_t)l * D.d;
   float *hout = D.hidden + (size_t)(l + 1) * D.d;
   const int lane = pre.lane;
   float ab = 0.f, aa = 0.f, bb = 0.f;
+  int ord = 0;                          // ordinal of the task among this wavefront's
   auto epi = [&](int n0, auto &acc) {
     constexpr int R = sizeof(acc) / sizeof(float);
     const int n = n0 + lane;
     if (lane < R && n < D.d) {
-      const float h0 = sub(hin + n);
-      const float h2 = sub(D.h1 + n) + pick<R>(acc, lane);
+      const float h0 = ord == 0 ? pre.rh[0] : ord == 1 ? pre.rh[1] : sub(hin + n);
+      const float h1 = ord == 0 ? pre.r1[0] : ord == 1 ? pre.r1[1] : sub(D.h1 + n);
+      const float h2 = h1 + pick<R>(acc, lane);
       pub(hout + n, h2);
       ab = fmaf(h0, h2, ab); aa = fmaf(h0, h0, aa); bb = fmaf(h2, h2, bb);
     }
+    ++ord;
   };
   run_phase<DT, PH_DOWN>(D, l, river, lds, pre, epi);
+  RIVER_MARK(D, 30);
   if (river) return;                    // river blocks take no exit test
   float *red = lds_red(D, lds);
   ab = block_sum(ab, red); aa = block_sum(aa, red); bb = block_sum(bb, red);
@@ -1265,11 +1341,10 @@ __device__ __forceinline__ void head_rows(DevRef D, int t, Rows<kRD> &rw) {
   }
 }
 template <int DT>
-__device__ __forceinline__ void prefetch_head(DevRef D, Pre<DT> &g, int which = 3) {
+__device__ __forceinline__ void prefetch_head(DevRef D, Pre<DT> &g, int part = 2) {
   auto rows_of = [&](int t, Rows<kRD> &rw) { head_rows<DT>(D, t, rw); };
   const int n = (D.vocab + kRD - 1) / kRD;
-  if (which & 1) issue_seq<Dense<DT, kRD, kUD>, DT, kRD>(0, n, D.d, D.group, g.a, g.lane, rows_of);
-  if (which & 2) issue_seq<Dense<DT, kRD, kUD>, DT, kRD>(1, n, D.d, D.group, g.b, g.lane, rows_of);
+  issue_first<Dense<DT, kRD, kUD>, DT, kRD>(part, n, D.d, D.group, g, rows_of);
 }
 template <int DT>
 __device__ __forceinline__ void phase_head(DevRef D, const StepArgs &A, const Ctl &ctl, float *lds, Pre<DT> &pre) {
@@ -1278,7 +1353,7 @@ __device__ __forceinline__ void phase_head(DevRef D, const StepArgs &A, const Ct
     const float s = similarity_from_partials(D, red);
     if (blockIdx.x == 0 && threadIdx.x == 0) D.rec_sims[(size_t)A.rec_slot * D.L + (D.L - 1)] = s;
   }
-  stage_norm<DT>(D.hidden + (size_t)D.L * D.d, D.final_norm, D.d, D.eps, lds, red);
+  stage_norm<DT>(D.hidden + (size_t)D.L * D.d, D.final_norm, D.d, D.eps, run_log2<DT>(false, D.d), lds, red);
   const int lane = pre.lane;
   float best = -INFINITY;
   int besti = 0x7fffffff;
