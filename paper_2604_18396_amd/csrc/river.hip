@@ -505,7 +505,7 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   D.rec_token = (int *)(ws + lay.rec_token); D.rec_exit = (int *)(ws + lay.rec_exit);
   D.rec_sims = (float *)(ws + lay.rec_sims);
   D.trace = (unsigned long long *)(ws + lay.trace);
-  x->lds_bytes = ((size_t)D.xcap + 64) * sizeof(float);
+  x->lds_bytes = ((size_t)D.xcap + lds_half_floats(D.xcap) + 64) * sizeof(float);
 
   // RoPE table in double precision: angle = pos * base^(-2i/hd)
   const int half = cfg->head_dim / 2;

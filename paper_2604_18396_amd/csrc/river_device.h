@@ -215,10 +215,31 @@ __device__ __forceinline__ void publish_barrier() {
 
 // ------------------------------------------------------------ reductions
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+
+// Sum over the 16 lanes of a DPP row; every lane gets the result.  DPP lane permutations
+// only (no LDS pipe traffic): two quad permutes, then the mirrors of a half row and of a
+// row, which after the previous steps hold the other half's sum.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v = dpp_add<0xB1>(v);      // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E>(v);      // quad_perm [2,3,0,1]
+  v = dpp_add<0x141>(v);     // row_half_mirror
+  v = dpp_add<0x140>(v);     // row_mirror
   return v;
+}
+
+// Sum over the wavefront, the same value (a scalar) in every lane: row sums, then the last
+// lane of row r added into row r + 1 (rows 1 and 3), then the last lane of row 1 into rows
+// 2 and 3; lane 63 holds the total.  Lane permutations only -- the LDS-pipe exchange this
+// replaces took several times as long per step, on the critical path of every task.
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row16_sum(v);
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142 /* row_bcast:15 */, 0xa, 0xf, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143 /* row_bcast:31 */, 0xc, 0xf, false));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // Sum over the workgroup in a fixed order; every thread gets the result.
@@ -314,10 +335,13 @@ __device__ __forceinline__ bool last_arriver(unsigned int *cnt, unsigned int exp
 
 // ------------------------------------------------------------- LDS layout
 
-// [0, xcap) staged vector (or the attention merge area), [xcap, xcap+32) reduction
-// scratch, [xcap+32] last-arriver flag.
-__device__ __forceinline__ float *lds_red(DevRef D, float *lds) { return lds + D.xcap; }
-__device__ __forceinline__ int *lds_flag(DevRef D, float *lds) { return (int *)(lds + D.xcap + 32); }
+// [0, xcap) staged vector in fp32 (or the attention merge area); then xcap/2 words for the
+// staged vector as half pairs and xcap/32 floats for its per-run sums (4-bit phases of a
+// bf16 model, see W4); then 32 floats of reduction scratch and the last-arriver flag.
+__host__ __device__ inline int lds_half_floats(int xcap) { return xcap / 2 + xcap / 32; }
+__device__ __forceinline__ float *lds_half(DevRef D, float *lds) { return lds + D.xcap; }
+__device__ __forceinline__ float *lds_red(DevRef D, float *lds) { return lds + D.xcap + lds_half_floats(D.xcap); }
+__device__ __forceinline__ int *lds_flag(DevRef D, float *lds) { return (int *)(lds_red(D, lds) + 32); }
 
 // wave-uniform by construction; readfirstlane tells the compiler, so that task indices and
 // row pointers live in scalar registers
@@ -365,14 +389,16 @@ __device__ __forceinline__ void stage_norm(const float *h, const void *gain, int
 
 // Same, the source being row `tok` of the embedding table (block 1 of a token); also
 // publishes h(0) (each workgroup a slice) for the residual adds and the similarity.
+// lp < 0: the half layout, written to xh (see half_store8; defined further down).
+__device__ __forceinline__ void half_store8(float *xh, int n, int c, const float (&v)[8]);
 template <int DT>
 __device__ __forceinline__ void stage_norm_embed(DevRef D, int tok, const void *gain, int lp, float *xl,
-                                                 float *red) {
+                                                 float *xh, float *red) {
   const int n = D.d;
   float ss = 0.f;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     const float v = Store<DT>::ld(D.tok_emb, (size_t)tok * n + i);
-    xl[x_slot(i, lp)] = v;
+    xl[lp < 0 ? i : x_slot(i, lp)] = v;
     ss += v * v;
   }
   const int per = (n + gridDim.x - 1) / gridDim.x;
@@ -380,13 +406,88 @@ __device__ __forceinline__ void stage_norm_embed(DevRef D, int tok, const void *
     pub(D.hidden + i, Store<DT>::ld(D.tok_emb, (size_t)tok * n + i));
   const float tot = block_sum(ss, red);
   const float r = 1.0f / sqrtf(tot / (float)n + D.eps);
-  for (int i = threadIdx.x; i < n; i += blockDim.x) xl[x_slot(i, lp)] = xl[x_slot(i, lp)] * r * Store<DT>::ld(gain, i);
+  if (lp < 0) {
+    for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = xl[i + k] * r * Store<DT>::ld(gain, i + k);
+      half_store8(xh, n, i, v);
+    }
+  } else {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) xl[x_slot(i, lp)] = xl[x_slot(i, lp)] * r * Store<DT>::ld(gain, i);
+  }
   lds_barrier();
 }
 
 __device__ __forceinline__ void stage_copy(const float *src, int n, int lp, float *xl) {
   lds_barrier();
   for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) *(float4 *)(xl + x_slot(i, lp)) = sub4(src, i);
+  lds_barrier();
+}
+
+// The staged vector for the 4-bit phases of a bf16 model (columns a multiple of 32): rounded
+// to half precision -- the river is a weight-only 4-bit format with 16-bit activations --
+// and stored as the pairs the packed dot product consumes.  A lane load is 32 codes in four
+// words; word w holds codes of columns 8w .. 8w+7, and its nibble pairs (k, k+4) are
+// extracted two at a time, so the vector is stored as half2 (x[8w+k], x[8w+k+4]), k < 4:
+// one uint4 per (lane, word), lane after lane per word (conflict-free as in x_slot):
+//   uint4 (granule g, word w, lane) at word offset g * 1024 + w * 256 + lane * 4.
+// Behind the pairs, sums[g * 64 + lane] = sum of the lane's 32 rounded values.
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_half2(float a, float b) {
+  const half2_t h = {(_Float16)a, (_Float16)b};
+  return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ int half_sums_offset(int n) { return ((n + 2047) >> 11) * 1024; }
+
+// Store eight consecutive values v[0..7] (columns c .. c+7, c % 8 == 0) of the half layout
+// and add their rounded sum into the run sum; the four threads that hold one lane's run
+// are neighbours (c / 8 consecutive), so the run sum is a quad reduction.
+__device__ __forceinline__ void half_store8(float *xh, int n, int c, const float (&v)[8]) {
+  const int g = c >> 11, lane = (c >> 5) & 63, w = (c >> 3) & 3;
+  uint4 o;
+  o.x = pack_half2(v[0], v[4]); o.y = pack_half2(v[1], v[5]);
+  o.z = pack_half2(v[2], v[6]); o.w = pack_half2(v[3], v[7]);
+  *(uint4 *)((uint32_t *)xh + g * 1024 + w * 256 + lane * 4) = o;
+  float sr = 0.f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) sr += (float)(_Float16)v[k];
+  sr = dpp_add<0xB1>(sr);       // quad_perm [1,0,3,2]
+  sr = dpp_add<0x4E>(sr);       // quad_perm [2,3,0,1]
+  if (w == 0) xh[half_sums_offset(n) + g * 64 + lane] = sr;
+}
+
+// xh = half layout of h * rsqrt(mean(h^2) + eps) * gain; n % 32 == 0.  `xl` (n floats)
+// holds h between the two passes.
+template <int DT>
+__device__ __forceinline__ void stage_norm_half(const float *h, const void *gain, int n, float eps,
+                                                float *xl, float *xh, float *red) {
+  float ss = 0.f;
+  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) {
+    const float4 v = sub4(h, i);
+    *(float4 *)(xl + i) = v;
+    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+  }
+  const float tot = block_sum(ss, red);
+  const float r = 1.0f / sqrtf(tot / (float)n + eps);
+  // whole quads of threads run the loop together (n % 32 == 0), as the run sums need
+  for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
+    const float4 a = *(float4 *)(xl + i), b = *(float4 *)(xl + i + 4);
+    float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = v[k] * r * Store<DT>::ld(gain, i + k);
+    half_store8(xh, n, i, v);
+  }
+  lds_barrier();
+}
+
+__device__ __forceinline__ void stage_copy_half(const float *src, int n, float *xh) {
+  lds_barrier();
+  for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
+    const float4 a = sub4(src, i), b = sub4(src, i + 4);
+    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    half_store8(xh, n, i, v);
+  }
   lds_barrier();
 }
 
@@ -495,8 +596,47 @@ template <int DT, int R, int U, int CPL> struct W4 {
     a = fmaf((float)(hi >> 24), x[7], a);
     return a;
   }
+  // Half-precision activations (bf16 models, 32 codes per lane load): xl points to the half
+  // layout (see half_store8).  A code nibble n is turned into the half value 1024 + n by
+  // OR-ing it into the mantissa of 1024.0, two nibbles (k, k+4) of a word at a time; the
+  // packed dot product accumulates in fp32, and the 1024 offsets leave with the zero point:
+  // sum (code - zero) x = sum (1024 + code) x - (zero + 1024) sum x.
+  static constexpr bool HALF = DT == 1 && CPL == 32;
+  static __device__ __forceinline__ float dot8h(uint32_t v, const uint4 &xw, float a) {
+    const uint32_t m = 0x000f000fu, one = 0x64006400u;
+    a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, (v & m) | one), __builtin_bit_cast(half2_t, xw.x), a, false);
+    a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, ((v >> 4) & m) | one), __builtin_bit_cast(half2_t, xw.y), a, false);
+    a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, ((v >> 8) & m) | one), __builtin_bit_cast(half2_t, xw.z), a, false);
+    a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, ((v >> 12) & m) | one), __builtin_bit_cast(half2_t, xw.w), a, false);
+    return a;
+  }
+  static __device__ __forceinline__ void fma_half(const Regs<DT> &g, int base, int cols, int step,
+                                                  const float *xl, float (&acc)[R], int lane) {
+    const float *sums = xl + half_sums_offset(cols);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int gi = step * U + u;                         // granule
+      if ((gi * 64 + lane) * 32 < cols) {
+        const uint32_t *xp = (const uint32_t *)xl + gi * 1024 + lane * 4;
+        const uint4 x0 = *(const uint4 *)xp, x1 = *(const uint4 *)(xp + 256);
+        const uint4 x2 = *(const uint4 *)(xp + 512), x3 = *(const uint4 *)(xp + 768);
+        const float sx = sums[gi * 64 + lane];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const uint4 &w = g.w[base + r * U + u];
+          const float aq = dot8h(w.w, x3, dot8h(w.z, x2, dot8h(w.y, x1, dot8h(w.x, x0, 0.f))));
+          const float s = Store<DT>::scale(g.sz[base + r * U + u]), z = Store<DT>::zero(g.sz[base + r * U + u]);
+          acc[r] = fmaf(s, aq - (z + 1024.0f) * sx, acc[r]);
+        }
+      }
+    }
+  }
   static __device__ __forceinline__ void fma(const Regs<DT> &g, int base, int cols, int group, int step,
                                              const float *xl, float (&acc)[R], int lane) {
+    if constexpr (HALF) {
+      fma_half(g, base, cols, step, xl, acc, lane);
+      return;
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int gb = (step * U + u) * 64 * CPL;            // granule base; see x_slot
@@ -523,12 +663,14 @@ template <int DT, int R, int U, int CPL> struct W4 {
   }
 };
 
-// The two register sets of the streaming pipeline.  The (task, step) pairs of a wavefront
+// The register sets of the streaming pipeline.  The (task, step) pairs of a wavefront
 // form one sequence j = 0, 1, 2, ...: task wave_id() + (j / NS) * wave_count(), step j % NS.
 // An element occupies one "slot": a whole register set, or half of one for formats whose
-// step needs at most kNL / 2 loads (F::SUB == 2) -- then four elements are in flight
-// instead of two, for the same registers.  While one slot is consumed the others are in
-// flight, and all of them can be issued before the barrier in front of the phase.
+// step needs at most kNL / 2 loads (F::SUB == 2) -- then twice as many elements are in
+// flight for the same registers.  While one slot is consumed the others are in flight.
+// The slots of the first sets are issued before the barrier in front of the phase, the
+// last set's once the barrier has been passed (a larger burst in flight delays the barrier
+// itself), so that its latency is covered by the staging of the input vector.
 // `lane` is the lane id passed through an empty asm: with all phases of all blocks inlined
 // into one kernel the compiler would otherwise derive every lane-offset variant once at
 // kernel entry and keep (spill) them all; this way they are re-derived per phase.
@@ -537,15 +679,16 @@ __device__ __forceinline__ int fresh_lane() {
   asm volatile("" : "+v"(t));
   return t;
 }
+constexpr int kSets = 2;          // register sets of the streaming pipeline (a third one only delayed the phases)
 template <int DT> struct Pre {
-  Regs<DT> a, b;
+  Regs<DT> set[kSets];
   float rh[2], r1[2];      // residual inputs of this wavefront's first two tasks (O, down phases)
   int lane;
   __device__ __forceinline__ Pre() : lane(fresh_lane()) {}
 };
 
-// Issue element j of this wavefront's sequence into slot j % (2 * F::SUB) (nothing if the
-// sequence is shorter).
+// Issue element j of this wavefront's sequence into slot j % (kSets * F::SUB) (nothing if
+// the sequence is shorter).
 template <class F, int DT, int R, class RowsOf>
 __device__ __forceinline__ void issue_seq(int j, int slot, int n_tasks, int cols, int group, Pre<DT> &pre,
                                           RowsOf rows_of) {
@@ -554,24 +697,19 @@ __device__ __forceinline__ void issue_seq(int j, int slot, int n_tasks, int cols
   if (t < n_tasks) {
     Rows<R> rw;
     rows_of(t, rw);
-    F::issue(slot < F::SUB ? pre.a : pre.b, (slot % F::SUB) * (kNL / F::SUB), rw, cols, group, j % NS, pre.lane);
+    F::issue(pre.set[slot / F::SUB], (slot % F::SUB) * (kNL / F::SUB), rw, cols, group, j % NS, pre.lane);
   }
 }
 // The first elements into their slots.  part 0: the slots to fill before the barrier in
-// front of the phase; part 1: the rest, issued once the barrier has been passed (a larger
-// burst in flight delays the polls of the barrier itself); part 2: all.
-#ifndef RIVER_EARLY_SLOTS
-#define RIVER_EARLY_SLOTS 4
+// front of the phase; part 1: the rest, issued once the barrier has been passed; part 2: all.
+#ifndef RIVER_EARLY_SETS
+#define RIVER_EARLY_SETS 2
 #endif
 template <class F, int DT, int R, class RowsOf>
 __device__ __forceinline__ void issue_first(int part, int n_tasks, int cols, int group, Pre<DT> &pre,
                                             RowsOf rows_of) {
-  constexpr int NSLOT = 2 * F::SUB;
-#ifdef RIVER_POLLER_LATE
-  const int EARLY = wave_in_wg() == 0 ? 0 : (RIVER_EARLY_SLOTS < NSLOT ? RIVER_EARLY_SLOTS : NSLOT);
-#else
-  constexpr int EARLY = RIVER_EARLY_SLOTS < NSLOT ? RIVER_EARLY_SLOTS : NSLOT;
-#endif
+  constexpr int NSLOT = kSets * F::SUB;
+  constexpr int EARLY = RIVER_EARLY_SETS * F::SUB;
 #pragma unroll
   for (int q = 0; q < NSLOT; ++q)
     if (part == 2 || (part == 0) == (q < EARLY)) issue_seq<F, DT, R>(q, q, n_tasks, cols, group, pre, rows_of);
@@ -584,7 +722,7 @@ __device__ __forceinline__ void issue_first(int part, int n_tasks, int cols, int
 template <class F, int DT, int R, class RowsOf, class Epi>
 __device__ __forceinline__ void stream_tasks(int n_tasks, int cols, int group, const float *xl,
                                              Pre<DT> &pre, RowsOf rows_of, Epi epi) {
-  constexpr int NSLOT = 2 * F::SUB;
+  constexpr int NSLOT = kSets * F::SUB;
   const int nw = wave_count(), w = wave_id();
   if (w >= n_tasks) return;
   const int NS = F::steps(cols);
@@ -597,7 +735,7 @@ __device__ __forceinline__ void stream_tasks(int n_tasks, int cols, int group, c
 #pragma unroll
     for (int q = 0; q < NSLOT; ++q) {
       if (j + q < J) {
-        F::fma(q < F::SUB ? pre.a : pre.b, (q % F::SUB) * (kNL / F::SUB), cols, group, s, xl, acc, pre.lane);
+        F::fma(pre.set[q / F::SUB], (q % F::SUB) * (kNL / F::SUB), cols, group, s, xl, acc, pre.lane);
         if (++s == NS) {
 #pragma unroll
           for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
@@ -636,10 +774,18 @@ template <> struct Shape<PH_O, true> { static constexpr int R = 2, U = 2; };
 template <> struct Shape<PH_GU, true> { static constexpr int R = 2, U = 2; };
 template <> struct Shape<PH_DOWN, true> { static constexpr int R = 1, U = 7; };
 
-// log2 of the columns a lane owns per lane load in the format a phase runs in (x_slot)
+// Layout of the staged vector for the format a phase runs in: log2 of the columns a lane
+// owns per lane load (x_slot), or -1 for the half layout (4-bit phases of a bf16 model
+// whose column count is a multiple of 32).
 template <int DT>
 __device__ __forceinline__ int run_log2(bool river, int cols) {
-  return !river ? (Store<DT>::EPL == 8 ? 3 : 2) : ((cols & 31) == 0 ? 5 : 4);
+  if (!river) return Store<DT>::EPL == 8 ? 3 : 2;
+  if ((cols & 31) != 0) return 4;
+  return DT == 1 ? -1 : 5;
+}
+// where the streaming engine finds the staged vector of that layout
+__device__ __forceinline__ const float *x_area(DevRef D, float *lds, int lp) {
+  return lp < 0 ? lds_half(D, lds) : lds;
 }
 __device__ __forceinline__ int phase_nrows(DevRef D, int ph) {
   return ph == PH_QKV ? (D.nq + 2 * D.nkv) * D.hd : ph == PH_GU ? 2 * D.ffn : D.d;
@@ -827,7 +973,9 @@ __device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bo
   if (l == 0) {
     int tok = A.token >= 0 ? A.token : D.st->cur_token;
     tok = min(max(tok, 0), D.vocab - 1);       // a NaN-poisoned argmax must not index out of range
-    stage_norm_embed<DT>(D, tok, Lw.attn_norm, run_log2<DT>(river, D.d), lds, lds_red(D, lds));
+    stage_norm_embed<DT>(D, tok, Lw.attn_norm, run_log2<DT>(river, D.d), lds, lds_half(D, lds), lds_red(D, lds));
+  } else if (run_log2<DT>(river, D.d) < 0) {
+    stage_norm_half<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, lds, lds_half(D, lds), lds_red(D, lds));
   } else {
     stage_norm<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, run_log2<DT>(river, D.d), lds,
                    lds_red(D, lds));
@@ -844,23 +992,8 @@ __device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bo
       else pub(D.kvcur + (n - qd), v);          // [k (kvd); v (kvd)]
     }
   };
-  run_phase<DT, PH_QKV>(D, l, river, lds, pre, epi);
+  run_phase<DT, PH_QKV>(D, l, river, x_area(D, lds, run_log2<DT>(river, D.d)), pre, epi);
   RIVER_MARK(D, 18);
-}
-
-// Sum over the 16 lanes of a DPP row; every lane gets the result.  DPP lane permutations
-// only (no LDS pipe traffic): two quad permutes, then the mirrors of a half row and of a
-// row, which after the previous steps hold the other half's sum.
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float row16_sum(float v) {
-  v = dpp_add<0xB1>(v);      // quad_perm [1,0,3,2]
-  v = dpp_add<0x4E>(v);      // quad_perm [2,3,0,1]
-  v = dpp_add<0x141>(v);     // row_half_mirror
-  v = dpp_add<0x140>(v);     // row_mirror
-  return v;
 }
 
 // a2 for the 16 lanes that share one head vector (lane dl holds elements dl*EL .. dl*EL+EL-1):
@@ -1056,15 +1189,24 @@ __device__ __forceinline__ float4 combine_splits(DevRef D, int S, int h, int e4)
 // Stage the attention output for the output projection: a copy of the finished vector
 // (one split), or the merge of the split partials, done by every workgroup for itself --
 // that costs the consumers some more loads but no extra hand-over between workgroups.
-__device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, int lp, float *xl) {
+__device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, int lp, float *xl, float *xh) {
   const int S = A.n_splits, n = D.nq * D.hd;
   if (S == 1) {
-    stage_copy(D.obuf, n, lp, xl);
+    if (lp < 0) stage_copy_half(D.obuf, n, xh);
+    else stage_copy(D.obuf, n, lp, xl);
     return;
   }
   lds_barrier();
-  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4)
-    *(float4 *)(xl + x_slot(i, lp)) = combine_splits(D, S, i / D.hd, i % D.hd);
+  if (lp < 0) {
+    for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
+      const float4 a = combine_splits(D, S, i / D.hd, i % D.hd), b = combine_splits(D, S, i / D.hd, i % D.hd + 4);
+      const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      half_store8(xh, n, i, v);
+    }
+  } else {
+    for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4)
+      *(float4 *)(xl + x_slot(i, lp)) = combine_splits(D, S, i / D.hd, i % D.hd);
+  }
   lds_barrier();
 }
 
@@ -1252,7 +1394,8 @@ __device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, f
 template <int DT>
 __device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   RIVER_MARK(D, 20);
-  stage_attn_out(D, A, run_log2<DT>(river, D.nq * D.hd), lds);
+  const int lp = run_log2<DT>(river, D.nq * D.hd);
+  stage_attn_out(D, A, lp, lds, lds_half(D, lds));
   RIVER_MARK(D, 21);
   const float *hin = D.hidden + (size_t)l * D.d;
   const int lane = pre.lane;
@@ -1266,7 +1409,7 @@ __device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, 
     }
     ++ord;
   };
-  run_phase<DT, PH_O>(D, l, river, lds, pre, epi);
+  run_phase<DT, PH_O>(D, l, river, x_area(D, lds, lp), pre, epi);
   RIVER_MARK(D, 22);
 }
 
@@ -1274,7 +1417,9 @@ __device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, 
 template <int DT>
 __device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   RIVER_MARK(D, 24);
-  stage_norm<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, run_log2<DT>(river, D.d), lds, lds_red(D, lds));
+  const int lp = run_log2<DT>(river, D.d);
+  if (lp < 0) stage_norm_half<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lds, lds_half(D, lds), lds_red(D, lds));
+  else stage_norm<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lp, lds, lds_red(D, lds));
   RIVER_MARK(D, 25);
   const int lane = pre.lane;
   auto epi = [&](int n0, auto &acc) {
@@ -1286,7 +1431,7 @@ __device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l,
     const int i = (n0 >> 1) + lane;
     if (lane < R / 2 && i < D.ffn) pub(D.abuf + i, gv / (1.0f + expf(-gv)) * uv);
   };
-  run_phase<DT, PH_GU>(D, l, river, lds, pre, epi);
+  run_phase<DT, PH_GU>(D, l, river, x_area(D, lds, lp), pre, epi);
   RIVER_MARK(D, 26);
 }
 
@@ -1297,7 +1442,9 @@ __device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l,
 template <int DT>
 __device__ __forceinline__ void phase_down(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   RIVER_MARK(D, 28);
-  stage_copy(D.abuf, D.ffn, run_log2<DT>(river, D.ffn), lds);
+  const int lp = run_log2<DT>(river, D.ffn);
+  if (lp < 0) stage_copy_half(D.abuf, D.ffn, lds_half(D, lds));
+  else stage_copy(D.abuf, D.ffn, lp, lds);
   RIVER_MARK(D, 29);
   const float *hin = D.hidden + (size_t)l * D.d;
   float *hout = D.hidden + (size_t)(l + 1) * D.d;
@@ -1316,7 +1463,7 @@ __device__ __forceinline__ void phase_down(DevRef D, const StepArgs &A, int l, b
     }
     ++ord;
   };
-  run_phase<DT, PH_DOWN>(D, l, river, lds, pre, epi);
+  run_phase<DT, PH_DOWN>(D, l, river, x_area(D, lds, lp), pre, epi);
   RIVER_MARK(D, 30);
   if (river) return;                    // river blocks take no exit test
   float *red = lds_red(D, lds);

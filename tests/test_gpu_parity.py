@@ -230,9 +230,13 @@ def test_lossless_river_equals_dense(mode, cfg0):
             hs.append(g.hidden())
         runs.append(np.array(hs))
         g.close()
+    # fp32: the same arithmetic up to summation order.  bf16: the 4-bit phases take their
+    # input vector in half precision (weight-only 4-bit, 16-bit activations), the backbone
+    # in fp32, so the two runs differ by that rounding.
+    tol = 1e-5 if cfg.dtype == configs.DTYPE_F32 else 4e-3
     for a, b in zip(runs[1], runs[0]):
         for l in range(cfg.n_layers + 1):
-            assert relerr(a[l], b[l].astype(np.float64)) <= 1e-5
+            assert relerr(a[l], b[l].astype(np.float64)) <= tol
 
 
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
