@@ -276,7 +276,6 @@ static bool valid_cfg(const river_config *c, std::string *why) {
   if (c->river_bits != 4) return bad("river_bits must be 4");
   if (c->river_group < 32 || c->river_group % 32) return bad("river_group must be a multiple of 32");
   if (c->n_q_heads % c->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
-  const int G = c->n_q_heads / c->n_kv_heads;
   const int hd = c->head_dim;
   if (hd != 64 && hd != 128) return bad("head_dim must be 64 or 128");
   if (c->d_model % 16 || c->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
@@ -292,7 +291,6 @@ static bool valid_cfg(const river_config *c, std::string *why) {
 
 
 static int x_capacity(const river_config *c) {
-  const int G = c->n_q_heads / c->n_kv_heads;
   int cap = c->d_model;
   cap = std::max(cap, c->n_q_heads * c->head_dim);
   cap = std::max(cap, c->d_ffn);
@@ -320,7 +318,6 @@ static Layout make_layout(const river_config *c) {
   Layout y{};
   const size_t es = c->dtype == RIVER_BF16 ? 2 : 4;
   const size_t kvd = (size_t)c->n_kv_heads * c->head_dim;
-  const int G = c->n_q_heads / c->n_kv_heads;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   y.cache_bytes = (size_t)c->n_layers * c->max_seq * kvd * es;
@@ -564,8 +561,7 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
         (const void *)k_qkv<0>, (const void *)k_qkv<1>, (const void *)k_attn<0>, (const void *)k_attn<1>,
         (const void *)k_oproj<0>, (const void *)k_oproj<1>, (const void *)k_gateup<0>,
         (const void *)k_gateup<1>, (const void *)k_down<0>, (const void *)k_down<1>,
-        (const void *)k_head<0>, (const void *)k_head<1>, (const void *)k_step_persistent<0>,
-        (const void *)k_step_persistent<1>};
+        (const void *)k_head<0>, (const void *)k_head<1>, (const void *)k_step_persistent<1>};
     for (const void *f : fns)
       if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lb)) != hipSuccess)
         return fail("hipFuncSetAttribute(max dynamic LDS)", e);

@@ -1024,7 +1024,10 @@ __device__ __forceinline__ void rope_rotate(float (&x)[EL], const float2 (&cs)[E
 // -- the result is independent of timing.
 // This token's own K/V come from the exchange buffer and seed the running softmax of the
 // lane group that owns the current position.
-constexpr int kAttnPosPerSplit = 512;   // positions a workgroup should cover before the host adds a split
+#ifndef RIVER_ATTN_POS_PER_SPLIT
+#define RIVER_ATTN_POS_PER_SPLIT 256
+#endif
+constexpr int kAttnPosPerSplit = RIVER_ATTN_POS_PER_SPLIT;   // positions a workgroup should cover before the host adds a split
 constexpr float kNegBig = -1.0e30f;     // "no position yet": finite, so differences never give NaN
 
 // LDS floats of the merge area: per wavefront hd outputs and (max, sum).
