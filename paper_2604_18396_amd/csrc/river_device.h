@@ -43,9 +43,7 @@ struct DevLayer {
 };
 
 struct DevState {
-  unsigned long long grp[8 * 16]; // first-level barrier counters, one per group of workgroups, padded
-  unsigned long long top;         // second-level barrier counter
-  unsigned long long gen;         // index of the last completed barrier
+  unsigned long long grp[8 * 16]; // barrier arrival counters, one per group of workgroups, a cache line apart
   int error;                      // set when a bounded wait gave up
   int cur_token;                  // token produced by the last head phase
   int slot_river[2], slot_exit[2];// exit state of the current token, by block parity (one-kernel-per-phase mode)
@@ -284,35 +282,39 @@ __device__ __forceinline__ void block_argmax(float &v, int &i, float *red) {
 // Device-wide barrier number k (1-based, counted over the life of the context) of the
 // persistent kernel, in two halves so that work which does not depend on other
 // workgroups (the next phase's weight prefetch) can be issued between arriving and
-// waiting.  Two levels keep the contention on one address low: workgroup i adds to counter
-// i % 8; the last of each group adds to the top counter; the last of those publishes k in
-// `gen`, which everybody polls.  Counters are monotone, so nothing is ever reset.  Only
-// relaxed agent-scope atomics are used: published values are already device-coherent and
-// publish_barrier() makes every wave wait for its own stores before the arrival.
+// waiting.  Workgroup i adds one to counter i % 8 (eight counters on separate cache lines
+// keep the contention on one address low) and does not wait for the result; a waiting
+// workgroup reads all eight with independent loads and is released when they add up to
+// k * gridDim.x.  Counters are monotone, so nothing is ever reset and a sum of values read
+// at slightly different times can only under-count.  The hand-over is thus one atomic that
+// nobody waits on plus one round of loads; a hierarchy of counters with a published
+// generation needs two dependent atomics with their results and a store before anybody can
+// see the release.  Only relaxed agent-scope operations are used: published values are
+// already device-coherent and publish_barrier() makes every wave wait for its own stores
+// before the arrival.
 // The wait is bounded: after spin_limit polls, or once another workgroup has flagged an
 // error, the workgroup flags the error and goes on, so every wave reaches the end of the
-// kernel whatever happens.  gridDim.x must be a multiple of 8.
+// kernel whatever happens.
 __device__ __forceinline__ void barrier_arrive(DevState *st, unsigned long long k) {
   publish_barrier();
-  if (threadIdx.x == 0) {
-    const unsigned long long per = gridDim.x >> 3;
-    const unsigned long long t =
-        __hip_atomic_fetch_add(&st->grp[(blockIdx.x & 7) * 16], 1ull, __ATOMIC_RELAXED, RIVER_AG);
-    if (t == k * per - 1) {
-      const unsigned long long t2 = __hip_atomic_fetch_add(&st->top, 1ull, __ATOMIC_RELAXED, RIVER_AG);
-      if (t2 == k * 8 - 1) __hip_atomic_store(&st->gen, k, __ATOMIC_RELAXED, RIVER_AG);
-    }
-  }
+  if (threadIdx.x == 0)
+    (void)__hip_atomic_fetch_add(&st->grp[(blockIdx.x & 7) * 16], 1ull, __ATOMIC_RELAXED, RIVER_AG);
 }
 __device__ __forceinline__ void barrier_wait(DevState *st, unsigned long long k, int spin_limit) {
   if (threadIdx.x == 0) {
+    const unsigned long long target = k * gridDim.x;
     int spins = 0;
-    while (__hip_atomic_load(&st->gen, __ATOMIC_RELAXED, RIVER_AG) < k) {
-      if (++spins > spin_limit || __hip_atomic_load(&st->error, __ATOMIC_RELAXED, RIVER_AG) != 0) {
+    for (;;) {
+      unsigned long long c[8];
+#pragma unroll
+      for (int g = 0; g < 8; ++g) c[g] = __hip_atomic_load(&st->grp[g * 16], __ATOMIC_RELAXED, RIVER_AG);
+      const int err = __hip_atomic_load(&st->error, __ATOMIC_RELAXED, RIVER_AG);
+      if (((c[0] + c[1]) + (c[2] + c[3])) + ((c[4] + c[5]) + (c[6] + c[7])) >= target) break;
+      if (++spins > spin_limit || err != 0) {
         __hip_atomic_store(&st->error, 1, __ATOMIC_RELAXED, RIVER_AG);
         break;
       }
-      __builtin_amdgcn_s_sleep(8);
+      __builtin_amdgcn_s_sleep(4);
     }
   }
   lds_barrier();
