@@ -122,10 +122,10 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
   Pre<DT> pre;
   // block l (1-based) has just run: what will block l + 1 run as, as far as known now
   const bool guess = (l == 0) ? ctl.river : guess_river_after(A, ctl, l);
-  if (l > 0) { barrier_arrive(D.st, k); TRACE_ARRIVE(); }
+  if (l > 0) { barrier_arrive(D.bar, k); TRACE_ARRIVE(); }
   prefetch_phase<DT>(D, l, PH_QKV, guess, pre, l > 0 ? 0 : 2);
   if (l > 0) {
-    barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+    barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE();
     prefetch_phase<DT>(D, l, PH_QKV, guess, pre, 1);
     exit_test(D, A, l, ctl, lds);
     if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
@@ -136,17 +136,17 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
 template <int DT>
 __device__ RIVER_PSTEP_INLINE void pstep_attn(const Dev *Dp, StepArgs A, int l, unsigned long long k, float *lds) {
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
-  phase_attn<DT>(D, A, l, lds, [&] { barrier_arrive(D.st, k); TRACE_ARRIVE(); },
-                 [&] { barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE(); });
+  phase_attn<DT>(D, A, l, lds, [&] { barrier_arrive(D.bar, k); TRACE_ARRIVE(); },
+                 [&] { barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE(); });
 }
 template <int DT, int PH>
 __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, bool river, unsigned long long k,
                                         float *lds) {
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
   Pre<DT> pre;
-  barrier_arrive(D.st, k); TRACE_ARRIVE();
+  barrier_arrive(D.bar, k); TRACE_ARRIVE();
   prefetch_phase<DT>(D, l, PH, river, pre, 0);
-  barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+  barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE();
   prefetch_phase<DT>(D, l, PH, river, pre, 1);
   if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre);
   else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre);
@@ -158,9 +158,9 @@ __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
   const Ctl ctl = unpack_ctl(ctl_packed);
   Pre<DT> pre;
-  barrier_arrive(D.st, k); TRACE_ARRIVE();
+  barrier_arrive(D.bar, k); TRACE_ARRIVE();
   prefetch_head<DT>(D, pre, 0);
-  barrier_wait(D.st, k, D.spin_limit); TRACE_RELEASE();
+  barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE();
   prefetch_head<DT>(D, pre, 1);
   phase_head<DT>(D, A, ctl, lds, pre);
 }
@@ -238,10 +238,11 @@ __global__ void k_fill_bytes(uint4 *p, size_t n16, uint32_t word) {
 // ------------------------------------------------------------------ context
 
 struct Layout {
-  size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part,
+  size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part, bar,
       amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
 };
+
 
 struct river_ctx {
   river_config cfg;
@@ -337,6 +338,7 @@ static Layout make_layout(const river_config *c) {
   y.amax_val = take((size_t)kMaxGrid * 4);
   y.amax_idx = take((size_t)kMaxGrid * 4);
   y.state = take(sizeof(DevState));
+  y.bar = take(kBarBytes);
   y.rec_token = take((size_t)kRecords * 4);
   y.rec_exit = take((size_t)kRecords * 4);
   y.rec_sims = take((size_t)kRecords * c->n_layers * 4);
@@ -390,6 +392,7 @@ extern "C" int river_quantize_w4(const void *w, int64_t rows, int64_t cols, int3
 
 static int reset_state(river_ctx *x) {
   HIP_TRY(x, hipMemsetAsync(x->ws + x->lay.state, 0, sizeof(DevState), x->stream));
+  HIP_TRY(x, hipMemsetAsync(x->dev.bar, 0, kBarBytes, x->stream));
   x->bar_total = 0;
   return RIVER_OK;
 }
@@ -499,6 +502,7 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   D.cos_part = (float *)(ws + lay.cos_part);
   D.amax_val = (float *)(ws + lay.amax_val); D.amax_idx = (int *)(ws + lay.amax_idx);
   D.st = (DevState *)(ws + lay.state);
+  D.bar = (unsigned long long *)(ws + lay.bar);
   D.rec_token = (int *)(ws + lay.rec_token); D.rec_exit = (int *)(ws + lay.rec_exit);
   D.rec_sims = (float *)(ws + lay.rec_sims);
   D.trace = (unsigned long long *)(ws + lay.trace);
@@ -624,7 +628,7 @@ static int enqueue(river_ctx *x, int token, int forced_e, int want_head, int rec
 // After a synchronising call: did a bounded device wait give up?
 static int check_device_error(river_ctx *x) {
   int err = 0;
-  HIP_TRY(x, hipMemcpyAsync(&err, (char *)x->dev.st + offsetof(DevState, error), sizeof(int),
+  HIP_TRY(x, hipMemcpyAsync(&err, (char *)x->dev.bar + kBarErrorByte, sizeof(int),
                             hipMemcpyDeviceToHost, x->stream));
   HIP_TRY(x, hipStreamSynchronize(x->stream));
   if (err) {
@@ -772,7 +776,7 @@ extern "C" const char *river_last_error(const river_ctx *x) {
 
 extern "C" int river_destroy(river_ctx *x) {
   if (!x) return RIVER_OK;
-  hipStreamSynchronize(x->stream);
+  (void)hipStreamSynchronize(x->stream);
   delete x;
   return RIVER_OK;
 }

@@ -43,8 +43,6 @@ struct DevLayer {
 };
 
 struct DevState {
-  unsigned long long grp[8 * 16]; // barrier arrival counters, one per group of workgroups, a cache line apart
-  int error;                      // set when a bounded wait gave up
   int cur_token;                  // token produced by the last head phase
   int slot_river[2], slot_exit[2];// exit state of the current token, by block parity (one-kernel-per-phase mode)
   unsigned int head_cnt;
@@ -70,6 +68,7 @@ struct Dev {
   float *amax_val;                // [kMaxGrid]
   int *amax_idx;                  // [kMaxGrid]
   DevState *st;
+  unsigned long long *bar;        // barrier block (see barrier_arrive): 8 counters 128 B apart, error flag at byte 1024
   int *rec_token, *rec_exit;      // [kRecords]
   float *rec_sims;                // [kRecords][L]
   unsigned long long *trace;      // [5L][2][grid] barrier arrive / release times (RIVER_TRACE builds)
@@ -295,23 +294,27 @@ __device__ __forceinline__ void block_argmax(float &v, int &i, float *red) {
 // The wait is bounded: after spin_limit polls, or once another workgroup has flagged an
 // error, the workgroup flags the error and goes on, so every wave reaches the end of the
 // kernel whatever happens.
-__device__ __forceinline__ void barrier_arrive(DevState *st, unsigned long long k) {
+constexpr int kBarErrorByte = 1024;      // offset of the error flag in the barrier block
+constexpr int kBarBytes = 2048;
+__device__ __forceinline__ int *bar_error(unsigned long long *bar) { return (int *)((char *)bar + kBarErrorByte); }
+
+__device__ __forceinline__ void barrier_arrive(unsigned long long *bar, unsigned long long k) {
   publish_barrier();
   if (threadIdx.x == 0)
-    (void)__hip_atomic_fetch_add(&st->grp[(blockIdx.x & 7) * 16], 1ull, __ATOMIC_RELAXED, RIVER_AG);
+    (void)__hip_atomic_fetch_add(&bar[(blockIdx.x & 7) * 16], 1ull, __ATOMIC_RELAXED, RIVER_AG);
 }
-__device__ __forceinline__ void barrier_wait(DevState *st, unsigned long long k, int spin_limit) {
+__device__ __forceinline__ void barrier_wait(unsigned long long *bar, unsigned long long k, int spin_limit) {
   if (threadIdx.x == 0) {
     const unsigned long long target = k * gridDim.x;
     int spins = 0;
     for (;;) {
       unsigned long long c[8];
 #pragma unroll
-      for (int g = 0; g < 8; ++g) c[g] = __hip_atomic_load(&st->grp[g * 16], __ATOMIC_RELAXED, RIVER_AG);
-      const int err = __hip_atomic_load(&st->error, __ATOMIC_RELAXED, RIVER_AG);
+      for (int g = 0; g < 8; ++g) c[g] = __hip_atomic_load(&bar[g * 16], __ATOMIC_RELAXED, RIVER_AG);
+      const int err = __hip_atomic_load(bar_error(bar), __ATOMIC_RELAXED, RIVER_AG);
       if (((c[0] + c[1]) + (c[2] + c[3])) + ((c[4] + c[5]) + (c[6] + c[7])) >= target) break;
       if (++spins > spin_limit || err != 0) {
-        __hip_atomic_store(&st->error, 1, __ATOMIC_RELAXED, RIVER_AG);
+        __hip_atomic_store(bar_error(bar), 1, __ATOMIC_RELAXED, RIVER_AG);
         break;
       }
       __builtin_amdgcn_s_sleep(4);
