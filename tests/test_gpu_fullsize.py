@@ -4,7 +4,7 @@
  * the whole 8B-shape model (32 blocks, 128256-row head) with a short prompt and a forced
    exit schedule that covers backbone-only, river-mostly and mixed tokens;
  * two 8B-shape blocks over a 520-token prompt: the attention phase at the benchmark's
-   context length (5 splits, cross-workgroup combine), with exits at both depths;
+   context length (3 splits, merged by the output projection), with exits at both depths;
  * the whole 1B-shape model with a 64-token prompt.
 
 The oracle needs about a second per 8B-shape token on 16 cores, which bounds the samples."""
