@@ -280,7 +280,8 @@ def test_mid_shape_ragged_tiles(mode, cfg):
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
 def test_long_context_many_splits(mode, cfg0):
-    """Attention over 1100+ cached positions: 3 splits of 2 chunks, merged by the consumer."""
+    """Attention over 1100+ cached positions: 5 splits (one chunk of up to 256 positions per
+    workgroup), merged by the consumer."""
     needs_mode(cfg0, mode)
     say(f"long context {cfg0.name} mode={mode}")
     cfg = cfg0.with_(max_seq=1200, tau=0.675)
@@ -289,6 +290,29 @@ def test_long_context_many_splits(mode, cfg0):
     prompt = inputs.make_prompt(cfg.vocab, 1100, 91)
     run_teacher_forced(pair, prompt, 6, label="long")
     pair.compare_cache(1106)
+    pair.close()
+
+
+MANY_HEADS = configs.ModelConfig("many-heads-bf16", 2, 512, 128, 32, 64, 1024, 512, 10000.0, 1e-5,
+                                 configs.DTYPE_BF16, 1200, 1, 2.0)
+
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("cfg", [MANY_HEADS, MANY_HEADS.with_(name="many-heads-fp32", dtype=configs.DTYPE_F32)],
+                         ids=lambda c: c.name)
+def test_many_heads_several_chunks_per_workgroup(mode, cfg):
+    """128 query heads leave room for two splits only, so at 1100 positions a workgroup walks
+    550 of them: both chunks in flight, then the first one issued again (the loop of the
+    attention phase that the other shapes never take), one item per workgroup."""
+    needs_mode(cfg, mode)
+    say(f"many heads {cfg.name} mode={mode}")
+    w = inputs.make_weights(cfg, 5)
+    pair = Pair(cfg, w, mode)
+    prompt = inputs.make_prompt(cfg.vocab, 1100, 6)
+    sched = [1, 2, 2, 1]
+    exits = run_teacher_forced(pair, prompt, len(sched), sched, cfg.name)
+    assert exits == sched
+    pair.compare_cache(1100 + len(sched))
     pair.close()
 
 
