@@ -36,6 +36,7 @@ def needs_mode(cfg, mode):
 MID = configs.ModelConfig("mid-bf16", 3, 1024, 8, 2, 128, 2816, 1002, 500000.0, 1e-5,
                           configs.DTYPE_BF16, 192, 1, 2.0)
 MID_F32 = MID.with_(name="mid-fp32", dtype=configs.DTYPE_F32, n_q_heads=16, n_kv_heads=2, head_dim=64)
+MID_F32_HD128 = MID.with_(name="mid-fp32-hd128", dtype=configs.DTYPE_F32)     # fp32 cache rows of 128 elements
 
 
 def say(msg):
@@ -263,7 +264,7 @@ def test_kv_canary_every_slot_written(mode, cfg0):
 # ------------------------------------------------- several tiles, ragged tails
 
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
-@pytest.mark.parametrize("cfg", [MID, MID_F32], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [MID, MID_F32, MID_F32_HD128], ids=lambda c: c.name)
 def test_mid_shape_ragged_tiles(mode, cfg):
     needs_mode(cfg, mode)
     say(f"mid shape {cfg.name} mode={mode}")
