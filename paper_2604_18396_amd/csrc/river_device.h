@@ -1,19 +1,19 @@
 // Device code of the early-exit decode step for gfx950 (CDNA4, 64-wide wavefronts).
 //
 // One decode step is a fixed sequence of phases (River-LLM method section,
-// "Inference with Seamless Exit"): per block RMSNorm+QKV+RoPE+KV write, split-K GQA
-// attention, O-proj + residual, RMSNorm + gate/up + SwiGLU, down-proj + residual +
-// the three sums of the Eq. 1 similarity; then the original final norm + LM head +
-// argmax.  After a token has exited, the same phases run with the block's 4-bit river
-// twin and write K/V into the same cache slot.  Every phase strides over its work with
-// whatever grid it is given, so the same code serves the one-kernel-per-phase mode and
-// the persistent one-kernel-per-token mode.
+// "Inference with Seamless Exit"): per block RMSNorm + QKV, attention (which also applies
+// RoPE and writes this position's K/V), O-proj + residual, RMSNorm + gate/up + SwiGLU,
+// down-proj + residual + the three sums of the Eq. 1 similarity; then the original final
+// norm + LM head + argmax.  After a token has exited, the same phases run with the block's
+// 4-bit river twin and write K/V into the same cache slot.  Every phase strides over its
+// work with whatever grid it is given, so the same code serves the one-kernel-per-phase
+// mode and the persistent one-kernel-per-token mode.
 //
 // Design points for MI355X:
-//  * Weight streaming is HBM-bound at batch 1.  A wavefront owns whole rows; a "step" is
-//    16 non-temporal 16-byte loads per lane (16 KiB per wavefront, fully coalesced 1 KiB
-//    rows of loads), double buffered, so 8 wavefronts keep >= 128 KiB per CU in flight.
-//  * The first step of the NEXT phase is issued before the device-wide barrier that
+//  * Weight streaming is HBM-bound at batch 1.  A wavefront owns whole rows; a "step" is up
+//    to 8 non-temporal 16-byte loads per lane (8 KiB per wavefront, each load 1 KiB
+//    contiguous), two register sets in flight, so 8 wavefronts keep 128 KiB per CU in flight.
+//  * The first steps of the NEXT phase are issued before the device-wide barrier that
 //    separates the phases: weights do not depend on activations, so the HBM pipe stays
 //    busy while the workgroups synchronise and exchange the small activation vector.
 //  * Activations cross workgroups (and XCDs, whose L2s are not coherent with each other)
@@ -970,7 +970,7 @@ __device__ __forceinline__ bool guess_river_after(const StepArgs &A, const Ctl &
 // a0 + a1: (block 1: h(0) = E[token]); x = RMSNorm(h) * g1; [q;k;v] = W x, published raw.
 // RoPE, the rounding of k, v to the cache dtype and the write of slot (l, pos) happen in the
 // attention phase (a2 there), which frees the row-to-wavefront assignment here: single rows,
-// three per wavefront at the 8B shape, instead of rotation pairs (one and a half).
+// three per wavefront at the 8B shape.
 template <int DT>
 __device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
   RIVER_MARK(D, 16);
