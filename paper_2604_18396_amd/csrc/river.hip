@@ -103,11 +103,12 @@ __global__ __launch_bounds__(kBlock) void k_head(const Dev *Dp, StepArgs A) {
 #define TRACE_RELEASE()
 #endif
 
-// Persistent mode: one launch per token.  Each phase is a separate (not inlined) function
-// with its own register allocation.  The device-wide barrier that PRECEDES a phase is
-// executed inside that phase's function, and the phase's first weight loads are issued
-// between arriving at and waiting on it, so they are in flight while the workgroups
-// synchronise.  k is the index of that barrier (0: none, first phase of the launch).
+// Persistent mode: one launch per token.  The phase functions are inlined into one loop body
+// (as separate functions every call saved and restored ~100 registers per lane).  The
+// device-wide barrier that PRECEDES a phase is executed inside that phase's function, and
+// the phase's first weight loads are issued between arriving at and waiting on it, so they
+// are in flight while the workgroups synchronise.  k is the index of that barrier (0: none,
+// first phase of the launch).
 #ifndef RIVER_PSTEP_INLINE
 #define RIVER_PSTEP_INLINE __forceinline__
 #endif
