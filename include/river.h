@@ -12,9 +12,11 @@
  *
  * Conventions
  *  - Every pointer is marked HOST or DEVICE.  Device memory is allocated by the
- *    caller (for example through torch) and handed over; the library allocates
- *    no device memory.  The context borrows weights and workspace: they must
- *    outlive it.  The context owns only host bookkeeping.
+ *    caller (for example through torch) and handed over.  The one exception:
+ *    the first river_create on a device allocates 128 KiB of uncached device
+ *    memory for the counters of the device-wide barrier (2 KiB per live
+ *    context, at most 64 contexts per device); it is kept until the process
+ *    ends.  The context borrows weights and workspace: they must outlive it.
  *  - All calls return RIVER_OK (0) or a negative RIVER_E* code, never throw and
  *    never abort.  river_last_error() gives a text for the last failure.
  *  - Matrices are [out, in] row-major (nn.Linear orientation).  dtype selects

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -239,11 +240,44 @@ __global__ void k_fill_bytes(uint4 *p, size_t n16, uint32_t word) {
 // ------------------------------------------------------------------ context
 
 struct Layout {
-  size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part, bar,
+  size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part,
       amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
 };
 
+
+// Barrier blocks that are polled with scalar loads live in uncached device memory, which is
+// allocated once per device and process and never freed (freeing uncached memory that a
+// kernel has read is not safe on all systems); contexts take and return slots of it.
+namespace {
+constexpr int kBarSlots = 64, kBarDevices = 16;
+std::mutex g_bar_mu;
+char *g_bar_pool[kBarDevices];
+unsigned long long g_bar_used[kBarDevices];
+}
+static int bar_acquire(int dev, int *slot, char **ptr, std::string *why) {
+  std::lock_guard<std::mutex> lk(g_bar_mu);
+  if (dev < 0 || dev >= kBarDevices) { *why = "device index too large for the barrier pool"; return RIVER_EINVAL; }
+  if (!g_bar_pool[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipExtMallocWithFlags(&p, (size_t)kBarSlots * kBarBytes, hipDeviceMallocUncached);
+    if (e != hipSuccess) { *why = std::string("uncached barrier pool: ") + hipGetErrorString(e); return RIVER_EHIP; }
+    g_bar_pool[dev] = (char *)p;
+  }
+  for (int i = 0; i < kBarSlots; ++i)
+    if (!(g_bar_used[dev] >> i & 1ull)) {
+      g_bar_used[dev] |= 1ull << i;
+      *slot = i;
+      *ptr = g_bar_pool[dev] + (size_t)i * kBarBytes;
+      return RIVER_OK;
+    }
+  *why = "more than 64 live contexts on one device";
+  return RIVER_ENOSPC;
+}
+static void bar_release(int dev, int slot) {
+  std::lock_guard<std::mutex> lk(g_bar_mu);
+  if (slot >= 0) g_bar_used[dev] &= ~(1ull << slot);
+}
 
 struct river_ctx {
   river_config cfg;
@@ -257,6 +291,9 @@ struct river_ctx {
   bool have_river;
   long long steps;      // decode steps recorded so far
   unsigned long long bar_total;
+  int bar_slot = -1;    // slot of the process-wide barrier pool
+  int bar_device = 0;
+  ~river_ctx() { bar_release(bar_device, bar_slot); }
   int grid_persist, grid_gemv, block;
   size_t lds_bytes;
   bool broken;
@@ -339,7 +376,6 @@ static Layout make_layout(const river_config *c) {
   y.amax_val = take((size_t)kMaxGrid * 4);
   y.amax_idx = take((size_t)kMaxGrid * 4);
   y.state = take(sizeof(DevState));
-  y.bar = take(kBarBytes);
   y.rec_token = take((size_t)kRecords * 4);
   y.rec_exit = take((size_t)kRecords * 4);
   y.rec_sims = take((size_t)kRecords * c->n_layers * 4);
@@ -503,7 +539,14 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   D.cos_part = (float *)(ws + lay.cos_part);
   D.amax_val = (float *)(ws + lay.amax_val); D.amax_idx = (int *)(ws + lay.amax_idx);
   D.st = (DevState *)(ws + lay.state);
-  D.bar = (unsigned long long *)(ws + lay.bar);
+  {
+    char *bp = nullptr;
+    std::string why2;
+    x->bar_device = dev_id;
+    const int rc = bar_acquire(dev_id, &x->bar_slot, &bp, &why2);
+    if (rc != RIVER_OK) { g_create_err = why2; delete x; return rc; }
+    D.bar = (unsigned long long *)bp;
+  }
   D.rec_token = (int *)(ws + lay.rec_token); D.rec_exit = (int *)(ws + lay.rec_exit);
   D.rec_sims = (float *)(ws + lay.rec_sims);
   D.trace = (unsigned long long *)(ws + lay.trace);

@@ -303,21 +303,42 @@ __device__ __forceinline__ void barrier_arrive(unsigned long long *bar, unsigned
   if (threadIdx.x == 0)
     (void)__hip_atomic_fetch_add(&bar[(blockIdx.x & 7) * 16], 1ull, __ATOMIC_RELAXED, RIVER_AG);
 }
+// The barrier block lives in uncached device memory and is polled with scalar loads: vector
+// loads of a wavefront return in order, so a vector poll would wait for the weight prefetch
+// the same wavefront has just issued -- in the workgroups that arrive last, which then start
+// the next phase last (measured: 2.6 % of a dense token).  glc makes the scalar loads miss the
+// scalar cache; uncached memory keeps the counters out of the (per-XCD, mutually
+// non-coherent) L2s.  The first wavefront polls; the others wait at the workgroup barrier.
+__device__ __forceinline__ bool barrier_poll(const unsigned long long *bar, unsigned long long target, int &err) {
+  unsigned long long c0, c1, c2, c3, c4, c5, c6, c7;
+  asm volatile(
+      "s_load_dwordx2 %0, %9, 0x0 glc\n\t"
+      "s_load_dwordx2 %1, %9, 0x80 glc\n\t"
+      "s_load_dwordx2 %2, %9, 0x100 glc\n\t"
+      "s_load_dwordx2 %3, %9, 0x180 glc\n\t"
+      "s_load_dwordx2 %4, %9, 0x200 glc\n\t"
+      "s_load_dwordx2 %5, %9, 0x280 glc\n\t"
+      "s_load_dwordx2 %6, %9, 0x300 glc\n\t"
+      "s_load_dwordx2 %7, %9, 0x380 glc\n\t"
+      "s_load_dword %8, %9, 0x400 glc\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(c0), "=&s"(c1), "=&s"(c2), "=&s"(c3), "=&s"(c4), "=&s"(c5), "=&s"(c6), "=&s"(c7), "=&s"(err)
+      : "s"(bar)
+      : "memory");
+  return ((c0 + c1) + (c2 + c3)) + ((c4 + c5) + (c6 + c7)) >= target;
+}
 __device__ __forceinline__ void barrier_wait(unsigned long long *bar, unsigned long long k, int spin_limit) {
-  if (threadIdx.x == 0) {
+  if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) {
     const unsigned long long target = k * gridDim.x;
     int spins = 0;
     for (;;) {
-      unsigned long long c[8];
-#pragma unroll
-      for (int g = 0; g < 8; ++g) c[g] = __hip_atomic_load(&bar[g * 16], __ATOMIC_RELAXED, RIVER_AG);
-      const int err = __hip_atomic_load(bar_error(bar), __ATOMIC_RELAXED, RIVER_AG);
-      if (((c[0] + c[1]) + (c[2] + c[3])) + ((c[4] + c[5]) + (c[6] + c[7])) >= target) break;
+      int err;
+      if (barrier_poll(bar, target, err)) break;
       if (++spins > spin_limit || err != 0) {
-        __hip_atomic_store(bar_error(bar), 1, __ATOMIC_RELAXED, RIVER_AG);
+        if ((threadIdx.x & 63) == 0) __hip_atomic_store(bar_error(bar), 1, __ATOMIC_RELAXED, RIVER_AG);
         break;
       }
-      __builtin_amdgcn_s_sleep(4);
+      __builtin_amdgcn_s_sleep(2);
     }
   }
   lds_barrier();
