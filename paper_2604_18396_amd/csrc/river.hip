@@ -55,7 +55,8 @@ __global__ __launch_bounds__(kBlock) void k_qkv(const Dev *Dp, StepArgs A, int l
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_attn(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
-  phase_attn<DT>(*RIVER_CONSTANT(Dev, Dp), A, l, lds, [] {}, [] {});
+  DevRef D = *RIVER_CONSTANT(Dev, Dp);
+  phase_attn<DT>(D, A, l, load_ctl(D, l), lds, [] {}, [] {});
 }
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_oproj(const Dev *Dp, StepArgs A, int l) {
@@ -136,9 +137,10 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
   return pack_ctl(ctl);
 }
 template <int DT>
-__device__ RIVER_PSTEP_INLINE void pstep_attn(const Dev *Dp, StepArgs A, int l, unsigned long long k, float *lds) {
+__device__ RIVER_PSTEP_INLINE void pstep_attn(const Dev *Dp, StepArgs A, int l, int ctl_packed, unsigned long long k,
+                                        float *lds) {
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
-  phase_attn<DT>(D, A, l, lds, [&] { barrier_arrive(D.bar, k); TRACE_ARRIVE(); },
+  phase_attn<DT>(D, A, l, unpack_ctl(ctl_packed), lds, [&] { barrier_arrive(D.bar, k); TRACE_ARRIVE(); },
                  [&] { barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE(); });
 }
 template <int DT, int PH>
@@ -180,7 +182,7 @@ __global__ __launch_bounds__(kBlock) void k_step_persistent(const Dev *Dp, StepA
   for (int l = 0; l < L; ++l) {
     ctl = pstep_qkv<DT>(Dp, A, l, ctl, l ? ++k : 0, lds);
     const bool river = ctl & 1;
-    pstep_attn<DT>(Dp, A, l, ++k, lds);
+    pstep_attn<DT>(Dp, A, l, ctl, ++k, lds);
     pstep_gemv<DT, PH_O>(Dp, A, l, river, ++k, lds);
     pstep_gemv<DT, PH_GU>(Dp, A, l, river, ++k, lds);
     pstep_gemv<DT, PH_DOWN>(Dp, A, l, river, ++k, lds);

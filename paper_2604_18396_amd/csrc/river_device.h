@@ -970,16 +970,35 @@ __device__ __forceinline__ float similarity_from_partials(DevRef D, float *red) 
 }
 
 // Exit test after backbone block l1 (1-based), Eq. 1: first hit at or above L_s, never at
-// L, strict '>'; a forced exit position overrides the threshold.
+// L, strict '>'; a forced exit position overrides the threshold.  With a forced position the
+// decision needs no similarity, so the reduction is kept off the path of every workgroup:
+// the similarity is then computed for the record only, by one workgroup that has nothing to
+// do in the attention phase (record_similarity).
 __device__ __forceinline__ void exit_test(DevRef D, const StepArgs &A, int l1, Ctl &ctl, float *lds) {
   if (ctl.river) return;
+  const bool may = l1 >= D.min_exit && l1 < D.L;
+  if (A.forced_e >= 0) {
+    if (may && A.forced_e == l1) { ctl.river = true; ctl.exit_pos = l1; }
+    return;
+  }
   const float s = similarity_from_partials(D, lds_red(D, lds));
   if (blockIdx.x == 0 && threadIdx.x == 0 && A.rec_slot >= 0)
-    D.rec_sims[(size_t)A.rec_slot * D.L + (l1 - 1)] = s;
-  if (l1 >= D.min_exit && l1 < D.L && ((A.forced_e < 0 && s > D.tau) || A.forced_e == l1)) {
+    pub(D.rec_sims + (size_t)A.rec_slot * D.L + (l1 - 1), s);
+  if (may && s > D.tau) {
     ctl.river = true;
     ctl.exit_pos = l1;
   }
+}
+// The similarity of backbone block l1 for the record of a forced-exit step (see exit_test).
+// ctl is the exit state AFTER the test that followed block l1.  Called by every workgroup in
+// the attention phase of the next block; the last workgroup does the work (the per-workgroup
+// sums it reads stay valid until the next down-projection).
+__device__ __forceinline__ void record_similarity(DevRef D, const StepArgs &A, int l1, const Ctl &ctl, float *lds) {
+  if (l1 < 1 || A.forced_e < 0 || A.rec_slot < 0 || blockIdx.x != gridDim.x - 1) return;
+  if (ctl.river && ctl.exit_pos < l1) return;          // block l1 ran as a river block: no similarity
+  const float s = similarity_from_partials(D, lds_red(D, lds));
+  // device-coherent stores: the record row is written by workgroups of different XCDs
+  if (threadIdx.x == 0) pub(D.rec_sims + (size_t)A.rec_slot * D.L + (l1 - 1), s);
 }
 
 // Which format will block l1 + 1 run in, as far as can be known before block l1's
@@ -1405,7 +1424,7 @@ __device__ __forceinline__ void attn_items(DevRef D, const StepArgs &A, int l, f
 // arriving and waiting.  Register arrays are sized by the elements per lane (head_dim 64
 // or 128).
 template <int DT, class Arrive, class Wait>
-__device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, float *lds,
+__device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, const Ctl &ctl, float *lds,
                                            Arrive arrive, Wait wait) {
   const int lane = fresh_lane();
   auto run = [&](auto el) {
@@ -1417,6 +1436,8 @@ __device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, f
     attn_items<DT, EL>(D, A, l, lds, lane, c);
   };
   if (D.hd == 128) run(IC<8>()); else run(IC<4>());
+  lds_barrier();                                   // the merge area of the last item is read
+  record_similarity(D, A, l, ctl, lds);
 }
 
 // a4: h1 = h + W_o o
@@ -1527,7 +1548,7 @@ __device__ __forceinline__ void phase_head(DevRef D, const StepArgs &A, const Ct
   float *red = lds_red(D, lds);
   if (!ctl.river && A.rec_slot >= 0) {      // similarity of the last backbone block: recorded, never tested
     const float s = similarity_from_partials(D, red);
-    if (blockIdx.x == 0 && threadIdx.x == 0) D.rec_sims[(size_t)A.rec_slot * D.L + (D.L - 1)] = s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) pub(D.rec_sims + (size_t)A.rec_slot * D.L + (D.L - 1), s);
   }
   stage_norm<DT>(D.hidden + (size_t)D.L * D.d, D.final_norm, D.d, D.eps, run_log2<DT>(false, D.d), lds, red);
   const int lane = pre.lane;
@@ -1578,7 +1599,7 @@ __device__ __forceinline__ Ctl ctl_init(DevRef D, const StepArgs &A) {
 __device__ __forceinline__ void record_init(DevRef D, const StepArgs &A) {
   if (blockIdx.x == 0 && A.rec_slot >= 0)
     for (int i = threadIdx.x; i < D.L; i += blockDim.x)
-      D.rec_sims[(size_t)A.rec_slot * D.L + i] = __uint_as_float(0x7fc00000u);
+      pub(D.rec_sims + (size_t)A.rec_slot * D.L + i, __uint_as_float(0x7fc00000u));
 }
 
 }  // namespace river
