@@ -252,6 +252,27 @@ __device__ __forceinline__ float block_sum(float v, float *red) {
   return t;
 }
 
+// K sums at once (one pair of workgroup barriers), each in the order block_sum uses.
+// red: LDS scratch of at least 8 K floats.
+template <int K>
+__device__ __forceinline__ void block_sum_k(float (&v)[K], float *red) {
+#pragma unroll
+  for (int k = 0; k < K; ++k) v[k] = wave_sum(v[k]);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  lds_barrier();
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) red[w * K + k] = v[k];
+  }
+  lds_barrier();
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    float t = 0.f;
+    for (int i = 0; i < nw; ++i) t += red[i * K + k];
+    v[k] = t;
+  }
+}
+
 __device__ __forceinline__ void argmax_take(float &v, int &i, float v2, int i2) {
   if (v2 > v || (v2 == v && i2 < i)) { v = v2; i = i2; }   // lower index wins ties
 }
@@ -960,7 +981,9 @@ __device__ __forceinline__ float similarity_from_partials(DevRef D, float *red) 
     const float4 v = sub4(D.cos_part, i * 4);
     pab += v.x; paa += v.y; pbb += v.z;
   }
-  pab = block_sum(pab, red); paa = block_sum(paa, red); pbb = block_sum(pbb, red);
+  float p3[3] = {pab, paa, pbb};
+  block_sum_k<3>(p3, red);
+  pab = p3[0]; paa = p3[1]; pbb = p3[2];
   float s = 0.f;
   if (paa > 0.f && pbb > 0.f) {
     s = pab / (sqrtf(paa) * sqrtf(pbb));
@@ -1517,11 +1540,12 @@ __device__ __forceinline__ void phase_down(DevRef D, const StepArgs &A, int l, b
   RIVER_MARK(D, 30);
   if (river) return;                    // river blocks take no exit test
   float *red = lds_red(D, lds);
-  ab = block_sum(ab, red); aa = block_sum(aa, red); bb = block_sum(bb, red);
+  float p3[3] = {ab, aa, bb};
+  block_sum_k<3>(p3, red);
   if (threadIdx.x == 0) {
-    pub(D.cos_part + blockIdx.x * 4 + 0, ab);
-    pub(D.cos_part + blockIdx.x * 4 + 1, aa);
-    pub(D.cos_part + blockIdx.x * 4 + 2, bb);
+    pub(D.cos_part + blockIdx.x * 4 + 0, p3[0]);
+    pub(D.cos_part + blockIdx.x * 4 + 1, p3[1]);
+    pub(D.cos_part + blockIdx.x * 4 + 2, p3[2]);
   }
 }
 
