@@ -664,7 +664,12 @@ static int enqueue(river_ctx *x, int token, int forced_e, int want_head, int rec
   const int T = x->pos + 1;
   // one workgroup per (query head, split); splits as far as there are workgroups for them
   const int max_splits = std::max(1, std::min(kMaxSplits, x->grid_persist / x->cfg.n_q_heads));
-  A.n_splits = std::max(1, std::min(max_splits, (T + kAttnPosPerSplit - 1) / kAttnPosPerSplit));
+  // One split per kAttnPosPerSplit positions up to four splits; every further split costs each
+  // consumer another read of all partial outputs, so beyond that a workgroup first takes
+  // twice the positions (measured at contexts 768 .. 4096).
+  int S = (T + kAttnPosPerSplit - 1) / kAttnPosPerSplit;
+  if (S > 4) S = std::max(4, (T + 2 * kAttnPosPerSplit - 1) / (2 * kAttnPosPerSplit));
+  A.n_splits = std::max(1, std::min(max_splits, S));
   A.bar_base = 0;
   const int rc = x->cfg.dtype == RIVER_BF16 ? launch_step<1>(x, A) : launch_step<0>(x, A);
   if (rc == RIVER_OK) x->pos += 1;
