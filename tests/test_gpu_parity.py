@@ -348,6 +348,32 @@ def test_async_steps_and_records_match_sync():
     g.close()
 
 
+@pytest.mark.parametrize("cfg0", TINY_BOTH, ids=lambda c: c.name)
+def test_one_token_prompt_and_rewind_replay(cfg0):
+    """A prompt of a single token; then a rewind by three positions followed by the same
+    steps gives the same bits as the first pass (the rewritten cache slots hold the same
+    values) and still matches the oracle, which is rewound the same way."""
+    say(f"short prompt + rewind {cfg0.name}")
+    cfg = cfg0.with_(tau=0.675)
+    w = inputs.make_weights(cfg, configs.C1.seed_weights)
+    pair = Pair(cfg, w, None)
+    tok = pair.prefill([7])
+    toks, hs = [tok], []
+    for i in range(6):
+        tok, e, _ = pair.step(tok, what=f"pass 1 step {i}")
+        toks.append(tok)
+        hs.append(pair.g.hidden())
+    pair.g.rewind(4)                 # positions 4, 5, 6 are decoded again
+    pair.o.rewind(4)
+    tok = toks[3]
+    for i in range(3, 6):
+        tok, e, _ = pair.step(tok, what=f"pass 2 step {i}")
+        assert tok == toks[i + 1]
+        np.testing.assert_array_equal(pair.g.hidden(), hs[i])
+    pair.compare_cache(7)
+    pair.close()
+
+
 def test_error_paths_through_the_abi():
     say("error paths")
     cfg = configs.TINY.with_(max_seq=8)
