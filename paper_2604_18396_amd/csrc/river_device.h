@@ -1228,33 +1228,38 @@ __device__ __forceinline__ void attn_prefetch(DevRef D, const StepArgs &A, int l
   }
 }
 
-// Merge the S <= kMaxSplits published split partials of query head h, elements e4 .. e4+3,
+// Merge the S <= kMaxSplits published split partials of query head h, elements e8 .. e8+7,
 // in split order (independent of timing); all loads go out before the first is used.
-__device__ __forceinline__ float4 combine_splits(DevRef D, int S, int h, int e4) {
+__device__ __forceinline__ void combine_splits8(DevRef D, int S, int h, int e8, float (&out)[8]) {
   const size_t p_base = (size_t)h * kMaxSplits;
-  float4 ml[kMaxSplits], po[kMaxSplits];
+  float4 ml[kMaxSplits], pa[kMaxSplits], pb[kMaxSplits];
 #pragma unroll
   for (int j = 0; j < kMaxSplits; ++j) {
     if (j < S) {                                       // uniform
       ml[j] = sub4(D.part_ml, (int)((p_base + j) * 4));
-      po[j] = sub4(D.part_o, (int)((p_base + j) * D.hd + e4));
+      pa[j] = sub4(D.part_o, (int)((p_base + j) * D.hd + e8));
+      pb[j] = sub4(D.part_o, (int)((p_base + j) * D.hd + e8 + 4));
     } else {
-      ml[j] = po[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      ml[j] = pa[j] = pb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
   float M = kNegBig;
 #pragma unroll
   for (int j = 0; j < kMaxSplits; ++j) M = fmaxf(M, j < S ? ml[j].x : kNegBig);
   float Lsum = 0.f;
-  float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) out[e] = 0.f;
 #pragma unroll
   for (int j = 0; j < kMaxSplits; ++j) {
     const float cj = j < S ? __builtin_amdgcn_exp2f(ml[j].x - M) : 0.f;
     Lsum = fmaf(ml[j].y, cj, Lsum);
-    O.x = fmaf(po[j].x, cj, O.x); O.y = fmaf(po[j].y, cj, O.y);
-    O.z = fmaf(po[j].z, cj, O.z); O.w = fmaf(po[j].w, cj, O.w);
+    out[0] = fmaf(pa[j].x, cj, out[0]); out[1] = fmaf(pa[j].y, cj, out[1]);
+    out[2] = fmaf(pa[j].z, cj, out[2]); out[3] = fmaf(pa[j].w, cj, out[3]);
+    out[4] = fmaf(pb[j].x, cj, out[4]); out[5] = fmaf(pb[j].y, cj, out[5]);
+    out[6] = fmaf(pb[j].z, cj, out[6]); out[7] = fmaf(pb[j].w, cj, out[7]);
   }
-  return make_float4(O.x / Lsum, O.y / Lsum, O.z / Lsum, O.w / Lsum);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) out[e] /= Lsum;
 }
 
 // Stage the attention output for the output projection: a copy of the finished vector
@@ -1268,15 +1273,15 @@ __device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, int 
     return;
   }
   lds_barrier();
-  if (lp < 0) {
-    for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
-      const float4 a = combine_splits(D, S, i / D.hd, i % D.hd), b = combine_splits(D, S, i / D.hd, i % D.hd + 4);
-      const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
+    float v[8];
+    combine_splits8(D, S, i / D.hd, i % D.hd, v);
+    if (lp < 0) {
       half_store8(xh, n, i, v);
+    } else {
+      *(float4 *)(xl + x_slot(i, lp)) = make_float4(v[0], v[1], v[2], v[3]);
+      *(float4 *)(xl + x_slot(i + 4, lp)) = make_float4(v[4], v[5], v[6], v[7]);
     }
-  } else {
-    for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4)
-      *(float4 *)(xl + x_slot(i, lp)) = combine_splits(D, S, i / D.hd, i % D.hd);
   }
   lds_barrier();
 }
