@@ -15,7 +15,7 @@
  *     hidden states is compared with tau; on exit the remaining blocks run as
  *     river twins, chained serially, and the ORIGINAL final norm + LM head
  *     produce the logits.  Generation phase = token-level exit; the prompt is
- *     processed at one unified depth (here: the full depth L).
+ *     processed at one unified depth given by the caller (default: the full depth L).
  *   - Table "Evaluation results ... Exit Position" caption: the exit position
  *     is the number of executed backbone layers.
  *
@@ -427,15 +427,22 @@ static int step(orc_ctx *x, int token, int forced_e, int want_logits, int *out_t
   return ORC_OK;
 }
 
-/* prompt at full depth (every prompt position has exit position L); returns the
- * greedy token after the last prompt position */
-int orc_prefill(orc_ctx *x, const int32_t *tokens, int n, int32_t *out_token) {
+/*
+ * Prefill phase ("Inference with Seamless Exit", the list of phases: the prompt is
+ * processed by sequence-level exit, every prompt token leaving the backbone at one
+ * unified depth).  exit_layer is that depth e_p: every prompt position runs backbone
+ * blocks 1..e_p and river twins e_p+1..L, each writing its K/V to the shared slot.
+ * e_p = L (or negative) is the full depth.  How e_p is chosen the paper does not say:
+ * it is the caller's.  Returns the greedy token after the last prompt position.
+ */
+int orc_prefill(orc_ctx *x, const int32_t *tokens, int n, int exit_layer, int32_t *out_token) {
   if (!x || !tokens || n < 1) return ORC_EINVAL;
+  int ep = exit_layer < 0 ? x->c.n_layers : exit_layer;
   x->pos = 0;
   memset(x->written, 0, (size_t)x->c.n_layers * x->c.max_seq);
   for (int i = 0; i < n; ++i) {
     int tok = 0, e = 0;
-    int rc = step(x, tokens[i], x->c.n_layers, i == n - 1, &tok, &e);
+    int rc = step(x, tokens[i], ep, i == n - 1, &tok, &e);
     if (rc) return rc;
     if (i == n - 1 && out_token) *out_token = tok;
   }

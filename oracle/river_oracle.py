@@ -54,7 +54,7 @@ def lib():
                                  C.POINTER(_Layer), C.POINTER(_QLayer), C.POINTER(C.c_void_p)]
         L.orc_destroy.argtypes = [C.c_void_p]
         L.orc_destroy.restype = None
-        L.orc_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int32)]
+        L.orc_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int32)]
         L.orc_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                       C.POINTER(C.c_int32), C.c_void_p]
         L.orc_rewind.argtypes = [C.c_void_p, C.c_int]
@@ -165,10 +165,12 @@ class Oracle:
         except Exception:
             pass
 
-    def prefill(self, tokens) -> int:
+    def prefill(self, tokens, exit_layer: int | None = None) -> int:
+        """Prefill phase at the unified depth exit_layer (None: the full depth L)."""
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         out = C.c_int32()
-        rc = lib().orc_prefill(self._h, _ptr(t), len(t), C.byref(out))
+        rc = lib().orc_prefill(self._h, _ptr(t), len(t), -1 if exit_layer is None else int(exit_layer),
+                               C.byref(out))
         if rc:
             raise ValueError(f"orc_prefill failed: {rc}")
         return out.value

@@ -284,3 +284,54 @@ def test_similarity_equal_to_tau_does_not_exit(tiny_setup):
     o2 = ro.Oracle(cfg.with_(tau=float(np.nextafter(np.float32(1.0), np.float32(0.0)))), w2, river2)
     o2.prefill([1, 2])
     assert o2.decode_step(3)[1] == cfg.min_exit_layer
+
+
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
+@pytest.mark.parametrize("ep", [0, 2, 3, 4])
+def test_sequence_level_exit_prefill_equals_plain_definition(cfg0, ep):
+    """Prefill phase with sequence-level exit (the phase list of "Inference with Seamless
+    Exit"): every prompt position leaves the backbone at the unified depth e_p.  Pinned to
+    the plain definition with e_j = e_p for every prompt position, followed by token-level
+    steps; e_p = L must be today's full-depth prefill bit for bit."""
+    cfg = cfg0.with_(min_exit_layer=0)
+    L = cfg.n_layers
+    w = inputs.make_weights(cfg, 41)
+    river = ro.quantize_river(cfg, w)
+    prompt = inputs.make_prompt(cfg.vocab, 9, 42)
+    sched = [4, 1, 0, 3, 2]
+    o = ro.Oracle(cfg, w, river)
+    tok = o.prefill(prompt, ep)
+    h_prefill, l_prefill = o.hidden(), o.logits()
+    toks, hids, logits = [tok], [], []
+    for e in sched:
+        t, eo, _ = o.decode_step(toks[-1], e)
+        assert eo == e
+        toks.append(t); hids.append(o.hidden()); logits.append(o.logits())
+    ref = pd.run(cfg, w, river, list(prompt) + toks[:-1], exits=[ep] * len(prompt) + sched)
+    np.testing.assert_allclose(h_prefill, ref["hidden"][len(prompt) - 1], rtol=1e-8, atol=1e-11)
+    np.testing.assert_allclose(l_prefill, ref["logits"][len(prompt) - 1], rtol=1e-8, atol=1e-11)
+    assert list(ref["tokens"][len(prompt) - 1:]) == toks
+    for i in range(len(sched)):
+        np.testing.assert_allclose(hids[i], ref["hidden"][len(prompt) + i], rtol=1e-8, atol=1e-11)
+        np.testing.assert_allclose(logits[i], ref["logits"][len(prompt) + i], rtol=1e-8, atol=1e-11)
+    assert np.all(o.written()[:, :len(prompt) + len(sched)] == 1)
+    if ep == L:
+        full = ro.Oracle(cfg, w, river)
+        assert full.prefill(prompt) == tok
+        np.testing.assert_array_equal(full.hidden(), h_prefill)
+        np.testing.assert_array_equal(full.kcache()[:, :len(prompt)], o.kcache()[:, :len(prompt)])
+    else:
+        # the shallow prefill really differs from the full-depth one (the river is lossy)
+        full = ro.Oracle(cfg, w, river)
+        full.prefill(prompt)
+        assert np.abs(full.kcache()[L - 1, :len(prompt)] - o.kcache()[L - 1, :len(prompt)]).max() > 1e-5
+
+
+def test_prefill_exit_layer_range(tiny_setup):
+    cfg, w, river = tiny_setup
+    o = ro.Oracle(cfg, w, river)
+    with pytest.raises(ValueError):
+        o.prefill([1, 2, 3], 1)                   # below L_s = 2
+    with pytest.raises(ValueError):
+        o.prefill([1, 2, 3], cfg.n_layers + 1)
+    assert 0 <= o.prefill([1, 2, 3], 2) < cfg.vocab
