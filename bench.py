@@ -39,14 +39,16 @@ def timed_steps(g, torch, forced, k):
     torch.cuda.synchronize()
     start.record(stream)
     for i in range(k):
-        g.decode_step(None, int(forced[i]), sync=False)
+        g.decode_step(None, None if forced[i] is None else int(forced[i]), sync=False)
     end.record(stream)
     torch.cuda.synchronize()
     return start.elapsed_time(end)        # ms
 
 
-def cpu_baseline(cfg, weights, sched, budget_steps):
-    """The oracle as it stands, on the host cores, on a bounded sample of the workload."""
+def cpu_baseline(cfg, weights, sched, budget_steps, budget_seconds=25.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the workload:
+    at most budget_steps decode steps (and at most the schedule's length, and about
+    budget_seconds) of the same shape and exit schedule after a 4-token prompt."""
     from oracle import river_oracle as ro
     from paper_2604_18396_amd import inputs
     t0 = time.time()
@@ -57,10 +59,10 @@ def cpu_baseline(cfg, weights, sched, budget_steps):
     log(f"oracle ready (quantise + 4-token prompt) in {time.time() - t0:.1f}s")
     t1 = time.time()
     n = 0
-    for i in range(budget_steps):
+    for i in range(min(int(budget_steps), len(sched), 56)):
         tok, e, _ = o.decode_step(tok, int(sched[i]))
         n += 1
-        if time.time() - t1 > 25.0:
+        if time.time() - t1 > budget_seconds:
             break
     dt = time.time() - t1
     o.close()
@@ -68,6 +70,20 @@ def cpu_baseline(cfg, weights, sched, budget_steps):
     return {"value": n / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"{n} decode steps of the same shape and exit schedule after a 4-token "
                       f"prompt (context 5..{4 + n}); fp64 C oracle with OpenMP"}
+
+
+def calibrate_copy(mib, iters):
+    """A plain device copy of known size, for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    counters: run `rocprofv3 --pmc FETCH_SIZE -- python3 bench.py --calibrate-copy 1024`."""
+    import torch
+    n = mib << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(iters):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibration_copy_mib": mib, "launches": iters}), flush=True)
 
 
 def main():
@@ -79,6 +95,8 @@ def main():
     ap.add_argument("--mode", default="persistent", choices=["persistent", "kernels"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=24)
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of MIB MiB three times (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus must be 1 "
@@ -93,6 +111,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        calibrate_copy(args.calibrate_copy, 3)
+        return
     wl = configs.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
     cfg = wl.model.with_(max_seq=wl.prompt_len + W + K + 8)
@@ -107,7 +128,9 @@ def main():
     torch.cuda.synchronize()
     log(f"uploaded + river built on the GPU in {time.time() - t0:.1f}s")
     mode = binding.EXEC_PERSISTENT if args.mode == "persistent" else binding.EXEC_KERNELS
-    g = binding.River(cfg, dw, dr, exec_mode=mode)
+    # tau = 1: Eq. 1 never fires (s <= 1, strict '>'), so the threshold-mode leg below runs
+    # the whole backbone with the exit test taken after every block; forced legs ignore tau
+    g = binding.River(cfg.with_(tau=1.0), dw, dr, exec_mode=mode)
     prompt = inputs.make_prompt(cfg.vocab, wl.prompt_len, wl.seed_prompt)
     t0 = time.time()
     g.prefill(prompt)
@@ -126,6 +149,15 @@ def main():
     for i in range(W):
         g.decode_step(None, L, sync=False)
     ms_dense = timed_steps(g, torch, dense[W:], K)
+    # the same dense steps with Eq. 1 deciding (tau = 1 never exits): every workgroup reduces
+    # the similarity partials after every backbone block; the difference to the forced dense
+    # run is the cost of the exit decision on the critical path
+    g.rewind(wl.prompt_len)
+    for i in range(W):
+        g.decode_step(None, None, sync=False)
+    ms_thr = timed_steps(g, torch, [None] * K, K)
+    _, exits_thr, _ = g.read_records(K)
+    assert set(int(e) for e in exits_thr) == {L}, "tau = 1 must never exit"
     g.close()
     # all-river run ("Full-Quant." of the paper's speed table: every block as its 4-bit twin,
     # exit position 0), same shape and context lengths; needs L_s = 0, hence its own context
@@ -154,6 +186,10 @@ def main():
         traffic_detail = json.load(open(MEASURED)).get(f"{args.workload}:{args.mode}")
         if traffic_detail:
             traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]
+            traffic_detail = dict(traffic_detail,
+                                  source="NOT measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                         "runs summarised under profiles/ (see its note for the step count "
+                                         "and the algorithmic bytes of that run)")
 
     out = {
         "metric": "decode tokens/s @batch1 (8B shape) w/ early exit; HBM GB/s as % of peak",
@@ -174,13 +210,23 @@ def main():
         "full_quant": {"value": tok_s_fq, "unit": "tokens/s", "ms_per_step": ms_fq / K,
                        "achieved_GBps": gbs_fq, "frac": gbs_fq / HBM_PEAK_GBS,
                        "note": "every block as its 4-bit river twin (exit position 0)"},
+        "threshold_dense": {"value": K / (ms_thr * 1e-3), "unit": "tokens/s", "ms_per_step": ms_thr / K,
+                            "note": "Eq. 1 decides with tau = 1 (never exits): dense steps with the exit "
+                                    "test on the critical path of every block"},
+        "exit_decision_us_per_block": (ms_thr - ms_dense) / K * 1e3 / (L - 1),
+        "exit_decision_us_per_token": (ms_thr - ms_dense) / K * 1e3,
         "speedup_vs_dense": tok_s / tok_s_dense,
         "full_quant_speedup_vs_dense": tok_s_fq / tok_s_dense,
         "paper_context": "River-LLM reports 1.53x-2.16x over its 16-bit backbone on one NVIDIA A40 "
                          "(Llama3.1-8B: 25.3 -> 45.0 tokens/s on GSM8K); other hardware, not a target",
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, weights, sched[W:], args.cpu_steps)
+        # the GPU figures above are printed whatever happens in the CPU leg
+        try:
+            out["cpu_baseline"] = cpu_baseline(cfg, weights, sched[W:], args.cpu_steps)
+        except Exception as exc:          # noqa: BLE001
+            out["cpu_baseline"] = None
+            out["cpu_baseline_error"] = f"{type(exc).__name__}: {exc}"
     print(json.dumps(out), flush=True)
 
 

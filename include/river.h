@@ -122,14 +122,19 @@ int river_create(const river_config *cfg, const river_weights *w, const river_qw
                  void *workspace, size_t workspace_bytes, void *hip_stream, river_ctx **out);
 
 /*
- * Prefill phase: the prompt is processed at one unified depth, here the full
- * backbone depth L (every prompt position has exit position L), filling the KV
- * cache for positions 0..n_tokens-1.  Restarts the sequence at position 0.
- * seq must be 0.  tokens: HOST [n_tokens].  out_token: HOST, the greedy token
- * after the last prompt position (nullable).  Synchronises the stream.
+ * Prefill phase ("Inference with Seamless Exit", list of phases: the prompt is
+ * processed by sequence-level exit, all prompt tokens leaving the backbone at one
+ * unified depth).  prefill_exit_layer is that depth e_p: every prompt position runs
+ * backbone blocks 1..e_p and river twins e_p+1..L, filling the shared KV cache for
+ * positions 0..n_tokens-1 of every block.  e_p must lie in [L_s, L]; negative or L =
+ * the full backbone depth (then no river weights are needed).  How e_p is chosen the
+ * paper leaves open: it is the caller's.  Restarts the sequence at position 0.
+ * seq must be 0.  tokens: HOST [n_tokens].  out_token: HOST, the greedy token after
+ * the last prompt position (nullable).  out_logits: DEVICE fp32 [vocab], the logits of
+ * the last prompt position (nullable).  Synchronises the stream.
  */
 int river_prefill(river_ctx *ctx, int32_t seq, const int32_t *tokens, int32_t n_tokens,
-                  int32_t *out_token);
+                  int32_t prefill_exit_layer, int32_t *out_token, float *out_logits);
 
 /*
  * Generation phase, one token-level-exit decode step (Eq. 1).

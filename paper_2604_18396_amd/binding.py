@@ -72,7 +72,8 @@ def load():
     L.river_create.argtypes = [C.POINTER(river_config), C.POINTER(river_weights),
                                C.POINTER(river_qweights), C.c_void_p, C.c_size_t, C.c_void_p,
                                C.POINTER(C.c_void_p)]
-    L.river_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    L.river_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                                C.POINTER(C.c_int32), C.c_void_p]
     L.river_decode_step.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
     L.river_read_records.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -186,10 +187,17 @@ class River:
         except Exception:
             pass
 
-    def prefill(self, tokens) -> int:
+    def prefill(self, tokens, exit_layer: int | None = None, out_logits: torch.Tensor | None = None) -> int:
+        """Prefill phase at the unified depth exit_layer (None: the full depth L).
+        out_logits: optional device fp32 [vocab] tensor that receives the last position's logits."""
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         out = C.c_int32()
-        self._check(load().river_prefill(self._h, 0, t.ctypes.data, len(t), C.byref(out)))
+        if out_logits is not None:
+            assert out_logits.is_cuda and out_logits.dtype == torch.float32 and out_logits.is_contiguous()
+            assert out_logits.numel() == self.cfg.vocab
+        self._check(load().river_prefill(self._h, 0, t.ctypes.data, len(t),
+                                         -1 if exit_layer is None else int(exit_layer), C.byref(out),
+                                         out_logits.data_ptr() if out_logits is not None else None))
         return out.value
 
     def decode_step(self, token: int | None = None, forced_exit: int | None = None, sync: bool = True):
@@ -265,8 +273,8 @@ def river_create(cfg, dev_weights, dev_river, exec_mode=None, spin_limit=0) -> R
     return River(cfg, dev_weights, dev_river, exec_mode, spin_limit)
 
 
-def river_prefill(ctx: River, tokens) -> int:
-    return ctx.prefill(tokens)
+def river_prefill(ctx: River, tokens, exit_layer=None, out_logits=None) -> int:
+    return ctx.prefill(tokens, exit_layer, out_logits)
 
 
 def river_decode_step(ctx: River, token=None, forced_exit=None, sync=True):

@@ -697,12 +697,19 @@ static int check_device_error(river_ctx *x) {
   } while (0)
 
 extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, int32_t n_tokens,
-                             int32_t *out_token) {
+                             int32_t prefill_exit_layer, int32_t *out_token, float *out_logits) {
   if (!x) return RIVER_EINVAL;
   if (seq != 0 || !tokens || n_tokens < 1) { x->err = "bad prefill arguments"; return RIVER_EINVAL; }
   if (n_tokens > x->cfg.max_seq) { x->err = "prompt longer than max_seq"; return RIVER_ENOSPC; }
   for (int i = 0; i < n_tokens; ++i)
     if (tokens[i] < 0 || tokens[i] >= x->cfg.vocab) { x->err = "token id out of range"; return RIVER_EINVAL; }
+  const int L = x->cfg.n_layers;
+  const int ep = prefill_exit_layer < 0 ? L : prefill_exit_layer;
+  if (ep != L && (ep < x->cfg.min_exit_layer || ep > L)) {
+    x->err = "prefill exit layer outside [L_s, L]";
+    return RIVER_EINVAL;
+  }
+  if (ep < L && !x->have_river) { x->err = "prefill below full depth needs river weights"; return RIVER_ESTATE; }
   // a new sequence also clears a previous device-side time-out
   x->broken = false;
   int rc = reset_state(x);
@@ -710,9 +717,12 @@ extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, i
   x->pos = 0;
   x->have_token = false;
   for (int i = 0; i < n_tokens; ++i) {
-    rc = enqueue(x, tokens[i], x->cfg.n_layers, i == n_tokens - 1, -1);
+    rc = enqueue(x, tokens[i], ep, i == n_tokens - 1, -1);
     if (rc) return rc;
   }
+  if (out_logits)
+    HIP_TRY(x, hipMemcpyAsync(out_logits, x->dev.logits, (size_t)x->cfg.vocab * 4, hipMemcpyDeviceToDevice,
+                              x->stream));
   rc = check_device_error(x);
   if (rc) return rc;
   x->have_token = true;
@@ -744,15 +754,16 @@ extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const in
   if ((fe >= 0 && fe < L) || (fe < 0 && x->cfg.tau < 1.0f)) {
     if (!x->have_river) { x->err = "an exit is possible but no river weights were given"; return RIVER_ESTATE; }
   }
+  if (!out_token && (out_exit_layer || out_sims)) {
+    x->err = "out_token is NULL but other outputs are not";
+    return RIVER_EINVAL;
+  }
   const int slot = (int)(x->steps % kRecords);
   int rc = enqueue(x, tok, fe, 1, slot);
   if (rc) return rc;
   x->steps += 1;
   x->have_token = true;
-  if (!out_token) {
-    if (out_exit_layer || out_sims) { x->err = "out_token is NULL but other outputs are not"; return RIVER_EINVAL; }
-    return RIVER_OK;
-  }
+  if (!out_token) return RIVER_OK;
   HIP_TRY(x, hipMemcpyAsync(out_token, x->dev.rec_token + slot, 4, hipMemcpyDeviceToHost, x->stream));
   if (out_exit_layer)
     HIP_TRY(x, hipMemcpyAsync(out_exit_layer, x->dev.rec_exit + slot, 4, hipMemcpyDeviceToHost, x->stream));

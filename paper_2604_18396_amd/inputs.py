@@ -59,18 +59,27 @@ def _normal_tensor(shape: tuple[int, int], seed_key: tuple[int, ...], dtype: int
     return t.contiguous()
 
 
-def make_weights(cfg: ModelConfig, seed: int, layers: range | None = None) -> dict:
+def _gain(n: int, seed_key: tuple[int, ...], std: float, tdt) -> torch.Tensor:
+    """Norm gains: ones, or 1 + N(0, std^2) drawn from the generator keyed by seed_key."""
+    if std <= 0.0:
+        return torch.ones(n, dtype=tdt)
+    g = 1.0 + std * np.random.default_rng(list(seed_key)).standard_normal(n).astype(np.float32)
+    return torch.from_numpy(g).to(tdt).contiguous()
+
+
+def make_weights(cfg: ModelConfig, seed: int, layers: range | None = None, gain_std: float = 0.0) -> dict:
     """Random-init backbone weights.
 
     Returns {"tok_emb", "final_norm", "lm_head", "layers": [ {attn_norm, wq, wk,
     wv, wo, ffn_norm, w_gate, w_up, w_down}, ... ]}; matrices are [out, in]
     row-major.  `layers` restricts generation to a sub-range (others are None).
+    gain_std > 0 draws the norm gains as 1 + N(0, gain_std^2) instead of ones.
     """
     tdt = torch.bfloat16 if cfg.dtype == DTYPE_BF16 else torch.float32
     w = {
         "tok_emb": _normal_tensor((cfg.vocab, cfg.d_model), (seed, 0, 0), cfg.dtype),
         "lm_head": _normal_tensor((cfg.vocab, cfg.d_model), (seed, 0, 1), cfg.dtype),
-        "final_norm": torch.ones(cfg.d_model, dtype=tdt),
+        "final_norm": _gain(cfg.d_model, (seed, 0, 2), gain_std, tdt),
         "layers": [],
     }
     want = set(layers) if layers is not None else set(range(cfg.n_layers))
@@ -78,8 +87,8 @@ def make_weights(cfg: ModelConfig, seed: int, layers: range | None = None) -> di
         if l not in want:
             w["layers"].append(None)
             continue
-        blk = {"attn_norm": torch.ones(cfg.d_model, dtype=tdt),
-               "ffn_norm": torch.ones(cfg.d_model, dtype=tdt)}
+        blk = {"attn_norm": _gain(cfg.d_model, (seed, l + 1, 100), gain_std, tdt),
+               "ffn_norm": _gain(cfg.d_model, (seed, l + 1, 101), gain_std, tdt)}
         for m, name in enumerate(MATRICES):
             blk[name] = _normal_tensor(matrix_shape(cfg, name), (seed, l + 1, m), cfg.dtype)
         w["layers"].append(blk)

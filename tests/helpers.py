@@ -2,6 +2,9 @@
 import numpy as np
 import torch
 
+# uses of the near-tie rule for greedy tokens in the GPU parity tests (see check_token there)
+NEAR_TIES: list = []
+
 
 def grid_weights(rows, cols, group, dtype, seed):
     """Weights that already lie on a 4-bit grid: w = (q - z) * 2^-k with integer z, every

@@ -14,6 +14,8 @@ import time
 import numpy as np
 import pytest
 
+import helpers
+
 from oracle import river_oracle as ro
 from paper_2604_18396_amd import binding, configs, inputs
 
@@ -62,9 +64,12 @@ def run(cfg, seed, prompt, sched, label):
         say(f"{label}: step {i} exit {e}: hidden {eh:.2e} logits {el:.2e} ({time.time() - t0:.1f}s)")
         assert eh <= TOL and el <= TOL
         np.testing.assert_allclose(sg[:e], so[:e], atol=2e-4)
-        if tg != to:
+        if tg != to:      # bf16 near-tie of the two best logits only; counted and reported
             lo = o.logits()
-            assert (lo[to] - lo[tg]) / np.abs(lo).max() <= TOL
+            gap = (lo[to] - lo[tg]) / np.abs(lo).max()
+            assert gap <= TOL, f"{label}: token {tg} vs oracle {to} (gap {gap:.3e})"
+            helpers.NEAR_TIES.append(f"{label} step {i}: token {tg} vs oracle {to}, gap {gap:.3e}")
+            say(f"NEAR-TIE accepted: {helpers.NEAR_TIES[-1]}")
         tok = to
     n = len(prompt) + len(sched)
     for name, a, b in (("K", g.kcache(), o.kcache()), ("V", g.vcache(), o.vcache())):

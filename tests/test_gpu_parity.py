@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 import torch
 
+import helpers
 from helpers import grid_model
 from oracle import river_oracle as ro
 from paper_2604_18396_amd import binding, configs, inputs
@@ -48,21 +49,35 @@ def relerr(a, b):
     return float(np.abs(np.asarray(a, np.float64) - b).max() / max(np.abs(b).max(), 1e-30))
 
 
+def check_token(cfg, tg, to, lo, what):
+    """Greedy token against the oracle's.  fp32: must be equal.  bf16: logits are only
+    required to agree within TOL * max|logit|, so two logits closer than that cannot be
+    ordered reliably; a different token is accepted only then, and every use is counted
+    and printed (the total appears in the terminal summary)."""
+    if tg == to:
+        return
+    gap = (lo[to] - lo[tg]) / max(np.abs(lo).max(), 1e-30)
+    assert cfg.dtype == configs.DTYPE_BF16, f"{what}: fp32 token {tg} vs oracle {to} (gap {gap:.3e})"
+    assert gap <= TOL[cfg.dtype], f"{what}: token {tg} vs oracle {to} (gap {gap:.3e})"
+    helpers.NEAR_TIES.append(f"{what}: token {tg} vs oracle {to}, oracle logit gap {gap:.3e} of max|logit|")
+    say(f"NEAR-TIE accepted: {helpers.NEAR_TIES[-1]}")
+
+
 class Pair:
     """Oracle and HIP context on the same weights; each side quantises its own river."""
 
-    def __init__(self, cfg, weights, mode, with_river=True):
+    def __init__(self, cfg, weights, mode, with_river=True, oracle=None):
         self.cfg = cfg
-        self.o = ro.Oracle(cfg, weights, ro.quantize_river(cfg, weights) if with_river else None)
+        self.o = oracle or ro.Oracle(cfg, weights, ro.quantize_river(cfg, weights) if with_river else None)
         self.dw = binding.upload_weights(weights)
         self.dr = binding.quantize_river(cfg, self.dw) if with_river else None
         self.g = binding.River(cfg, self.dw, self.dr, exec_mode=mode)
 
-    def prefill(self, prompt):
-        to = self.o.prefill(prompt)
-        tg = self.g.prefill(prompt)
+    def prefill(self, prompt, exit_layer=None):
+        to = self.o.prefill(prompt, exit_layer)
+        tg = self.g.prefill(prompt, exit_layer)
         self.compare_state("prefill")
-        assert tg == to
+        check_token(self.cfg, tg, to, self.o.logits(), "prefill")
         return to
 
     def compare_state(self, what):
@@ -92,11 +107,7 @@ class Pair:
                                    err_msg=f"{what}: similarities")
         assert np.all(np.isnan(sg[ne:])) and np.all(np.isnan(so[ne:]))
         self.compare_state(what)
-        if tg != to:
-            # a different greedy token is only acceptable on a numerical near-tie of the logits
-            lo = self.o.logits()
-            gap = (lo[to] - lo[tg]) / max(np.abs(lo).max(), 1e-30)
-            assert gap <= TOL[cfg.dtype], f"{what}: token {tg} vs oracle {to} (gap {gap:.3e})"
+        check_token(cfg, tg, to, self.o.logits(), what)
         return to, eo, so
 
     def compare_cache(self, n_pos):
@@ -281,8 +292,8 @@ def test_mid_shape_ragged_tiles(mode, cfg):
 @pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16], ids=lambda c: c.name)
 def test_long_context_many_splits(mode, cfg0):
-    """Attention over 1100+ cached positions: 5 splits (one chunk of up to 256 positions per
-    workgroup), merged by the consumer."""
+    """Attention over 1100+ cached positions: 4 splits of about 276 positions (two chunks
+    per workgroup), merged by the consumer."""
     needs_mode(cfg0, mode)
     say(f"long context {cfg0.name} mode={mode}")
     cfg = cfg0.with_(max_seq=1200, tau=0.675)
@@ -432,4 +443,142 @@ def test_barrier_wait_is_bounded():
     # a fresh context on the same device works afterwards
     g = binding.River(cfg.with_(tau=2.0), dw, None, exec_mode=binding.EXEC_PERSISTENT)
     assert 0 <= g.prefill([1, 2, 3, 4]) < cfg.vocab
+    g.close()
+
+
+# ------------------------------------------- long context: 5 to 8 attention splits
+
+LONG = configs.ModelConfig("long-hd128-bf16", 2, 512, 8, 2, 128, 1408, 1002, 500000.0, 1e-5,
+                           configs.DTYPE_BF16, 4208, 1, 2.0)
+LONG_F32 = LONG.with_(name="long-hd128-fp32", dtype=configs.DTYPE_F32)
+
+
+@pytest.mark.parametrize("cfg", [LONG, LONG_F32], ids=lambda c: c.name)
+def test_long_context_5_to_8_splits_head_dim_128(cfg):
+    """Contexts of 2305 .. 4203 positions at head_dim 128: the host picks 5, 6, 7 and 8
+    attention splits (one per 512 positions above 2048), every workgroup walks more than
+    two chunks (bf16: 3 chunks of 256 positions, fp32: 5 of 128), and the consumer merges
+    up to eight partials.  One 4200-token prompt, then the sequence is rewound to shorter
+    lengths on both sides (slots beyond the length are never read), three teacher-forced
+    steps with backbone and river blocks at each length."""
+    w = inputs.make_weights(cfg, 61)
+    river = ro.quantize_river(cfg, w)
+    prompt = inputs.make_prompt(cfg.vocab, 4200, 62)
+    modes = MODES if cfg.dtype == configs.DTYPE_BF16 else [binding.EXEC_KERNELS]
+    for mode in modes:
+        say(f"long context {cfg.name} mode={mode}: oracle prefill of {len(prompt)} tokens")
+        pair = Pair(cfg, w, mode, oracle=ro.Oracle(cfg, w, river))
+        tok = pair.prefill(prompt)
+        for length, splits in ((4200, 8), (3328, 7), (2816, 6), (2304, 5)):
+            pair.g.rewind(length)
+            pair.o.rewind(length)
+            assert min(8, -(-(length + 1) // 512)) == splits
+            for i, e in enumerate((1, 2, 2)):
+                tok, eo, _ = pair.step(tok, e, what=f"{cfg.name} mode {mode} length {length} step {i}")
+            say(f"  length {length} ({splits} splits) ok")
+        pair.compare_cache(4203)
+        pair.close()
+
+
+# ------------------------------------------------------------ non-unit norm gains
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16, MID, MID_F32_HD128], ids=lambda c: c.name)
+def test_non_unit_norm_gains(mode, cfg0):
+    """Norm gains 1 + N(0, 0.1^2): the gain multiply of the fused RMSNorm prologue (embedding
+    row, hidden state and half-precision layouts, final norm) in backbone and river blocks."""
+    needs_mode(cfg0, mode)
+    say(f"norm gains {cfg0.name} mode={mode}")
+    cfg = cfg0.with_(min_exit_layer=0)
+    w = inputs.make_weights(cfg, 83, gain_std=0.1)
+    assert float((w["layers"][0]["attn_norm"].float() - 1).abs().max()) > 0.05
+    pair = Pair(cfg, w, mode)
+    L = cfg.n_layers
+    sched = [0, L, 1, L - 1, 2 % L, 0]
+    exits = run_teacher_forced(pair, inputs.make_prompt(cfg.vocab, 9, 84), len(sched), sched, cfg0.name)
+    assert exits == sched
+    pair.compare_cache(9 + len(sched))
+    pair.close()
+
+
+# ------------------------------------------------ sequence-level exit in the prefill
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("ep", [0, 2, 3])
+@pytest.mark.parametrize("cfg0", [configs.TINY, TINY_BF16, MID], ids=lambda c: c.name)
+def test_prefill_at_unified_exit_depth(mode, ep, cfg0):
+    """Prefill phase with sequence-level exit: every prompt position runs e_p backbone blocks
+    and river twins above; then token-level steps over that cache."""
+    needs_mode(cfg0, mode)
+    say(f"prefill depth {ep} {cfg0.name} mode={mode}")
+    cfg = cfg0.with_(min_exit_layer=0)
+    ep = min(ep, cfg.n_layers)
+    w = inputs.make_weights(cfg, 87, gain_std=0.05)
+    pair = Pair(cfg, w, mode)
+    n = 37
+    tok = pair.prefill(inputs.make_prompt(cfg.vocab, n, 88), ep)
+    for i, e in enumerate((cfg.n_layers, 1, 0, 2)):
+        tok, eo, _ = pair.step(tok, e, what=f"after prefill at {ep}, step {i}")
+    pair.compare_cache(n + 4)
+    pair.close()
+
+
+def test_prefill_outputs_and_argument_checks():
+    say("prefill outputs")
+    cfg = TINY_BF16
+    w = inputs.make_weights(cfg, 3)
+    dw = binding.upload_weights(w)
+    dr = binding.quantize_river(cfg, dw)
+    g = binding.River(cfg, dw, dr)
+    out = torch.full((cfg.vocab,), float("nan"), dtype=torch.float32, device="cuda")
+    tok = g.prefill([5, 6, 7], None, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), g.logits())
+    assert int(out.argmax()) == tok
+    with pytest.raises(binding.RiverError) as ei:
+        g.prefill([5, 6, 7], 1)                                  # below L_s = 2
+    assert ei.value.code == binding.RIVER_EINVAL
+    with pytest.raises(binding.RiverError) as ei:
+        g.prefill([5, 6, 7], cfg.n_layers + 1)
+    assert ei.value.code == binding.RIVER_EINVAL
+    g.close()
+    dense = binding.River(cfg.with_(tau=2.0), dw, None)
+    with pytest.raises(binding.RiverError) as ei:
+        dense.prefill([5, 6, 7], 2)                              # needs the river
+    assert ei.value.code == binding.RIVER_ESTATE
+    # outputs asked for without out_token: refused before anything is enqueued
+    dense.prefill([5, 6, 7])
+    import ctypes as C
+    e = C.c_int32()
+    rc = binding.load().river_decode_step(dense._h, None, None, None, C.byref(e), None)
+    assert rc == binding.RIVER_EINVAL and dense.pos == 3
+    dense.close()
+
+
+def test_barrier_slot_pool_reuse_and_exhaustion():
+    """Contexts take one of 64 barrier slots per device: 70 contexts created and destroyed one
+    after the other reuse slots; the 65th simultaneous context is refused with RIVER_ENOSPC."""
+    import gc
+    say("barrier slot pool")
+    gc.collect()
+    cfg = TINY_BF16.with_(tau=2.0, max_seq=8)
+    w = inputs.make_weights(cfg, 3)
+    dw = binding.upload_weights(w)
+    for i in range(70):
+        g = binding.River(cfg, dw, None)
+        if i % 23 == 0:
+            assert 0 <= g.prefill([1, 2, 3]) < cfg.vocab
+        g.close()
+    held = []
+    with pytest.raises(binding.RiverError) as ei:
+        for i in range(65):
+            held.append(binding.River(cfg, dw, None))
+    assert ei.value.code == binding.RIVER_ENOSPC and "64" in str(ei.value)
+    assert len(held) == 64
+    ref = held[0].prefill([1, 2, 3])
+    assert held[63].prefill([1, 2, 3]) == ref                    # the last slot works like the first
+    for g in held:
+        g.close()
+    g = binding.River(cfg, dw, None)                             # slots are free again
+    assert g.prefill([1, 2, 3]) == ref
     g.close()
