@@ -122,6 +122,25 @@ int river_create(const river_config *cfg, const river_weights *w, const river_qw
                  void *workspace, size_t workspace_bytes, void *hip_stream, river_ctx **out);
 
 /*
+ * river_create for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments and
+ * behaviour as river_create, and the workspace must have the same size, but the call
+ * allocates nothing: the step-transient part of the workspace (activations, partial
+ * results, counters, step records, descriptor tables) and the counters of the device-wide
+ * barrier live in a static device array of 8 MiB inside the library, which every GPU the
+ * library runs on holds until the process ends; the KV cache, the RoPE table and the packed
+ * river scales stay in the caller's workspace.  RIVER_ENOSPC if the configuration needs more
+ * than the 8 MiB (the 8B shape needs 4.5 MiB).  The array is shared by every call on a device
+ * and keeps the last context's contents; the call clears what must start at zero.  At most one
+ * context created this way can be live per device (RIVER_ESTATE otherwise: two would race on
+ * the array); contexts from river_create are not affected.  The barrier counters are then in
+ * ordinary device memory and polled with device-coherent vector loads, a few percent slower
+ * per token than river_create's uncached pool; results are identical.
+ */
+int river_create_static(const river_config *cfg, const river_weights *w, const river_qweights *q,
+                        void *workspace, size_t workspace_bytes, void *hip_stream, river_ctx **out);
+
+/*
  * Prefill phase ("Inference with Seamless Exit", list of phases: the prompt is
  * processed by sequence-level exit, all prompt tokens leaving the backbone at one
  * unified depth).  prefill_exit_layer is that depth e_p: every prompt position runs

@@ -19,7 +19,7 @@ RIVER_OK, RIVER_EINVAL, RIVER_ENOSPC, RIVER_ESTATE, RIVER_EHIP = 0, -1, -2, -3, 
 EXEC_KERNELS, EXEC_PERSISTENT = 0, 1
 DBG_HIDDEN, DBG_LOGITS, DBG_KCACHE, DBG_VCACHE, DBG_TRACE = 0, 1, 2, 3, 4
 
-EXPORTS = ("river_quantize_w4", "river_workspace_bytes", "river_create", "river_prefill",
+EXPORTS = ("river_quantize_w4", "river_workspace_bytes", "river_create", "river_create_static", "river_prefill",
            "river_decode_step", "river_read_records", "river_rewind", "river_position",
            "river_get_debug", "river_fill_cache", "river_last_error", "river_destroy")
 
@@ -72,6 +72,7 @@ def load():
     L.river_create.argtypes = [C.POINTER(river_config), C.POINTER(river_weights),
                                C.POINTER(river_qweights), C.c_void_p, C.c_size_t, C.c_void_p,
                                C.POINTER(C.c_void_p)]
+    L.river_create_static.argtypes = L.river_create.argtypes
     L.river_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                                 C.POINTER(C.c_int32), C.c_void_p]
     L.river_decode_step.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
@@ -138,7 +139,9 @@ class River:
     """One decode context (river_create .. river_destroy)."""
 
     def __init__(self, cfg: ModelConfig, dev_weights: dict, dev_river: list | None,
-                 exec_mode: int | None = None, spin_limit: int = 0):
+                 exec_mode: int | None = None, spin_limit: int = 0, static_scratch: bool = False):
+        """static_scratch=True goes through river_create_static (no device allocation inside
+        the library: activations and barrier counters in the library's static device array)."""
         L = load()
         self.cfg = cfg
         self._c = make_config(cfg, exec_mode, spin_limit)
@@ -166,8 +169,9 @@ class River:
             raise RiverError(RIVER_EINVAL, "invalid configuration")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev_weights["tok_emb"].device)
         h = C.c_void_p()
-        rc = L.river_create(C.byref(self._c), C.byref(w), C.byref(q) if q is not None else None,
-                            self.workspace.data_ptr(), nbytes, _stream_ptr(), C.byref(h))
+        create = L.river_create_static if static_scratch else L.river_create
+        rc = create(C.byref(self._c), C.byref(w), C.byref(q) if q is not None else None,
+                    self.workspace.data_ptr(), nbytes, _stream_ptr(), C.byref(h))
         if rc:
             raise RiverError(rc, L.river_last_error(None).decode())
         self._h = h
@@ -271,6 +275,10 @@ class River:
 # the context kept in an object).
 def river_create(cfg, dev_weights, dev_river, exec_mode=None, spin_limit=0) -> River:
     return River(cfg, dev_weights, dev_river, exec_mode, spin_limit)
+
+
+def river_create_static(cfg, dev_weights, dev_river, exec_mode=None, spin_limit=0) -> River:
+    return River(cfg, dev_weights, dev_river, exec_mode, spin_limit, static_scratch=True)
 
 
 def river_prefill(ctx: River, tokens, exit_layer=None, out_logits=None) -> int:

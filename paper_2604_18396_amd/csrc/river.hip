@@ -128,7 +128,7 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
   if (l > 0) { barrier_arrive(D.bar, k); TRACE_ARRIVE(); }
   prefetch_phase<DT>(D, l, PH_QKV, guess, pre, l > 0 ? 0 : 2);
   if (l > 0) {
-    barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE();
+    barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE();
     prefetch_phase<DT>(D, l, PH_QKV, guess, pre, 1);
     exit_test(D, A, l, ctl, lds);
     if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
@@ -141,7 +141,7 @@ __device__ RIVER_PSTEP_INLINE void pstep_attn(const Dev *Dp, StepArgs A, int l, 
                                         float *lds) {
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
   phase_attn<DT>(D, A, l, unpack_ctl(ctl_packed), lds, [&] { barrier_arrive(D.bar, k); TRACE_ARRIVE(); },
-                 [&] { barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE(); });
+                 [&] { barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE(); });
 }
 template <int DT, int PH>
 __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, bool river, unsigned long long k,
@@ -150,7 +150,7 @@ __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, 
   Pre<DT> pre;
   barrier_arrive(D.bar, k); TRACE_ARRIVE();
   prefetch_phase<DT>(D, l, PH, river, pre, 0);
-  barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE();
+  barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE();
   prefetch_phase<DT>(D, l, PH, river, pre, 1);
   if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre);
   else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre);
@@ -164,7 +164,7 @@ __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl
   Pre<DT> pre;
   barrier_arrive(D.bar, k); TRACE_ARRIVE();
   prefetch_head<DT>(D, pre, 0);
-  barrier_wait(D.bar, k, D.spin_limit); TRACE_RELEASE();
+  barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE();
   prefetch_head<DT>(D, pre, 1);
   phase_head<DT>(D, A, ctl, lds, pre);
 }
@@ -257,6 +257,33 @@ std::mutex g_bar_mu;
 char *g_bar_pool[kBarDevices];
 unsigned long long g_bar_used[kBarDevices];
 }
+// Static scratch for river_create_static: the step-transient part of the workspace
+// (activations, partial results, counters, records, descriptor tables) and the barrier
+// block, for callers that must not allocate.  Each device holds its own copy of the array;
+// host code uses the per-device address from hipGetSymbolAddress, never the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+namespace {
+char *g_static_ptr[kBarDevices];          // device address of g_static_scratch, per device
+bool g_static_live[kBarDevices];          // a live context uses the device's scratch
+}
+// Address of the current device's copy of the static scratch (looked up once per device).
+static int static_scratch_ptr(int dev, char **ptr, std::string *why) {
+  std::lock_guard<std::mutex> lk(g_bar_mu);
+  if (dev < 0 || dev >= kBarDevices) { *why = "device index too large for the static scratch table"; return RIVER_EINVAL; }
+  if (!g_static_ptr[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess || !p) {
+      *why = std::string("hipGetSymbolAddress(static scratch): ") + hipGetErrorString(e);
+      return RIVER_EHIP;
+    }
+    g_static_ptr[dev] = (char *)p;
+  }
+  *ptr = g_static_ptr[dev];
+  return RIVER_OK;
+}
+
 static int bar_acquire(int dev, int *slot, char **ptr, std::string *why) {
   std::lock_guard<std::mutex> lk(g_bar_mu);
   if (dev < 0 || dev >= kBarDevices) { *why = "device index too large for the barrier pool"; return RIVER_EINVAL; }
@@ -295,7 +322,14 @@ struct river_ctx {
   unsigned long long bar_total;
   int bar_slot = -1;    // slot of the process-wide barrier pool
   int bar_device = 0;
-  ~river_ctx() { bar_release(bar_device, bar_slot); }
+  bool is_static = false; // activations and barrier block live in the device's static scratch
+  ~river_ctx() {
+    bar_release(bar_device, bar_slot);
+    if (is_static) {
+      std::lock_guard<std::mutex> lk(g_bar_mu);
+      g_static_live[bar_device] = false;
+    }
+  }
   int grid_persist, grid_gemv, block;
   size_t lds_bytes;
   bool broken;
@@ -436,9 +470,9 @@ static int reset_state(river_ctx *x) {
   return RIVER_OK;
 }
 
-extern "C" int river_create(const river_config *cfg, const river_weights *w, const river_qweights *q,
-                            void *workspace, size_t workspace_bytes, void *hip_stream,
-                            river_ctx **out) {
+static int create_impl(const river_config *cfg, const river_weights *w, const river_qweights *q,
+                       void *workspace, size_t workspace_bytes, void *hip_stream, river_ctx **out,
+                       bool use_static) {
   std::string why;
   if (!out) { g_create_err = "null out"; return RIVER_EINVAL; }
   *out = nullptr;
@@ -520,6 +554,40 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   x->grid_persist = std::max(8, std::min(cus, kMaxGrid) / 8 * 8);
   x->grid_gemv = x->grid_persist;
 
+  // Where the step-transient part of the layout [hidden, qsz) lives: in the workspace, or in
+  // the device's static scratch followed by the barrier block (`act + lay.X` addresses member
+  // X of that part in both cases).
+  char *act = x->ws;
+  char *static_bar = nullptr;
+  if (use_static) {
+    const size_t need = (lay.qsz - lay.hidden) + kBarBytes;
+    if (need > kStaticScratchBytes) {
+      g_create_err = "configuration needs " + std::to_string(need) + " bytes of scratch; the static scratch of "
+                     "river_create_static holds " + std::to_string(kStaticScratchBytes) + " (use river_create)";
+      delete x;
+      return RIVER_ENOSPC;
+    }
+    char *sp = nullptr;
+    std::string why2;
+    const int rc = static_scratch_ptr(dev_id, &sp, &why2);
+    if (rc != RIVER_OK) { g_create_err = why2; delete x; return rc; }
+    bool busy;
+    {
+      std::lock_guard<std::mutex> lk(g_bar_mu);
+      busy = g_static_live[dev_id];
+      if (!busy) g_static_live[dev_id] = true;
+    }
+    if (busy) {                 // (the context's destructor takes the same lock)
+      g_create_err = "the static scratch of this device is in use by a live context";
+      delete x;
+      return RIVER_ESTATE;
+    }
+    x->is_static = true;
+    x->bar_device = dev_id;
+    act = sp - lay.hidden;
+    static_bar = sp + (lay.qsz - lay.hidden);
+  }
+
   Dev &D = x->dev;
   D.L = L; D.d = cfg->d_model; D.nq = cfg->n_q_heads; D.nkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
   D.ffn = cfg->d_ffn; D.vocab = cfg->vocab; D.max_seq = cfg->max_seq; D.min_exit = cfg->min_exit_layer;
@@ -529,29 +597,34 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   D.eps = cfg->rms_eps; D.tau = cfg->tau;
   D.tok_emb = w->tok_emb; D.final_norm = w->final_norm; D.lm_head = w->lm_head;
   char *ws = x->ws;
-  D.layers = (const DevLayer *)(ws + lay.layers);
+  D.layers = (const DevLayer *)(act + lay.layers);
   D.kcache = ws + lay.kcache; D.vcache = ws + lay.vcache;
   D.rope = (const float2 *)(ws + lay.rope);
-  D.hidden = (float *)(ws + lay.hidden);
-  D.qbuf = (float *)(ws + lay.qbuf); D.obuf = (float *)(ws + lay.obuf);
-  D.kvcur = (float *)(ws + lay.kvcur);
-  D.h1 = (float *)(ws + lay.h1); D.abuf = (float *)(ws + lay.abuf);
-  D.logits = (float *)(ws + lay.logits);
-  D.part_o = (float *)(ws + lay.part_o); D.part_ml = (float *)(ws + lay.part_ml);
-  D.cos_part = (float *)(ws + lay.cos_part);
-  D.amax_val = (float *)(ws + lay.amax_val); D.amax_idx = (int *)(ws + lay.amax_idx);
-  D.st = (DevState *)(ws + lay.state);
-  {
+  D.hidden = (float *)(act + lay.hidden);
+  D.qbuf = (float *)(act + lay.qbuf); D.obuf = (float *)(act + lay.obuf);
+  D.kvcur = (float *)(act + lay.kvcur);
+  D.h1 = (float *)(act + lay.h1); D.abuf = (float *)(act + lay.abuf);
+  D.logits = (float *)(act + lay.logits);
+  D.part_o = (float *)(act + lay.part_o); D.part_ml = (float *)(act + lay.part_ml);
+  D.cos_part = (float *)(act + lay.cos_part);
+  D.amax_val = (float *)(act + lay.amax_val); D.amax_idx = (int *)(act + lay.amax_idx);
+  D.st = (DevState *)(act + lay.state);
+  if (use_static) {
+    // ordinary device memory: polled with device-coherent vector loads (see barrier_wait)
+    D.bar = (unsigned long long *)static_bar;
+    D.bar_vector_poll = 1;
+  } else {
     char *bp = nullptr;
     std::string why2;
     x->bar_device = dev_id;
     const int rc = bar_acquire(dev_id, &x->bar_slot, &bp, &why2);
     if (rc != RIVER_OK) { g_create_err = why2; delete x; return rc; }
     D.bar = (unsigned long long *)bp;
+    D.bar_vector_poll = 0;
   }
-  D.rec_token = (int *)(ws + lay.rec_token); D.rec_exit = (int *)(ws + lay.rec_exit);
-  D.rec_sims = (float *)(ws + lay.rec_sims);
-  D.trace = (unsigned long long *)(ws + lay.trace);
+  D.rec_token = (int *)(act + lay.rec_token); D.rec_exit = (int *)(act + lay.rec_exit);
+  D.rec_sims = (float *)(act + lay.rec_sims);
+  D.trace = (unsigned long long *)(act + lay.trace);
   x->lds_bytes = ((size_t)D.xcap + lds_half_floats(D.xcap) + 64) * sizeof(float);
 
   // RoPE table in double precision: angle = pos * base^(-2i/hd)
@@ -573,8 +646,8 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   if ((e = hipMemcpyAsync(ws + lay.rope, rope.data(), rope.size() * sizeof(float2),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("rope upload", e);
-  x->dev_d = (const Dev *)(ws + lay.dev);
-  if ((e = hipMemcpyAsync(ws + lay.dev, &x->dev, sizeof(Dev), hipMemcpyHostToDevice, x->stream)) != hipSuccess)
+  x->dev_d = (const Dev *)(act + lay.dev);
+  if ((e = hipMemcpyAsync(act + lay.dev, &x->dev, sizeof(Dev), hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("descriptor upload", e);
   // pack (scale, zero) pairs of every river matrix that was given into the workspace
   {
@@ -595,12 +668,15 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
       }
     if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) packing", e);
   }
-  if ((e = hipMemcpyAsync(ws + lay.layers, hl.data(), hl.size() * sizeof(DevLayer),
+  if ((e = hipMemcpyAsync(act + lay.layers, hl.data(), hl.size() * sizeof(DevLayer),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("layer table upload", e);
-  // everything after the caches starts at zero (state, counters, records, activations)
-  if ((e = hipMemsetAsync(ws + lay.hidden, 0, lay.layers - lay.hidden, x->stream)) != hipSuccess)
+  // everything after the caches starts at zero (state, counters, records, activations); the
+  // static scratch keeps the previous context's contents, so this clear is what resets it
+  if ((e = hipMemsetAsync(act + lay.hidden, 0, lay.layers - lay.hidden, x->stream)) != hipSuccess)
     return fail("workspace clear", e);
+  if (use_static && (e = hipMemsetAsync(static_bar, 0, kBarBytes, x->stream)) != hipSuccess)
+    return fail("barrier block clear", e);
   if ((e = hipMemsetAsync(ws + lay.kcache, 0, 2 * align_up(lay.cache_bytes, 256), x->stream)) != hipSuccess)
     return fail("cache clear", e);
   if ((e = hipStreamSynchronize(x->stream)) != hipSuccess) return fail("create sync", e);
@@ -618,6 +694,18 @@ extern "C" int river_create(const river_config *cfg, const river_weights *w, con
   }
   *out = x;
   return RIVER_OK;
+}
+
+extern "C" int river_create(const river_config *cfg, const river_weights *w, const river_qweights *q,
+                            void *workspace, size_t workspace_bytes, void *hip_stream,
+                            river_ctx **out) {
+  return create_impl(cfg, w, q, workspace, workspace_bytes, hip_stream, out, false);
+}
+
+extern "C" int river_create_static(const river_config *cfg, const river_weights *w, const river_qweights *q,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream,
+                                   river_ctx **out) {
+  return create_impl(cfg, w, q, workspace, workspace_bytes, hip_stream, out, true);
 }
 
 // Enqueue one token (prompt position or decode step).

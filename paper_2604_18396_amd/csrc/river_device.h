@@ -50,6 +50,7 @@ struct DevState {
 
 struct Dev {
   int L, d, nq, nkv, hd, ffn, vocab, max_seq, min_exit, group, spin_limit;
+  int bar_vector_poll;            // the barrier block is ordinary (cached) device memory: poll it with vector loads
   int xcap;                       // floats of LDS reserved for the staged input vector
   float eps, tau;
   const void *tok_emb, *final_norm, *lm_head;
@@ -348,13 +349,25 @@ __device__ __forceinline__ bool barrier_poll(const unsigned long long *bar, unsi
       : "memory");
   return ((c0 + c1) + (c2 + c3)) + ((c4 + c5) + (c6 + c7)) >= target;
 }
-__device__ __forceinline__ void barrier_wait(unsigned long long *bar, unsigned long long k, int spin_limit) {
+// The same poll for a barrier block in ordinary device memory (contexts whose barrier block
+// lives in the library's static scratch): scalar loads could be served from a stale L2 line
+// there, so the counters are read with device-coherent vector loads.  These return behind the
+// weight prefetch the polling wavefront has issued, which costs a few percent of a token.
+__device__ __forceinline__ bool barrier_poll_vector(const unsigned long long *bar, unsigned long long target, int &err) {
+  unsigned long long c = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) c += __hip_atomic_load(bar + i * 16, __ATOMIC_RELAXED, RIVER_AG);
+  err = __hip_atomic_load(bar_error((unsigned long long *)bar), __ATOMIC_RELAXED, RIVER_AG);
+  return c >= target;
+}
+__device__ __forceinline__ void barrier_wait(unsigned long long *bar, unsigned long long k, int spin_limit,
+                                             int vector_poll = 0) {
   if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) {
     const unsigned long long target = k * gridDim.x;
     int spins = 0;
     for (;;) {
       int err;
-      if (barrier_poll(bar, target, err)) break;
+      if (vector_poll ? barrier_poll_vector(bar, target, err) : barrier_poll(bar, target, err)) break;
       if (++spins > spin_limit || err != 0) {
         if ((threadIdx.x & 63) == 0) __hip_atomic_store(bar_error(bar), 1, __ATOMIC_RELAXED, RIVER_AG);
         break;
