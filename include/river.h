@@ -70,6 +70,10 @@ typedef struct {
   int32_t river_group;    /* consecutive input elements per quantisation group, multiple of 32 */
   int32_t exec_mode;      /* RIVER_EXEC_* */
   int32_t spin_limit;     /* PERSISTENT: polls before a barrier wait gives up (0 = default) */
+  int32_t prefill_gemm_min_tokens; /* prompts of at least this many tokens are prefilled with MFMA GEMMs
+                                      (RIVER_BF16, d_model, d_ffn and river_group multiples of 64); shorter
+                                      ones, and all other configurations, run the decode kernels per prompt
+                                      position.  0 = default (32); negative = never */
 } river_config;
 
 /* Backbone weights.  DEVICE pointers in HOST arrays of length n_layers. */

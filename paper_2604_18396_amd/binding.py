@@ -36,7 +36,7 @@ class river_config(C.Structure):
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
                 ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("min_exit_layer", C.c_int32),
                 ("tau", C.c_float), ("river_bits", C.c_int32), ("river_group", C.c_int32),
-                ("exec_mode", C.c_int32), ("spin_limit", C.c_int32)]
+                ("exec_mode", C.c_int32), ("spin_limit", C.c_int32), ("prefill_gemm_min_tokens", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -94,12 +94,14 @@ def default_exec_mode(cfg: ModelConfig) -> int:
     return EXEC_PERSISTENT if cfg.dtype == 1 else EXEC_KERNELS
 
 
-def make_config(cfg: ModelConfig, exec_mode: int | None = None, spin_limit: int = 0) -> river_config:
+def make_config(cfg: ModelConfig, exec_mode: int | None = None, spin_limit: int = 0,
+                prefill_gemm_min_tokens: int = 0) -> river_config:
     if exec_mode is None:
         exec_mode = default_exec_mode(cfg)
     return river_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
                         cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps, cfg.dtype, 1, cfg.max_seq,
-                        cfg.min_exit_layer, cfg.tau, 4, cfg.river_group, exec_mode, spin_limit)
+                        cfg.min_exit_layer, cfg.tau, 4, cfg.river_group, exec_mode, spin_limit,
+                        prefill_gemm_min_tokens)
 
 
 def _stream_ptr() -> int:
@@ -139,12 +141,13 @@ class River:
     """One decode context (river_create .. river_destroy)."""
 
     def __init__(self, cfg: ModelConfig, dev_weights: dict, dev_river: list | None,
-                 exec_mode: int | None = None, spin_limit: int = 0, static_scratch: bool = False):
+                 exec_mode: int | None = None, spin_limit: int = 0, static_scratch: bool = False,
+                 prefill_gemm_min_tokens: int = 0):
         """static_scratch=True goes through river_create_static (no device allocation inside
         the library: activations and barrier counters in the library's static device array)."""
         L = load()
         self.cfg = cfg
-        self._c = make_config(cfg, exec_mode, spin_limit)
+        self._c = make_config(cfg, exec_mode, spin_limit, prefill_gemm_min_tokens)
         self._keep = [dev_weights, dev_river]
         n = cfg.n_layers
         w = river_weights()

@@ -7,7 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "river.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "river_device.h"), os.path.join(ROOT, "include", "river.h")]
+DEPS = [SRC, os.path.join(HERE, "csrc", "river_device.h"), os.path.join(HERE, "csrc", "river_prefill.h"),
+        os.path.join(ROOT, "include", "river.h")]
 LIB = os.path.join(HERE, "libriver.so")
 
 HIPCC_FLAGS = [

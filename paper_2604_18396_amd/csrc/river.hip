@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "river_device.h"
+#include "river_prefill.h"
 
 using namespace river;
 
@@ -245,6 +246,9 @@ struct Layout {
   size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part,
       amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
+  // activation buffers of the GEMM prefill (pf_rows rows each; 0 rows: that path is not offered)
+  size_t pf_tok, pf_h, pf_x16, pf_q16, pf_a16, pf_big;
+  int pf_rows;
 };
 
 
@@ -334,6 +338,7 @@ struct river_ctx {
   size_t lds_bytes;
   bool broken;
   std::string err;
+  std::vector<DevLayer> layers_h;   // host copy of the per-block pointer table (GEMM prefill launches)
 };
 
 static thread_local std::string g_create_err;
@@ -389,6 +394,13 @@ static size_t qsz_matrix_bytes(const river_config *c, int m) {
   return (size_t)(rows * gpr) * (c->dtype == RIVER_BF16 ? 4 : 8);
 }
 
+// Shapes the GEMM prefill handles: bf16 storage, every contraction length a multiple of the
+// 64-column K tile, quantisation groups made of whole K tiles.
+static bool gemm_prefill_ok(const river_config *c) {
+  return c->dtype == RIVER_BF16 && c->d_model % 64 == 0 && c->d_ffn % 64 == 0 &&
+         (c->n_q_heads * c->head_dim) % 64 == 0 && c->river_group % 64 == 0 && c->prefill_gemm_min_tokens >= 0;
+}
+
 static Layout make_layout(const river_config *c) {
   Layout y{};
   const size_t es = c->dtype == RIVER_BF16 ? 2 : 4;
@@ -423,6 +435,18 @@ static Layout make_layout(const river_config *c) {
   for (int m = 0; m < 7; ++m) y.qsz_bytes += align_up(qsz_matrix_bytes(c, m), 256);
   y.qsz_bytes *= (size_t)c->n_layers;
   y.qsz = take(y.qsz_bytes);
+  y.pf_rows = 0;
+  if (gemm_prefill_ok(c)) {
+    const size_t rows = align_up((size_t)std::min(c->max_seq, pf::kChunk), 128);
+    const size_t qd = (size_t)c->n_q_heads * c->head_dim;
+    y.pf_rows = (int)rows;
+    y.pf_tok = take(rows * 4);
+    y.pf_h = take(rows * c->d_model * 4);
+    y.pf_x16 = take(rows * std::max((size_t)c->d_model, qd) * 2);
+    y.pf_q16 = take(rows * qd * 2);
+    y.pf_a16 = take(rows * c->d_ffn * 2);
+    y.pf_big = take(rows * std::max((size_t)2 * c->d_ffn, qd + 2 * kvd) * 4);
+  }
   y.total = off;
   return y;
 }
@@ -668,6 +692,7 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
       }
     if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) packing", e);
   }
+  x->layers_h = hl;
   if ((e = hipMemcpyAsync(act + lay.layers, hl.data(), hl.size() * sizeof(DevLayer),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("layer table upload", e);
@@ -784,6 +809,80 @@ static int check_device_error(river_ctx *x) {
     if ((x)->broken) return RIVER_EHIP;                \
   } while (0)
 
+// GEMM of the prefill: C[rows, N] (+)= A[rows, K] B^T over the stacked matrices ms[0..nm) of block l.
+template <bool W4, bool ADD>
+static void launch_gemm(river_ctx *x, int l, const int *ms, int nm, const _Float16 *A, int K, float *C, int rows) {
+  pf::GemmB B{};
+  int N = 0;
+  for (int i = 0; i < nm; ++i) {
+    long long r, c;
+    matrix_shape(&x->cfg, ms[i], &r, &c);
+    B.w[i] = W4 ? (const void *)x->layers_h[l].qc[ms[i]] : x->layers_h[l].w[ms[i]];
+    B.sz[i] = x->layers_h[l].qsz[ms[i]];
+    B.rows[i] = (int)r;
+    N += (int)r;
+  }
+  for (int i = nm; i < 3; ++i) { B.w[i] = B.w[0]; B.sz[i] = B.sz[0]; B.rows[i] = 0; }
+  const dim3 grid((N + pf::TN - 1) / pf::TN, rows / pf::TM);
+  pf::k_pf_gemm<W4, ADD><<<grid, dim3(256), 0, x->stream>>>(A, K, B, N, K, x->cfg.river_group, C, N);
+}
+
+// Prefill phase on the matrix cores: the prompt in chunks of up to pf_rows tokens, every block
+// as MFMA GEMMs over the chunk (see river_prefill.h); blocks above ep run as river twins.
+static int prefill_gemm(river_ctx *x, const int32_t *tokens, int n, int ep) {
+  const river_config &c = x->cfg;
+  const Dev &D = x->dev;
+  const Layout &y = x->lay;
+  hipStream_t s = x->stream;
+  const int L = c.n_layers, d = c.d_model, qd = c.n_q_heads * c.head_dim, ffn = c.d_ffn;
+  int *tok = (int *)(x->ws + y.pf_tok);
+  float *h = (float *)(x->ws + y.pf_h), *big = (float *)(x->ws + y.pf_big);
+  _Float16 *x16 = (_Float16 *)(x->ws + y.pf_x16), *q16 = (_Float16 *)(x->ws + y.pf_q16);
+  _Float16 *a16 = (_Float16 *)(x->ws + y.pf_a16);
+  const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
+  for (int c0 = 0; c0 < n; c0 += y.pf_rows) {
+    const int m = std::min(y.pf_rows, n - c0), rows = (m + 127) / 128 * 128;
+    const bool last = c0 + m == n;
+    HIP_TRY(x, hipMemcpyAsync(tok, tokens + c0, (size_t)m * 4, hipMemcpyHostToDevice, s));
+    pf::k_pf_embed<<<dim3(m), dim3(256), 0, s>>>(tok, D.tok_emb, d, h);
+    if (last) pf::k_pf_copy_row<<<dim3(4), dim3(256), 0, s>>>(h + (size_t)(m - 1) * d, D.hidden, d);
+    for (int l = 0; l < L; ++l) {
+      const bool river = l >= ep;
+      const DevLayer &W = x->layers_h[l];
+      pf::k_pf_rmsnorm<<<dim3(m), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
+      if (river) launch_gemm<true, false>(x, l, m_qkv, 3, x16, d, big, rows);
+      else launch_gemm<false, false>(x, l, m_qkv, 3, x16, d, big, rows);
+      pf::k_pf_rope_store<<<dim3(m), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, c0, l,
+                                                        c.max_seq, D.kcache, D.vcache, q16);
+      const dim3 ga(c.n_q_heads, (m + 127) / 128);
+      if (c.head_dim == 128)
+        pf::k_pf_attn<128><<<ga, dim3(256), 0, s>>>(q16, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
+                                                    c0, m, x16);
+      else
+        pf::k_pf_attn<64><<<ga, dim3(256), 0, s>>>(q16, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
+                                                   c0, m, x16);
+      if (river) launch_gemm<true, true>(x, l, m_o, 1, x16, qd, h, rows);
+      else launch_gemm<false, true>(x, l, m_o, 1, x16, qd, h, rows);
+      pf::k_pf_rmsnorm<<<dim3(m), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);
+      if (river) launch_gemm<true, false>(x, l, m_gu, 2, x16, d, big, rows);
+      else launch_gemm<false, false>(x, l, m_gu, 2, x16, d, big, rows);
+      pf::k_pf_swiglu<<<dim3(m), dim3(256), 0, s>>>(big, ffn, a16);
+      if (river) launch_gemm<true, true>(x, l, m_d, 1, a16, ffn, h, rows);
+      else launch_gemm<false, true>(x, l, m_d, 1, a16, ffn, h, rows);
+      if (last)
+        pf::k_pf_copy_row<<<dim3(4), dim3(256), 0, s>>>(h + (size_t)(m - 1) * d, D.hidden + (size_t)(l + 1) * d, d);
+    }
+    HIP_TRY(x, hipGetLastError());
+  }
+  // the original final norm + LM head + argmax on the last prompt position (the decode path's kernel)
+  StepArgs A{};
+  A.pos = n - 1; A.token = -1; A.forced_e = ep; A.want_head = 1; A.rec_slot = -1; A.n_splits = 1; A.bar_base = 0;
+  k_head<1><<<dim3(x->grid_gemv), dim3(x->block), x->lds_bytes, s>>>(x->dev_d, A);
+  HIP_TRY(x, hipGetLastError());
+  x->pos = n;
+  return RIVER_OK;
+}
+
 extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, int32_t n_tokens,
                              int32_t prefill_exit_layer, int32_t *out_token, float *out_logits) {
   if (!x) return RIVER_EINVAL;
@@ -804,9 +903,17 @@ extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, i
   if (rc) return rc;
   x->pos = 0;
   x->have_token = false;
-  for (int i = 0; i < n_tokens; ++i) {
-    rc = enqueue(x, tokens[i], ep, i == n_tokens - 1, -1);
+  const int min_gemm = x->cfg.prefill_gemm_min_tokens > 0 ? x->cfg.prefill_gemm_min_tokens : 32;
+  if (x->lay.pf_rows > 0 && n_tokens >= min_gemm) {
+    rc = prefill_gemm(x, tokens, n_tokens, ep);
     if (rc) return rc;
+  } else {
+    // short prompts, fp32 models and shapes the GEMM path does not take: the decode kernels,
+    // one prompt position after the other
+    for (int i = 0; i < n_tokens; ++i) {
+      rc = enqueue(x, tokens[i], ep, i == n_tokens - 1, -1);
+      if (rc) return rc;
+    }
   }
   if (out_logits)
     HIP_TRY(x, hipMemcpyAsync(out_logits, x->dev.logits, (size_t)x->cfg.vocab * 4, hipMemcpyDeviceToDevice,

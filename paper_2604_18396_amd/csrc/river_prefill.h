@@ -1,0 +1,418 @@
+// Prefill phase with sequence-level exit (River-LLM method section, "Inference with Seamless
+// Exit", list of phases): the whole prompt is processed at one unified depth e_p, blocks
+// 1..e_p with the backbone matrices, blocks e_p+1..L with their 4-bit river twins, every
+// block writing K/V of every prompt position into the shared cache slot.  Unlike a decode
+// step this is dense matrix-matrix work, so it runs on the matrix cores: the prompt is cut
+// into chunks of up to kChunk tokens and each block is a sequence of MFMA GEMMs over the
+// chunk (fp16 operands, fp32 accumulation) with small element-wise kernels between them:
+//
+//   embed -> [ rmsnorm -> GEMM(Wq;Wk;Wv) -> rope + cache store -> causal attention
+//              -> GEMM(Wo) += h -> rmsnorm -> GEMM(Wg;Wu) -> swiglu -> GEMM(Wd) += h1 ] x L
+//
+// Operand types: activations are rounded to half precision (fp16) when they enter a GEMM or
+// the attention; backbone weights (bf16) are converted to fp16 while a tile is staged in LDS
+// (exact but for magnitudes below 2^-14); river weights are dequantised, (code - zero) * scale
+// in fp32, and rounded to fp16 while staged; cached K/V (bf16) are converted the same way.
+// The residual stream stays fp32 in HBM.  Only bf16 models take this path.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "river_device.h"
+
+namespace river {
+namespace pf {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kChunk = 1024;          // prompt tokens per pass (rows of the activation buffers)
+constexpr int TM = 128, TN = 128, TK = 64;
+constexpr int LDK = TK + 8;           // LDS row stride in halfs: 144 B, rows 4 banks apart
+
+// v_mfma_f32_32x32x16_f16: D[32x32] += A[32x16] B[16x32].  Lane l supplies row l % 32 of A and
+// column l % 32 of B, eight K values each (those of lane group l / 32; which eight is the same
+// for A and B, so any fixed assignment gives the right sum).  D: register r of lane l is
+// row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32.
+__device__ __forceinline__ f32x16 mfma16(half8 a, half8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ int c_row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// eight bf16 values (16 bytes) -> eight fp16 values
+__device__ __forceinline__ half8 bf16x8_to_half8(const uint4 &w) {
+  half8 h;
+  h[0] = (_Float16)bf16_lo(w.x); h[1] = (_Float16)bf16_hi(w.x);
+  h[2] = (_Float16)bf16_lo(w.y); h[3] = (_Float16)bf16_hi(w.y);
+  h[4] = (_Float16)bf16_lo(w.z); h[5] = (_Float16)bf16_hi(w.z);
+  h[6] = (_Float16)bf16_lo(w.w); h[7] = (_Float16)bf16_hi(w.w);
+  return h;
+}
+
+// ------------------------------------------------------------------ GEMM
+//
+// C[M, N] (+)= A[M, K] B^T, B = up to three matrices stacked along N (rows of W_q, W_k, W_v;
+// of W_gate, W_up), each [rows, K] row-major: dense bf16, or 4-bit codes with one packed
+// (scale, zero) pair per (row, group of `group` columns).  One workgroup of four wavefronts
+// per 128 x 128 tile of C, each wavefront a 64 x 64 quarter (2 x 2 MFMA blocks); K in tiles of
+// 64 staged through LDS, the next tile's global loads in flight while the current one is
+// multiplied.  M must be a multiple of 128 (the activation buffers are; rows beyond the
+// prompt hold don't-care values); N is guarded; K % 64 == 0, group % 64 == 0.
+struct GemmB {
+  const void *w[3];
+  const void *sz[3];
+  int rows[3];
+};
+
+__device__ __forceinline__ void gemm_b_row(const GemmB &B, int n, int N, int &mat, int &row) {
+  n = min(n, N - 1);
+  mat = 0;
+  if (n >= B.rows[0]) { n -= B.rows[0]; mat = 1; }
+  if (mat == 1 && n >= B.rows[1]) { n -= B.rows[1]; mat = 2; }
+  row = n;
+}
+
+template <bool W4, bool ADD>
+__global__ __launch_bounds__(256) void k_pf_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int N, int K,
+                                                 int group, float *C, int ldc) {
+  __shared__ __attribute__((aligned(16))) _Float16 As[TM * LDK];
+  __shared__ __attribute__((aligned(16))) _Float16 Bs[TN * LDK];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  const int wm = wv >> 1, wn = wv & 1;
+
+  // what this thread stages per K tile: four 16-byte segments of A; of B four 16-byte
+  // segments (dense) or one 16-byte run of 32 codes with its (scale, zero) pair (river)
+  const char *a_src[4];
+  int a_dst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int seg = tid + 256 * i, row = seg >> 3, ks = seg & 7;
+    a_src[i] = (const char *)(A + (size_t)(m0 + row) * lda + ks * 8);
+    a_dst[i] = row * LDK + ks * 8;
+  }
+  const char *b_src[W4 ? 1 : 4];
+  const char *b_sz = nullptr;
+  int b_dst[W4 ? 1 : 4];
+  if constexpr (W4) {
+    const int row = tid >> 1, hf = tid & 1;
+    int mat, r;
+    gemm_b_row(B, n0 + row, N, mat, r);
+    b_src[0] = (const char *)B.w[mat] + (size_t)r * (K >> 1) + hf * 16;
+    b_sz = (const char *)B.sz[mat] + (size_t)r * (K / group) * 4;
+    b_dst[0] = row * LDK + hf * 32;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int seg = tid + 256 * i, row = seg >> 3, ks = seg & 7;
+      int mat, r;
+      gemm_b_row(B, n0 + row, N, mat, r);
+      b_src[i] = (const char *)B.w[mat] + ((size_t)r * K + ks * 8) * 2;
+      b_dst[i] = row * LDK + ks * 8;
+    }
+  }
+
+  uint4 ra[4], rb[W4 ? 1 : 4];
+  uint32_t rsz = 0;
+  auto load = [&](int kt) {
+    const int k0 = kt * TK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ra[i] = *(const uint4 *)(a_src[i] + (size_t)k0 * 2);
+    if constexpr (W4) {
+      rb[0] = *(const uint4 *)(b_src[0] + (k0 >> 1));
+      rsz = *(const uint32_t *)(b_sz + (size_t)(k0 / group) * 4);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) rb[i] = *(const uint4 *)(b_src[i] + (size_t)k0 * 2);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *(uint4 *)(As + a_dst[i]) = ra[i];
+    if constexpr (W4) {
+      // weight = (code - zero) * scale in fp32, then fp16; byte j of the run holds column 2j
+      // in its low nibble and column 2j + 1 in its high nibble
+      const float s = bf16_lo(rsz), z = bf16_hi(rsz);
+      const uint32_t wds[4] = {rb[0].x, rb[0].y, rb[0].z, rb[0].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        half8 h;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const uint32_t byte = (wds[w] >> (8 * b)) & 0xffu;
+          h[2 * b] = (_Float16)(((float)(byte & 15u) - z) * s);
+          h[2 * b + 1] = (_Float16)(((float)(byte >> 4) - z) * s);
+        }
+        *(half8 *)(Bs + b_dst[0] + w * 8) = h;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *(half8 *)(Bs + b_dst[i]) = bf16x8_to_half8(rb[i]);
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = K / TK;
+  const int r32 = lane & 31, g8 = (lane >> 5) * 8;
+  load(0);
+  stage();
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + 1 < nk) load(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < TK / 16; ++ks) {
+      half8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = *(const half8 *)(As + (wm * 64 + i * 32 + r32) * LDK + ks * 16 + g8);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = *(const half8 *)(Bs + (wn * 64 + j * 32 + r32) * LDK + ks * 16 + g8);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma16(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+    if (kt + 1 < nk) {
+      stage();
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn * 64 + j * 32 + r32;
+      if (col < N) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float *p = C + (size_t)(m0 + wm * 64 + i * 32 + c_row(r, lane)) * ldc + col;
+          if constexpr (ADD) *p += acc[i][j][r];
+          else *p = acc[i][j][r];
+        }
+      }
+    }
+}
+
+// ------------------------------------------------------- element-wise kernels
+
+// h[t, :] = E[token[t], :] for the m tokens of the chunk; one workgroup per token
+__global__ void k_pf_embed(const int *__restrict__ tokens, const void *tok_emb, int d, float *h) {
+  const int t = blockIdx.x;
+  const size_t src = (size_t)tokens[t] * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)t * d + i] = Store<1>::ld(tok_emb, src + i);
+}
+
+// x16[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain); one workgroup (256) per token
+__global__ __launch_bounds__(256) void k_pf_rmsnorm(const float *__restrict__ h, const void *gain, int d, float eps,
+                                                    _Float16 *x16) {
+  __shared__ float red[16];
+  const int t = blockIdx.x;
+  const float *row = h + (size_t)t * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) ss += row[i] * row[i];
+  const float tot = block_sum(ss, red);
+  const float r = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += blockDim.x)
+    x16[(size_t)t * d + i] = (_Float16)(row[i] * r * Store<1>::ld(gain, i));
+}
+
+// RoPE on q and k at position pos0 + t; q scaled by log2(e) / sqrt(hd) and stored as fp16 for
+// the attention kernel; k (rotated) and v rounded to the cache dtype and written to slot
+// (l, pos0 + t) of the shared cache.  qkv: fp32 [m, qd + 2 kvd] as the QKV GEMM left it.
+// One workgroup per token; thread i handles rotation pair (i, i + hd/2) of one head.
+__global__ void k_pf_rope_store(const float *__restrict__ qkv, const float2 *__restrict__ rope, int nq, int nkv,
+                                int hd, int pos0, int l, int max_seq, void *kcache, void *vcache, _Float16 *q16) {
+  const int t = blockIdx.x, p = pos0 + t, half = hd >> 1;
+  const int qd = nq * hd, kvd = nkv * hd, ld = qd + 2 * kvd;
+  const float *row = qkv + (size_t)t * ld;
+  const float qs = 1.4426950408889634f / sqrtf((float)hd);
+  for (int i = threadIdx.x; i < (nq + nkv) * half; i += blockDim.x) {
+    const int head = i / half, e = i % half;
+    const float2 cs = rope[(size_t)p * half + e];
+    const float *src = row + head * hd;            // q heads, then k heads: contiguous in qkv
+    const float a = src[e], b = src[e + half];
+    const float lo = a * cs.x - b * cs.y, hi = a * cs.y + b * cs.x;
+    if (head < nq) {
+      q16[(size_t)t * qd + head * hd + e] = (_Float16)(lo * qs);
+      q16[(size_t)t * qd + head * hd + e + half] = (_Float16)(hi * qs);
+    } else {
+      const size_t o = ((size_t)l * max_seq + p) * kvd + (size_t)(head - nq) * hd;
+      Store<1>::st(kcache, o + e, lo);
+      Store<1>::st(kcache, o + e + half, hi);
+    }
+  }
+  for (int i = threadIdx.x; i < kvd; i += blockDim.x)
+    Store<1>::st(vcache, ((size_t)l * max_seq + p) * kvd + i, row[qd + kvd + i]);
+}
+
+// a16[t, i] = fp16(silu(G[t, i]) * U[t, i]); gu: fp32 [m, 2 ffn], gate columns first
+__global__ void k_pf_swiglu(const float *__restrict__ gu, int ffn, _Float16 *a16) {
+  const int t = blockIdx.x;
+  const float *row = gu + (size_t)t * 2 * ffn;
+  for (int i = threadIdx.x; i < ffn; i += blockDim.x) {
+    const float g = row[i], u = row[ffn + i];
+    a16[(size_t)t * ffn + i] = (_Float16)(g / (1.0f + expf(-g)) * u);
+  }
+}
+
+// dst[0 .. d) = src[0 .. d)   (the last prompt position's hidden state, kept for the head and
+// for the debug view of h(0..L))
+__global__ void k_pf_copy_row(const float *__restrict__ src, float *dst, int d) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < d; i += gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+// ------------------------------------------------------------- attention
+//
+// Causal attention of the chunk's queries (positions pos0 .. pos0 + m - 1) over cache
+// positions 0 .. their own.  One workgroup of four wavefronts per (query head, 128 queries),
+// 32 queries per wavefront.  Keys in tiles of 64 through LDS.  Transposed products, so that
+// the softmax over keys runs along a lane's registers and the probabilities feed the second
+// product from the registers they are in:
+//   S^T[key, q] = K[key, :] . Q[q, :]        A = K tile rows (LDS), B = Q (registers, whole loop)
+//   O^T[d, q]  += V^T[d, key] P^T[key, q]    A = V tile stored transposed (LDS), B = P^T (registers)
+// In S^T's register layout lane l holds, for query l % 32, keys (r/4)*8 + (l/32)*4 + r%4: the
+// eight keys of registers 0..7 (8..15) are the K slots of that lane group in the first
+// (second) MFMA of a 32-key block, and V^T is read from LDS with the same assignment.
+// The scores carry log2(e)/sqrt(hd) (folded into q16): base-2 online softmax.
+template <int HD>
+__global__ __launch_bounds__(256) void k_pf_attn(const _Float16 *__restrict__ q16, const void *kcache,
+                                                 const void *vcache, int nq, int nkv, int l, int max_seq, int pos0,
+                                                 int m, _Float16 *o16) {
+  constexpr int LDH = HD + 8;                 // K tile row stride (halfs)
+  constexpr int LDV = 64 + 8;                 // V^T tile row stride (halfs)
+  __shared__ __attribute__((aligned(16))) _Float16 Ks[64 * LDH];
+  __shared__ __attribute__((aligned(16))) _Float16 Vt[HD * LDV];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int h = blockIdx.x, kvh = h / (nq / nkv);
+  const int q0 = blockIdx.y * 128 + wv * 32;               // first query (chunk-relative) of this wavefront
+  const int r32 = lane & 31, g = lane >> 5;
+  const int qd = nq * HD, kvd = nkv * HD;
+  const int tq = min(q0 + r32, m - 1);                      // this lane's query row (clamped: rows >= m are don't-care)
+  const int my_pos = pos0 + q0 + r32;                       // its position (unclamped: masks keys beyond it)
+
+  // Q of this wavefront as the B operand of S^T: for K step ks lane group g holds
+  // d = ks*16 + g*8 .. +7 of query l % 32
+  half8 qb[HD / 16];
+#pragma unroll
+  for (int ks = 0; ks < HD / 16; ++ks)
+    qb[ks] = *(const half8 *)(q16 + (size_t)tq * qd + h * HD + ks * 16 + g * 8);
+
+  f32x16 oacc[HD / 32];
+#pragma unroll
+  for (int b = 0; b < HD / 32; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[b][r] = 0.f;
+  float mrun = -1.0e30f, lrun = 0.f;
+
+  const int last_pos = min(pos0 + (int)blockIdx.y * 128 + 127, pos0 + m - 1);   // last key any query here attends
+  const size_t cbase = (size_t)l * max_seq * kvd + (size_t)kvh * HD;
+  for (int kt = 0; kt <= last_pos; kt += 64) {
+    __syncthreads();                                        // previous tile consumed
+    // stage the K tile [64 keys][HD] (16-byte runs along d, consecutive lanes along d) and the V
+    // tile transposed [HD][64 keys] (consecutive lanes along the keys, so that the 2-byte
+    // transposed stores of a wavefront fall into one row)
+    for (int seg = tid; seg < 64 * (HD / 8); seg += 256) {
+      const int key = seg / (HD / 8), ds = seg % (HD / 8);
+      const int p = min(kt + key, last_pos);
+      const uint4 kw = *(const uint4 *)((const char *)kcache + (cbase + (size_t)p * kvd + ds * 8) * 2);
+      *(half8 *)(Ks + key * LDH + ds * 8) = bf16x8_to_half8(kw);
+    }
+    for (int seg = tid; seg < 64 * (HD / 8); seg += 256) {
+      const int key = seg & 63, ds = seg >> 6;
+      const int p = min(kt + key, last_pos);
+      const uint4 vw = *(const uint4 *)((const char *)vcache + (cbase + (size_t)p * kvd + ds * 8) * 2);
+      const half8 vh = bf16x8_to_half8(vw);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Vt[(ds * 8 + e) * LDV + key] = vh[e];
+    }
+    __syncthreads();
+    // wavefronts whose queries all lie before this tile have nothing to add (uniform per wavefront)
+    if (kt > pos0 + q0 + 31) continue;
+
+    // S^T for the two 32-key blocks of the tile
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < HD / 16; ++ks) {
+        const half8 ka = *(const half8 *)(Ks + (kb * 32 + r32) * LDH + ks * 16 + g * 8);
+        s[kb] = mfma16(ka, qb[ks], s[kb]);
+      }
+    }
+    // mask keys beyond the query's position, running maximum over the lane's 32 keys and the
+    // other lane group's 32
+    float mx = mrun;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = kt + kb * 32 + c_row(r, lane);
+        if (key > my_pos) s[kb][r] = -1.0e30f;
+        mx = fmaxf(mx, s[kb][r]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float corr = __builtin_amdgcn_exp2f(mrun - mx);
+    mrun = mx;
+    float psum = 0.f;
+    half8 pb[2][2];                                          // [key block][MFMA of the block]: B operands
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = s[kb][r] > -0.5e30f ? __builtin_amdgcn_exp2f(s[kb][r] - mx) : 0.f;
+        const _Float16 ph = (_Float16)p;
+        psum += (float)ph;                                   // the sum of what is actually multiplied
+        pb[kb][r >> 3][r & 7] = ph;
+      }
+    psum += __shfl_xor(psum, 32);
+    lrun = lrun * corr + psum;
+#pragma unroll
+    for (int b = 0; b < HD / 32; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[b][r] *= corr;
+    // O^T += V^T P^T: per 32-key block two MFMAs; K slots of lane group g in MFMA j are keys
+    // kb*32 + j*16 + {g*4 .. g*4+3, 8 + g*4 .. 8 + g*4+3} (registers 8j .. 8j+7 of S^T)
+#pragma unroll
+    for (int b = 0; b < HD / 32; ++b)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const _Float16 *vp = Vt + (b * 32 + r32) * LDV + kb * 32 + j * 16 + g * 4;
+          const half4 v0 = *(const half4 *)vp, v1 = *(const half4 *)(vp + 8);
+          half8 va;
+          va[0] = v0[0]; va[1] = v0[1]; va[2] = v0[2]; va[3] = v0[3];
+          va[4] = v1[0]; va[5] = v1[1]; va[6] = v1[2]; va[7] = v1[3];
+          oacc[b] = mfma16(va, pb[kb][j], oacc[b]);
+        }
+  }
+  // O^T[d, q] / l -> o16[q, h*HD + d]; registers 4i .. 4i+3 are four consecutive d
+  if (q0 + r32 < m) {
+    const float inv = 1.0f / lrun;
+#pragma unroll
+    for (int b = 0; b < HD / 32; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (_Float16)(oacc[b][4 * i + e] * inv);
+        *(half4 *)(o16 + (size_t)(q0 + r32) * qd + h * HD + b * 32 + c_row(4 * i, lane)) = o;
+      }
+  }
+}
+
+}  // namespace pf
+}  // namespace river
