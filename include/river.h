@@ -62,7 +62,9 @@ typedef struct {
   float rope_base; /* theta_i = rope_base^(-2i/head_dim), rotate-half pairing (i, i+head_dim/2) */
   float rms_eps;
   int32_t dtype;          /* RIVER_F32 or RIVER_BF16: weights, river scale/zero, KV cache */
-  int32_t max_batch;      /* must be 1 */
+  int32_t max_batch;      /* sequences the context holds, 1..32.  1: the batch-1 decode path
+                             (river_decode_step).  > 1: a batched context (river_decode_batch); needs RIVER_BF16
+                             and d_model, d_ffn, river_group multiples of 64 */
   int32_t max_seq;        /* KV-cache capacity in positions */
   int32_t min_exit_layer; /* L_s: smallest allowed exit position ("predefined entry layer") */
   float tau;              /* Eq. 1 threshold, strict '>' ; tau >= 1 never exits */
@@ -74,6 +76,9 @@ typedef struct {
                                       (RIVER_BF16, d_model, d_ffn and river_group multiples of 64); shorter
                                       ones, and all other configurations, run the decode kernels per prompt
                                       position.  0 = default (32); negative = never */
+  int32_t batch_exit_rule; /* batched contexts, when Eq. 1 decides: 0 = every sequence for itself
+                              (s_b > tau); 1 = Eq. 1 as printed: the whole batch leaves the backbone together at
+                              the first block with min over the batch of s_b > tau */
 } river_config;
 
 /* Backbone weights.  DEVICE pointers in HOST arrays of length n_layers. */
@@ -152,7 +157,7 @@ int river_create_static(const river_config *cfg, const river_weights *w, const r
  * positions 0..n_tokens-1 of every block.  e_p must lie in [L_s, L]; negative or L =
  * the full backbone depth (then no river weights are needed).  How e_p is chosen the
  * paper leaves open: it is the caller's.  Restarts the sequence at position 0.
- * seq must be 0.  tokens: HOST [n_tokens].  out_token: HOST, the greedy token after
+ * seq: the sequence (0 unless the context is batched).  tokens: HOST [n_tokens].  out_token: HOST, the greedy token after
  * the last prompt position (nullable).  out_logits: DEVICE fp32 [vocab], the logits of
  * the last prompt position (nullable).  Synchronises the stream.
  */
@@ -176,27 +181,54 @@ int river_prefill(river_ctx *ctx, int32_t seq, const int32_t *tokens, int32_t n_
 int river_decode_step(river_ctx *ctx, const int32_t *in_token, const int32_t *forced_exit,
                       int32_t *out_token, int32_t *out_exit_layer, float *out_sims);
 
+/*
+ * One decode step of a batched context (max_batch > 1) for sequences 0..n_seq-1, each at
+ * its own position and with its own exit depth ("Inference with Seamless Exit"; Eq. 1 is
+ * stated over a batch B).  Every sequence must have been prefilled (river_prefill with its
+ * seq index).  Per block the rows still in the backbone run the bf16 matrices and the rows
+ * that have left it the 4-bit twins, both as MFMA GEMMs that write K/V to the sequence's
+ * own slot of the shared cache; which side a row is on is decided on the device after each
+ * backbone block by cfg.batch_exit_rule, or imposed by forced_exit.
+ * in_tokens:   HOST [n_seq] or NULL (= the tokens the previous step / prefill produced).
+ * forced_exit: HOST [n_seq] or NULL; entry b < 0 lets Eq. 1 decide for sequence b, else
+ *              the exit position to impose, in [L_s, L] (or 0 when L_s == 0).
+ * out_tokens, out_exit_layers: HOST [n_seq]; out_sims: HOST [n_seq][n_layers] (NaN for
+ *              blocks run as river twins); all nullable; if out_tokens is NULL the call
+ *              does not synchronise (read results with river_read_batch_records).
+ * Advances every sequence by one position.
+ */
+int river_decode_batch(river_ctx *ctx, int32_t n_seq, const int32_t *in_tokens, const int32_t *forced_exit,
+                       int32_t *out_tokens, int32_t *out_exit_layers, float *out_sims);
+
+/* Synchronises and copies tokens and exit positions of the last n_steps batched steps (at most
+ * 1024, oldest first) for sequences 0..n_seq-1.  tokens, exit_layers: HOST [n_steps][n_seq]. */
+int river_read_batch_records(river_ctx *ctx, int32_t n_steps, int32_t n_seq, int32_t *tokens,
+                             int32_t *exit_layers);
+
 /* Synchronises and copies the records of the last n decode steps (n <= 4096, oldest
  * first).  tokens, exit_layers: HOST [n]; sims: HOST [n][n_layers], nullable. */
 int river_read_records(river_ctx *ctx, int32_t n, int32_t *tokens, int32_t *exit_layers,
                        float *sims);
 
-/* Moves the sequence back to new_len positions (0 <= new_len <= current length) so
+/* Moves sequence seq back to new_len positions (0 <= new_len <= current length) so
  * that steps can be replayed; cache contents are left as they are. */
 int river_rewind(river_ctx *ctx, int32_t seq, int32_t new_len);
 
 /* Number of positions currently in the cache, or a negative error. */
 int river_position(const river_ctx *ctx);
+int river_seq_position(const river_ctx *ctx, int32_t seq); /* the same for sequence seq of a batched context */
 
 enum {
   RIVER_DBG_HIDDEN = 0, /* fp32 [n_layers+1][d_model]: h(0..L) of the last token processed */
   RIVER_DBG_LOGITS = 1, /* fp32 [vocab] of the last step that ran the head */
-  RIVER_DBG_KCACHE = 2, /* cache dtype [n_layers][max_seq][n_kv_heads*head_dim] */
+  RIVER_DBG_KCACHE = 2, /* cache dtype [max_batch][n_layers][max_seq][n_kv_heads*head_dim] */
   RIVER_DBG_VCACHE = 3,
-  RIVER_DBG_TRACE = 4   /* uint64 [5*n_layers][2][workgroups] then [64]: 100 MHz device clock at which each
+  RIVER_DBG_TRACE = 4,  /* uint64 [5*n_layers][2][workgroups] then [64]: 100 MHz device clock at which each
                            workgroup arrived at / was released from each device-wide barrier of the last
                            launch, then 64 marks inside the phases (PERSISTENT mode of a library built
                            with -DRIVER_TRACE; zeros otherwise); bytes = (5*n_layers*2*workgroups + 64)*8 */
+  RIVER_DBG_BATCH_HIDDEN = 5, /* batched context: fp32 [n_layers+1][max_batch][d_model] of the last step */
+  RIVER_DBG_BATCH_LOGITS = 6  /* batched context: fp32 [max_batch][vocab] of the last step */
 };
 /* Synchronises and copies a device buffer to dst (HOST, `bytes` must equal its size). */
 int river_get_debug(river_ctx *ctx, int32_t what, void *dst, size_t bytes);

@@ -461,6 +461,39 @@ int orc_decode_step(orc_ctx *x, int32_t token, int32_t forced_e, int32_t *out_to
   return ORC_OK;
 }
 
+/*
+ * The pieces of step() on their own, for the batched form of Eq. 1: there the exit decision
+ * after block l looks at every sequence of the batch (the minimum of their similarities),
+ * so a batch is stepped block by block over one context per sequence (oracle/batch_oracle.py):
+ * orc_embed, orc_block for l = 1..L at position orc_pos, orc_head, orc_advance.
+ */
+int orc_embed(const orc_ctx *x, int token, double *h) {
+  if (!x || !h || token < 0 || token >= x->c.vocab) return ORC_EINVAL;
+  for (int i = 0; i < x->c.d_model; ++i) h[i] = ld(x->tok_emb, (int64_t)token * x->c.d_model + i, x->c.dtype);
+  return ORC_OK;
+}
+
+/* logits = W_head RMSNorm(h) g_final (kept in the context), greedy token, lowest index on ties */
+int orc_head(orc_ctx *x, const double *h, int32_t *out_token) {
+  if (!x || !h) return ORC_EINVAL;
+  const orc_config *c = &x->c;
+  double *xn = malloc(sizeof(double) * c->d_model);
+  orc_rmsnorm(h, x->final_norm, c->dtype, c->d_model, c->rms_eps, xn);
+  matvec(x->lm_head, c->dtype, c->vocab, c->d_model, xn, x->logits);
+  free(xn);
+  int best = 0;
+  for (int i = 1; i < c->vocab; ++i)
+    if (x->logits[i] > x->logits[best]) best = i;
+  if (out_token) *out_token = best;
+  return ORC_OK;
+}
+
+int orc_advance(orc_ctx *x) {
+  if (!x || x->pos >= x->c.max_seq) return ORC_ENOSPC;
+  x->pos += 1;
+  return ORC_OK;
+}
+
 int orc_rewind(orc_ctx *x, int new_len) {
   if (!x || new_len < 0 || new_len > x->pos) return ORC_EINVAL;
   for (int l = 0; l < x->c.n_layers; ++l)

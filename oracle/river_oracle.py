@@ -60,6 +60,9 @@ def lib():
         L.orc_rewind.argtypes = [C.c_void_p, C.c_int]
         L.orc_pos.argtypes = [C.c_void_p]
         L.orc_block.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.orc_embed.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        L.orc_head.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+        L.orc_advance.argtypes = [C.c_void_p]
         for name, rt in (("orc_hidden", C.c_double), ("orc_logits", C.c_double),
                          ("orc_kcache", C.c_float), ("orc_vcache", C.c_float),
                          ("orc_written", C.c_uint8)):
@@ -219,6 +222,24 @@ class Oracle:
         c = self.cfg
         return np.ctypeslib.as_array(lib().orc_written(self._h), (c.n_layers * c.max_seq,)).reshape(
             c.n_layers, c.max_seq)
+
+    def embed(self, token: int) -> np.ndarray:
+        h = np.empty(self.cfg.d_model, dtype=np.float64)
+        if lib().orc_embed(self._h, int(token), _ptr(h)):
+            raise ValueError("orc_embed failed")
+        return h
+
+    def head(self, h: np.ndarray) -> int:
+        """Final norm + LM head on h (logits() afterwards); returns the greedy token."""
+        h = np.ascontiguousarray(h, dtype=np.float64)
+        tok = C.c_int32()
+        if lib().orc_head(self._h, _ptr(h), C.byref(tok)):
+            raise ValueError("orc_head failed")
+        return tok.value
+
+    def advance(self):
+        if lib().orc_advance(self._h):
+            raise ValueError("orc_advance failed")
 
     def block(self, layer1: int, pos: int, river: bool, h: np.ndarray) -> np.ndarray:
         h = np.ascontiguousarray(h, dtype=np.float64)

@@ -17,10 +17,12 @@ from .configs import MATRICES, ModelConfig
 
 RIVER_OK, RIVER_EINVAL, RIVER_ENOSPC, RIVER_ESTATE, RIVER_EHIP = 0, -1, -2, -3, -4
 EXEC_KERNELS, EXEC_PERSISTENT = 0, 1
-DBG_HIDDEN, DBG_LOGITS, DBG_KCACHE, DBG_VCACHE, DBG_TRACE = 0, 1, 2, 3, 4
+DBG_HIDDEN, DBG_LOGITS, DBG_KCACHE, DBG_VCACHE, DBG_TRACE, DBG_BATCH_HIDDEN, DBG_BATCH_LOGITS = 0, 1, 2, 3, 4, 5, 6
+EXIT_PER_SEQUENCE, EXIT_BATCH_MIN = 0, 1
 
 EXPORTS = ("river_quantize_w4", "river_workspace_bytes", "river_create", "river_create_static", "river_prefill",
-           "river_decode_step", "river_read_records", "river_rewind", "river_position",
+           "river_decode_step", "river_decode_batch", "river_read_batch_records", "river_read_records",
+           "river_rewind", "river_position", "river_seq_position",
            "river_get_debug", "river_fill_cache", "river_last_error", "river_destroy")
 
 
@@ -36,7 +38,8 @@ class river_config(C.Structure):
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
                 ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("min_exit_layer", C.c_int32),
                 ("tau", C.c_float), ("river_bits", C.c_int32), ("river_group", C.c_int32),
-                ("exec_mode", C.c_int32), ("spin_limit", C.c_int32), ("prefill_gemm_min_tokens", C.c_int32)]
+                ("exec_mode", C.c_int32), ("spin_limit", C.c_int32), ("prefill_gemm_min_tokens", C.c_int32),
+                ("batch_exit_rule", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -77,6 +80,10 @@ def load():
                                 C.POINTER(C.c_int32), C.c_void_p]
     L.river_decode_step.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
+    L.river_decode_batch.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p]
+    L.river_read_batch_records.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.river_seq_position.argtypes = [C.c_void_p, C.c_int32]
     L.river_read_records.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     L.river_rewind.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.river_position.argtypes = [C.c_void_p]
@@ -95,13 +102,13 @@ def default_exec_mode(cfg: ModelConfig) -> int:
 
 
 def make_config(cfg: ModelConfig, exec_mode: int | None = None, spin_limit: int = 0,
-                prefill_gemm_min_tokens: int = 0) -> river_config:
+                prefill_gemm_min_tokens: int = 0, max_batch: int = 1, batch_exit_rule: int = 0) -> river_config:
     if exec_mode is None:
         exec_mode = default_exec_mode(cfg)
     return river_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
-                        cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps, cfg.dtype, 1, cfg.max_seq,
+                        cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps, cfg.dtype, max_batch, cfg.max_seq,
                         cfg.min_exit_layer, cfg.tau, 4, cfg.river_group, exec_mode, spin_limit,
-                        prefill_gemm_min_tokens)
+                        prefill_gemm_min_tokens, batch_exit_rule)
 
 
 def _stream_ptr() -> int:
@@ -142,12 +149,13 @@ class River:
 
     def __init__(self, cfg: ModelConfig, dev_weights: dict, dev_river: list | None,
                  exec_mode: int | None = None, spin_limit: int = 0, static_scratch: bool = False,
-                 prefill_gemm_min_tokens: int = 0):
+                 prefill_gemm_min_tokens: int = 0, max_batch: int = 1, batch_exit_rule: int = 0):
         """static_scratch=True goes through river_create_static (no device allocation inside
         the library: activations and barrier counters in the library's static device array)."""
         L = load()
         self.cfg = cfg
-        self._c = make_config(cfg, exec_mode, spin_limit, prefill_gemm_min_tokens)
+        self._c = make_config(cfg, exec_mode, spin_limit, prefill_gemm_min_tokens, max_batch, batch_exit_rule)
+        self.max_batch = max_batch
         self._keep = [dev_weights, dev_river]
         n = cfg.n_layers
         w = river_weights()
@@ -194,15 +202,17 @@ class River:
         except Exception:
             pass
 
-    def prefill(self, tokens, exit_layer: int | None = None, out_logits: torch.Tensor | None = None) -> int:
+    def prefill(self, tokens, exit_layer: int | None = None, out_logits: torch.Tensor | None = None,
+                seq: int = 0) -> int:
         """Prefill phase at the unified depth exit_layer (None: the full depth L).
-        out_logits: optional device fp32 [vocab] tensor that receives the last position's logits."""
+        out_logits: optional device fp32 [vocab] tensor that receives the last position's logits.
+        seq: the sequence of a batched context."""
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         out = C.c_int32()
         if out_logits is not None:
             assert out_logits.is_cuda and out_logits.dtype == torch.float32 and out_logits.is_contiguous()
             assert out_logits.numel() == self.cfg.vocab
-        self._check(load().river_prefill(self._h, 0, t.ctypes.data, len(t),
+        self._check(load().river_prefill(self._h, seq, t.ctypes.data, len(t),
                                          -1 if exit_layer is None else int(exit_layer), C.byref(out),
                                          out_logits.data_ptr() if out_logits is not None else None))
         return out.value
@@ -220,6 +230,43 @@ class River:
                                              sims.ctypes.data))
         return tok.value, e.value, sims
 
+    def decode_batch(self, n_seq: int, tokens=None, forced_exits=None, sync: bool = True):
+        """One step of a batched context.  sync=True -> (tokens[n], exit_positions[n], sims[n, L])."""
+        tin = np.ascontiguousarray(tokens, dtype=np.int32) if tokens is not None else None
+        fe = (np.ascontiguousarray([-1 if f is None else int(f) for f in forced_exits], dtype=np.int32)
+              if forced_exits is not None else None)
+        a = tin.ctypes.data if tin is not None else None
+        b = fe.ctypes.data if fe is not None else None
+        if not sync:
+            self._check(load().river_decode_batch(self._h, n_seq, a, b, None, None, None))
+            return None
+        toks = np.empty(n_seq, dtype=np.int32)
+        es = np.empty(n_seq, dtype=np.int32)
+        sims = np.empty((n_seq, self.cfg.n_layers), dtype=np.float32)
+        self._check(load().river_decode_batch(self._h, n_seq, a, b, toks.ctypes.data, es.ctypes.data,
+                                              sims.ctypes.data))
+        return toks, es, sims
+
+    def read_batch_records(self, n_steps: int, n_seq: int):
+        toks = np.empty((n_steps, n_seq), dtype=np.int32)
+        es = np.empty((n_steps, n_seq), dtype=np.int32)
+        self._check(load().river_read_batch_records(self._h, n_steps, n_seq, toks.ctypes.data, es.ctypes.data))
+        return toks, es
+
+    def seq_pos(self, seq: int) -> int:
+        return load().river_seq_position(self._h, seq)
+
+    def batch_hidden(self) -> np.ndarray:
+        """[L+1, max_batch, d] hidden states of the last batched step."""
+        out = np.empty((self.cfg.n_layers + 1, self.max_batch, self.cfg.d_model), dtype=np.float32)
+        self._check(load().river_get_debug(self._h, DBG_BATCH_HIDDEN, out.ctypes.data, out.nbytes))
+        return out
+
+    def batch_logits(self) -> np.ndarray:
+        out = np.empty((self.max_batch, self.cfg.vocab), dtype=np.float32)
+        self._check(load().river_get_debug(self._h, DBG_BATCH_LOGITS, out.ctypes.data, out.nbytes))
+        return out
+
     def read_records(self, n: int):
         toks = np.empty(n, dtype=np.int32)
         es = np.empty(n, dtype=np.int32)
@@ -228,8 +275,8 @@ class River:
                                               sims.ctypes.data))
         return toks, es, sims
 
-    def rewind(self, new_len: int):
-        self._check(load().river_rewind(self._h, 0, new_len))
+    def rewind(self, new_len: int, seq: int = 0):
+        self._check(load().river_rewind(self._h, seq, new_len))
 
     @property
     def pos(self) -> int:
@@ -248,11 +295,12 @@ class River:
     def _cache(self, what) -> np.ndarray:
         c = self.cfg
         kvd = c.n_kv_heads * c.head_dim
+        shape = (c.n_layers, c.max_seq, kvd) if self.max_batch == 1 else (self.max_batch, c.n_layers, c.max_seq, kvd)
         if c.dtype == 1:
-            raw = np.empty((c.n_layers, c.max_seq, kvd), dtype=np.uint16)
+            raw = np.empty(shape, dtype=np.uint16)
             self._check(load().river_get_debug(self._h, what, raw.ctypes.data, raw.nbytes))
             return (raw.astype(np.uint32) << 16).view(np.float32)      # bf16 words -> fp32 values
-        raw = np.empty((c.n_layers, c.max_seq, kvd), dtype=np.float32)
+        raw = np.empty(shape, dtype=np.float32)
         self._check(load().river_get_debug(self._h, what, raw.ctypes.data, raw.nbytes))
         return raw
 
@@ -290,6 +338,14 @@ def river_prefill(ctx: River, tokens, exit_layer=None, out_logits=None) -> int:
 
 def river_decode_step(ctx: River, token=None, forced_exit=None, sync=True):
     return ctx.decode_step(token, forced_exit, sync)
+
+
+def river_decode_batch(ctx: River, n_seq: int, tokens=None, forced_exits=None, sync=True):
+    return ctx.decode_batch(n_seq, tokens, forced_exits, sync)
+
+
+def river_read_batch_records(ctx: River, n_steps: int, n_seq: int):
+    return ctx.read_batch_records(n_steps, n_seq)
 
 
 def river_read_records(ctx: River, n: int):

@@ -55,3 +55,17 @@ def backbone_param_bytes(cfg: ModelConfig) -> int:
 
 def kv_cache_bytes(cfg: ModelConfig, context: int) -> int:
     return kv_bytes_per_position(cfg) * context
+
+
+def batch_step_bytes(cfg: ModelConfig, exit_positions, attended) -> int:
+    """One batched decode step: block l (1-based) reads the backbone matrices if any sequence
+    is still in the backbone there (exit position >= l) and the river twin if any sequence has
+    left it (exit position < l); the head once; every sequence its own K/V."""
+    total = head_bytes(cfg)
+    for l in range(1, cfg.n_layers + 1):
+        if any(e >= l for e in exit_positions):
+            total += block_bytes_backbone(cfg)
+        if any(e < l for e in exit_positions):
+            total += block_bytes_river(cfg)
+    total += sum(kv_bytes_per_position(cfg) * t for t in attended)
+    return total

@@ -249,6 +249,8 @@ struct Layout {
   // activation buffers of the GEMM prefill (pf_rows rows each; 0 rows: that path is not offered)
   size_t pf_tok, pf_h, pf_x16, pf_q16, pf_a16, pf_big;
   int pf_rows;
+  // batched contexts (max_batch > 1): per-sequence state, step buffers, records
+  size_t bd_state, bd_hprev, bd_qf, bd_logits, bd_hist, bd_rec_token, bd_rec_exit, bd_rec_sims;
 };
 
 
@@ -339,11 +341,22 @@ struct river_ctx {
   bool broken;
   std::string err;
   std::vector<DevLayer> layers_h;   // host copy of the per-block pointer table (GEMM prefill launches)
+  std::vector<int> pos_b;           // batched contexts: positions in the cache, per sequence
+  long long steps_b = 0;            // batched decode steps recorded so far
+  int last_n = 0;                   // sequences of the last batched step
+  bd::SeqState st_b{};
 };
 
 static thread_local std::string g_create_err;
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Shapes the GEMM prefill handles: bf16 storage, every contraction length a multiple of the
+// 64-column K tile, quantisation groups made of whole K tiles.
+static bool gemm_prefill_ok(const river_config *c) {
+  return c->dtype == RIVER_BF16 && c->d_model % 64 == 0 && c->d_ffn % 64 == 0 &&
+         (c->n_q_heads * c->head_dim) % 64 == 0 && c->river_group % 64 == 0 && c->prefill_gemm_min_tokens >= 0;
+}
 
 static bool valid_cfg(const river_config *c, std::string *why) {
   auto bad = [&](const char *m) { if (why) *why = m; return false; };
@@ -352,7 +365,8 @@ static bool valid_cfg(const river_config *c, std::string *why) {
       c->vocab < 1 || c->max_seq < 1)
     return bad("non-positive dimension");
   if (c->dtype != RIVER_F32 && c->dtype != RIVER_BF16) return bad("dtype must be RIVER_F32 or RIVER_BF16");
-  if (c->max_batch != 1) return bad("max_batch must be 1");
+  if (c->max_batch < 1 || c->max_batch > bd::kRows) return bad("max_batch must be in [1, 32]");
+  if (c->batch_exit_rule != 0 && c->batch_exit_rule != 1) return bad("batch_exit_rule must be 0 or 1");
   if (c->river_bits != 4) return bad("river_bits must be 4");
   if (c->river_group < 32 || c->river_group % 32) return bad("river_group must be a multiple of 32");
   if (c->n_q_heads % c->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
@@ -366,6 +380,12 @@ static bool valid_cfg(const river_config *c, std::string *why) {
     return bad("RIVER_EXEC_PERSISTENT is available for RIVER_BF16 only; use RIVER_EXEC_KERNELS for RIVER_F32");
   if (c->spin_limit < 0) return bad("negative spin_limit");
   if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return bad("bad rope_base / rms_eps");
+  if (c->max_batch > 1) {
+    if (!gemm_prefill_ok(c))
+      return bad("max_batch > 1 needs RIVER_BF16 with d_model, d_ffn and river_group multiples of 64 and the GEMM "
+                 "prefill enabled");
+    if (bd::attn_lds_bytes(c->max_seq) > 65536) return bad("max_batch > 1 supports max_seq up to about 15900");
+  }
   return true;
 }
 
@@ -394,22 +414,15 @@ static size_t qsz_matrix_bytes(const river_config *c, int m) {
   return (size_t)(rows * gpr) * (c->dtype == RIVER_BF16 ? 4 : 8);
 }
 
-// Shapes the GEMM prefill handles: bf16 storage, every contraction length a multiple of the
-// 64-column K tile, quantisation groups made of whole K tiles.
-static bool gemm_prefill_ok(const river_config *c) {
-  return c->dtype == RIVER_BF16 && c->d_model % 64 == 0 && c->d_ffn % 64 == 0 &&
-         (c->n_q_heads * c->head_dim) % 64 == 0 && c->river_group % 64 == 0 && c->prefill_gemm_min_tokens >= 0;
-}
-
 static Layout make_layout(const river_config *c) {
   Layout y{};
   const size_t es = c->dtype == RIVER_BF16 ? 2 : 4;
   const size_t kvd = (size_t)c->n_kv_heads * c->head_dim;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  y.cache_bytes = (size_t)c->n_layers * c->max_seq * kvd * es;
-  y.kcache = take(y.cache_bytes);
-  y.vcache = take(y.cache_bytes);
+  y.cache_bytes = (size_t)c->n_layers * c->max_seq * kvd * es;      // one sequence
+  y.kcache = take(y.cache_bytes * c->max_batch);
+  y.vcache = take(y.cache_bytes * c->max_batch);
   y.rope = take((size_t)c->max_seq * (c->head_dim / 2) * sizeof(float2));
   y.hidden = take((size_t)(c->n_layers + 1) * c->d_model * 4);
   y.qbuf = take((size_t)c->n_q_heads * c->head_dim * 4);
@@ -446,6 +459,17 @@ static Layout make_layout(const river_config *c) {
     y.pf_q16 = take(rows * qd * 2);
     y.pf_a16 = take(rows * c->d_ffn * 2);
     y.pf_big = take(rows * std::max((size_t)2 * c->d_ffn, qd + 2 * kvd) * 4);
+  }
+  if (c->max_batch > 1) {
+    const size_t B = c->max_batch, qd = (size_t)c->n_q_heads * c->head_dim;
+    y.bd_state = take(6 * B * 4);
+    y.bd_hprev = take((size_t)bd::kRows * c->d_model * 4);
+    y.bd_qf = take((size_t)bd::kRows * qd * 4);
+    y.bd_logits = take(B * c->vocab * 4);
+    y.bd_hist = take((size_t)(c->n_layers + 1) * B * c->d_model * 4);
+    y.bd_rec_token = take((size_t)bd::kRecordsB * B * 4);
+    y.bd_rec_exit = take((size_t)bd::kRecordsB * B * 4);
+    y.bd_rec_sims = take((size_t)bd::kRecordsB * B * c->n_layers * 4);
   }
   y.total = off;
   return y;
@@ -693,6 +717,15 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
     if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) packing", e);
   }
   x->layers_h = hl;
+  x->pos_b.assign(cfg->max_batch, 0);
+  if (cfg->max_batch > 1) {
+    int *sp = (int *)(ws + lay.bd_state);
+    const int B = cfg->max_batch;
+    x->st_b.pos = sp; x->st_b.token = sp + B; x->st_b.river = sp + 2 * B; x->st_b.exit_pos = sp + 3 * B;
+    x->st_b.forced = sp + 4 * B;
+    if ((e = hipMemsetAsync(ws + lay.bd_state, 0, (size_t)6 * B * 4, x->stream)) != hipSuccess)
+      return fail("sequence state clear", e);
+  }
   if ((e = hipMemcpyAsync(act + lay.layers, hl.data(), hl.size() * sizeof(DevLayer),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
     return fail("layer table upload", e);
@@ -702,7 +735,8 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
     return fail("workspace clear", e);
   if (use_static && (e = hipMemsetAsync(static_bar, 0, kBarBytes, x->stream)) != hipSuccess)
     return fail("barrier block clear", e);
-  if ((e = hipMemsetAsync(ws + lay.kcache, 0, 2 * align_up(lay.cache_bytes, 256), x->stream)) != hipSuccess)
+  if ((e = hipMemsetAsync(ws + lay.kcache, 0, lay.vcache - lay.kcache + align_up(lay.cache_bytes * cfg->max_batch, 256),
+                          x->stream)) != hipSuccess)
     return fail("cache clear", e);
   if ((e = hipStreamSynchronize(x->stream)) != hipSuccess) return fail("create sync", e);
 
@@ -829,7 +863,7 @@ static void launch_gemm(river_ctx *x, int l, const int *ms, int nm, const _Float
 
 // Prefill phase on the matrix cores: the prompt in chunks of up to pf_rows tokens, every block
 // as MFMA GEMMs over the chunk (see river_prefill.h); blocks above ep run as river twins.
-static int prefill_gemm(river_ctx *x, const int32_t *tokens, int n, int ep) {
+static int prefill_gemm(river_ctx *x, int seq, const int32_t *tokens, int n, int ep) {
   const river_config &c = x->cfg;
   const Dev &D = x->dev;
   const Layout &y = x->lay;
@@ -840,6 +874,7 @@ static int prefill_gemm(river_ctx *x, const int32_t *tokens, int n, int ep) {
   _Float16 *x16 = (_Float16 *)(x->ws + y.pf_x16), *q16 = (_Float16 *)(x->ws + y.pf_q16);
   _Float16 *a16 = (_Float16 *)(x->ws + y.pf_a16);
   const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
+  char *kc = (char *)D.kcache + (size_t)seq * y.cache_bytes, *vc = (char *)D.vcache + (size_t)seq * y.cache_bytes;
   for (int c0 = 0; c0 < n; c0 += y.pf_rows) {
     const int m = std::min(y.pf_rows, n - c0), rows = (m + 127) / 128 * 128;
     const bool last = c0 + m == n;
@@ -853,13 +888,13 @@ static int prefill_gemm(river_ctx *x, const int32_t *tokens, int n, int ep) {
       if (river) launch_gemm<true, false>(x, l, m_qkv, 3, x16, d, big, rows);
       else launch_gemm<false, false>(x, l, m_qkv, 3, x16, d, big, rows);
       pf::k_pf_rope_store<<<dim3(m), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, c0, l,
-                                                        c.max_seq, D.kcache, D.vcache, q16);
+                                                        c.max_seq, kc, vc, q16);
       const dim3 ga(c.n_q_heads, (m + 127) / 128);
       if (c.head_dim == 128)
-        pf::k_pf_attn<128><<<ga, dim3(256), 0, s>>>(q16, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
+        pf::k_pf_attn<128><<<ga, dim3(256), 0, s>>>(q16, kc, vc, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
                                                     c0, m, x16);
       else
-        pf::k_pf_attn<64><<<ga, dim3(256), 0, s>>>(q16, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
+        pf::k_pf_attn<64><<<ga, dim3(256), 0, s>>>(q16, kc, vc, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
                                                    c0, m, x16);
       if (river) launch_gemm<true, true>(x, l, m_o, 1, x16, qd, h, rows);
       else launch_gemm<false, true>(x, l, m_o, 1, x16, qd, h, rows);
@@ -878,15 +913,21 @@ static int prefill_gemm(river_ctx *x, const int32_t *tokens, int n, int ep) {
   StepArgs A{};
   A.pos = n - 1; A.token = -1; A.forced_e = ep; A.want_head = 1; A.rec_slot = -1; A.n_splits = 1; A.bar_base = 0;
   k_head<1><<<dim3(x->grid_gemv), dim3(x->block), x->lds_bytes, s>>>(x->dev_d, A);
+  if (c.max_batch > 1)
+    bd::k_bd_after_prefill<<<dim3(1), dim3(64), 0, s>>>(x->st_b, seq, &D.st->cur_token, n);
   HIP_TRY(x, hipGetLastError());
-  x->pos = n;
+  if (c.max_batch > 1) x->pos_b[seq] = n;
+  else x->pos = n;
   return RIVER_OK;
 }
 
 extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, int32_t n_tokens,
                              int32_t prefill_exit_layer, int32_t *out_token, float *out_logits) {
   if (!x) return RIVER_EINVAL;
-  if (seq != 0 || !tokens || n_tokens < 1) { x->err = "bad prefill arguments"; return RIVER_EINVAL; }
+  if (seq < 0 || seq >= x->cfg.max_batch || !tokens || n_tokens < 1) {
+    x->err = "bad prefill arguments";
+    return RIVER_EINVAL;
+  }
   if (n_tokens > x->cfg.max_seq) { x->err = "prompt longer than max_seq"; return RIVER_ENOSPC; }
   for (int i = 0; i < n_tokens; ++i)
     if (tokens[i] < 0 || tokens[i] >= x->cfg.vocab) { x->err = "token id out of range"; return RIVER_EINVAL; }
@@ -904,8 +945,8 @@ extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, i
   x->pos = 0;
   x->have_token = false;
   const int min_gemm = x->cfg.prefill_gemm_min_tokens > 0 ? x->cfg.prefill_gemm_min_tokens : 32;
-  if (x->lay.pf_rows > 0 && n_tokens >= min_gemm) {
-    rc = prefill_gemm(x, tokens, n_tokens, ep);
+  if (x->lay.pf_rows > 0 && (n_tokens >= min_gemm || x->cfg.max_batch > 1)) {
+    rc = prefill_gemm(x, seq, tokens, n_tokens, ep);
     if (rc) return rc;
   } else {
     // short prompts, fp32 models and shapes the GEMM path does not take: the decode kernels,
@@ -932,6 +973,7 @@ extern "C" int river_prefill(river_ctx *x, int32_t seq, const int32_t *tokens, i
 extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const int32_t *forced_exit,
                                  int32_t *out_token, int32_t *out_exit_layer, float *out_sims) {
   CHECK_CTX(x);
+  if (x->cfg.max_batch > 1) { x->err = "a batched context decodes with river_decode_batch"; return RIVER_ESTATE; }
   if (!x->have_token && !in_token) { x->err = "decode before prefill"; return RIVER_ESTATE; }
   if (x->pos < 1) { x->err = "decode before prefill"; return RIVER_ESTATE; }
   if (x->pos >= x->cfg.max_seq) { x->err = "KV cache full"; return RIVER_ENOSPC; }
@@ -968,6 +1010,145 @@ extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const in
   return check_device_error(x);
 }
 
+// GEMM of a batched decode step over the stacked matrices ms[0..nm) of block l, for the rows whose
+// river flag equals `want` (see bd::k_bd_gemm).
+template <bool W4, bool ADD>
+static void launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, const _Float16 *A, int K, float *C, int want,
+                           int n) {
+  pf::GemmB B{};
+  int N = 0;
+  for (int i = 0; i < nm; ++i) {
+    long long r, c;
+    matrix_shape(&x->cfg, ms[i], &r, &c);
+    B.w[i] = W4 ? (const void *)x->layers_h[l].qc[ms[i]] : x->layers_h[l].w[ms[i]];
+    B.sz[i] = x->layers_h[l].qsz[ms[i]];
+    B.rows[i] = (int)r;
+    N += (int)r;
+  }
+  for (int i = nm; i < 3; ++i) { B.w[i] = B.w[0]; B.sz[i] = B.sz[0]; B.rows[i] = 0; }
+  bd::k_bd_gemm<W4, ADD><<<dim3((N + 31) / 32), dim3(256), 0, x->stream>>>(A, K, B, N, K, x->cfg.river_group, C, N,
+                                                                          x->st_b.river, want, n);
+}
+
+extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in_tokens, const int32_t *forced_exit,
+                                  int32_t *out_tokens, int32_t *out_exit_layers, float *out_sims) {
+  CHECK_CTX(x);
+  const river_config &c = x->cfg;
+  if (c.max_batch < 2) { x->err = "river_decode_batch needs a context created with max_batch > 1"; return RIVER_ESTATE; }
+  if (n_seq < 1 || n_seq > c.max_batch) { x->err = "n_seq outside [1, max_batch]"; return RIVER_EINVAL; }
+  if (!out_tokens && (out_exit_layers || out_sims)) {
+    x->err = "out_tokens is NULL but other outputs are not";
+    return RIVER_EINVAL;
+  }
+  const int L = c.n_layers, n = n_seq;
+  std::vector<int32_t> fe(n, -1);
+  for (int b = 0; b < n; ++b) {
+    if (x->pos_b[b] < 1) { x->err = "decode before prefill of every sequence"; return RIVER_ESTATE; }
+    if (x->pos_b[b] >= c.max_seq) { x->err = "KV cache full"; return RIVER_ENOSPC; }
+    if (in_tokens && (in_tokens[b] < 0 || in_tokens[b] >= c.vocab)) { x->err = "token id out of range"; return RIVER_EINVAL; }
+    if (forced_exit) {
+      fe[b] = forced_exit[b];
+      const bool ok = fe[b] < 0 || fe[b] == L || (fe[b] >= c.min_exit_layer && fe[b] <= L);
+      if (!ok) { x->err = "forced exit position outside [L_s, L]"; return RIVER_EINVAL; }
+    }
+    if (((fe[b] >= 0 && fe[b] < L) || (fe[b] < 0 && c.tau < 1.0f)) && !x->have_river) {
+      x->err = "an exit is possible but no river weights were given";
+      return RIVER_ESTATE;
+    }
+  }
+  const Dev &D = x->dev;
+  const Layout &y = x->lay;
+  hipStream_t s = x->stream;
+  const int d = c.d_model, qd = c.n_q_heads * c.head_dim, ffn = c.d_ffn;
+  float *h = (float *)(x->ws + y.pf_h), *big = (float *)(x->ws + y.pf_big);
+  float *hprev = (float *)(x->ws + y.bd_hprev), *qf = (float *)(x->ws + y.bd_qf);
+  float *logits = (float *)(x->ws + y.bd_logits), *hist = (float *)(x->ws + y.bd_hist);
+  _Float16 *x16 = (_Float16 *)(x->ws + y.pf_x16), *o16 = (_Float16 *)(x->ws + y.pf_q16);
+  _Float16 *a16 = (_Float16 *)(x->ws + y.pf_a16);
+  const int slot = (int)(x->steps_b % bd::kRecordsB);
+  const size_t B = c.max_batch;
+  int *rec_token = (int *)(x->ws + y.bd_rec_token) + (size_t)slot * B;
+  int *rec_exit = (int *)(x->ws + y.bd_rec_exit) + (size_t)slot * B;
+  float *rec_sims = (float *)(x->ws + y.bd_rec_sims) + (size_t)slot * B * L;
+  const bd::SeqState st = x->st_b;
+  float *s_of = (float *)(st.forced + B);                    // [max_batch] similarities of the current block
+  HIP_TRY(x, hipMemcpyAsync(st.forced, fe.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
+  if (in_tokens) HIP_TRY(x, hipMemcpyAsync(st.token, in_tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
+  bd::k_bd_fill_nan<<<dim3((n * L + 255) / 256), dim3(256), 0, s>>>(rec_sims, n * L);
+  bd::k_bd_embed<<<dim3(n), dim3(256), 0, s>>>(st, D.tok_emb, d, c.vocab, L, h, hprev, hist);
+  const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
+  const bool rv = x->have_river;
+  const size_t seq_stride = y.cache_bytes / 2;               // elements (bf16)
+  const size_t attn_lds = bd::attn_lds_bytes(c.max_seq);
+  for (int l = 0; l < L; ++l) {
+    const DevLayer &W = x->layers_h[l];
+    pf::k_pf_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
+    launch_bd_gemm<false, false>(x, l, m_qkv, 3, x16, d, big, 0, n);
+    if (rv && W.qc[M_WQ]) launch_bd_gemm<true, false>(x, l, m_qkv, 3, x16, d, big, 1, n);
+    bd::k_bd_rope_store<<<dim3(n), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, st.pos, l,
+                                                      c.max_seq, seq_stride, D.kcache, D.vcache, qf);
+    const dim3 ga(c.n_q_heads, n);
+    if (c.head_dim == 128)
+      bd::k_bd_attn<128><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l,
+                                                         c.max_seq, seq_stride, st.pos, o16);
+    else
+      bd::k_bd_attn<64><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l,
+                                                        c.max_seq, seq_stride, st.pos, o16);
+    launch_bd_gemm<false, true>(x, l, m_o, 1, o16, qd, h, 0, n);
+    if (rv && W.qc[M_WO]) launch_bd_gemm<true, true>(x, l, m_o, 1, o16, qd, h, 1, n);
+    pf::k_pf_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);
+    launch_bd_gemm<false, false>(x, l, m_gu, 2, x16, d, big, 0, n);
+    if (rv && W.qc[M_GATE]) launch_bd_gemm<true, false>(x, l, m_gu, 2, x16, d, big, 1, n);
+    pf::k_pf_swiglu<<<dim3(n), dim3(256), 0, s>>>(big, ffn, a16);
+    launch_bd_gemm<false, true>(x, l, m_d, 1, a16, ffn, h, 0, n);
+    if (rv && W.qc[M_DOWN]) launch_bd_gemm<true, true>(x, l, m_d, 1, a16, ffn, h, 1, n);
+    bd::k_bd_sim<<<dim3(n), dim3(256), 0, s>>>(hprev, h, d, l + 1, L, st, s_of, rec_sims,
+                                               hist + (size_t)(l + 1) * B * d);
+    if (l + 1 >= c.min_exit_layer && l + 1 < L)
+      bd::k_bd_decide<<<dim3(1), dim3(64), 0, s>>>(n, l + 1, L, c.min_exit_layer, c.tau, c.batch_exit_rule, st, s_of);
+  }
+  // the original final norm + LM head, greedy token per sequence
+  pf::k_pf_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, D.final_norm, d, c.rms_eps, x16);
+  {
+    pf::GemmB Bh{};
+    Bh.w[0] = Bh.w[1] = Bh.w[2] = D.lm_head;
+    Bh.rows[0] = c.vocab;
+    bd::k_bd_gemm<false, false><<<dim3((c.vocab + 31) / 32), dim3(256), 0, s>>>(x16, d, Bh, c.vocab, d, c.river_group,
+                                                                              logits, c.vocab, st.river, -1, n);
+  }
+  bd::k_bd_argmax<<<dim3(n), dim3(256), 0, s>>>(logits, c.vocab, st, rec_token, rec_exit);
+  HIP_TRY(x, hipGetLastError());
+  for (int b = 0; b < n; ++b) x->pos_b[b] += 1;
+  x->steps_b += 1;
+  x->last_n = n;
+  if (!out_tokens) return RIVER_OK;
+  HIP_TRY(x, hipMemcpyAsync(out_tokens, rec_token, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+  if (out_exit_layers) HIP_TRY(x, hipMemcpyAsync(out_exit_layers, rec_exit, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+  if (out_sims) HIP_TRY(x, hipMemcpyAsync(out_sims, rec_sims, (size_t)n * L * 4, hipMemcpyDeviceToHost, s));
+  HIP_TRY(x, hipStreamSynchronize(s));
+  return RIVER_OK;
+}
+
+extern "C" int river_read_batch_records(river_ctx *x, int32_t n_steps, int32_t n_seq, int32_t *tokens,
+                                        int32_t *exit_layers) {
+  CHECK_CTX(x);
+  if (x->cfg.max_batch < 2 || n_steps < 0 || n_steps > bd::kRecordsB || n_steps > x->steps_b || n_seq < 1 ||
+      n_seq > x->cfg.max_batch || (n_steps > 0 && (!tokens || !exit_layers))) {
+    x->err = "bad batch record request";
+    return RIVER_EINVAL;
+  }
+  const size_t B = x->cfg.max_batch;
+  for (int i = 0; i < n_steps; ++i) {
+    const size_t slot = (size_t)((x->steps_b - n_steps + i) % bd::kRecordsB);
+    HIP_TRY(x, hipMemcpyAsync(tokens + (size_t)i * n_seq, (int *)(x->ws + x->lay.bd_rec_token) + slot * B,
+                              (size_t)n_seq * 4, hipMemcpyDeviceToHost, x->stream));
+    HIP_TRY(x, hipMemcpyAsync(exit_layers + (size_t)i * n_seq, (int *)(x->ws + x->lay.bd_rec_exit) + slot * B,
+                              (size_t)n_seq * 4, hipMemcpyDeviceToHost, x->stream));
+  }
+  HIP_TRY(x, hipStreamSynchronize(x->stream));
+  return RIVER_OK;
+}
+
 extern "C" int river_read_records(river_ctx *x, int32_t n, int32_t *tokens, int32_t *exit_layers,
                                   float *sims) {
   CHECK_CTX(x);
@@ -992,12 +1173,26 @@ extern "C" int river_read_records(river_ctx *x, int32_t n, int32_t *tokens, int3
 
 extern "C" int river_rewind(river_ctx *x, int32_t seq, int32_t new_len) {
   CHECK_CTX(x);
+  if (x->cfg.max_batch > 1) {
+    if (seq < 0 || seq >= x->cfg.max_batch || new_len < 0 || new_len > x->pos_b[seq]) {
+      x->err = "bad rewind length";
+      return RIVER_EINVAL;
+    }
+    x->pos_b[seq] = new_len;
+    HIP_TRY(x, hipMemcpyAsync(x->st_b.pos + seq, &x->pos_b[seq], 4, hipMemcpyHostToDevice, x->stream));
+    HIP_TRY(x, hipStreamSynchronize(x->stream));
+    return RIVER_OK;
+  }
   if (seq != 0 || new_len < 0 || new_len > x->pos) { x->err = "bad rewind length"; return RIVER_EINVAL; }
   x->pos = new_len;
   return RIVER_OK;
 }
 
 extern "C" int river_position(const river_ctx *x) { return x ? x->pos : RIVER_EINVAL; }
+extern "C" int river_seq_position(const river_ctx *x, int32_t seq) {
+  if (!x || seq < 0 || seq >= x->cfg.max_batch) return RIVER_EINVAL;
+  return x->cfg.max_batch > 1 ? x->pos_b[seq] : x->pos;
+}
 
 extern "C" int river_get_debug(river_ctx *x, int32_t what, void *dst, size_t bytes) {
   if (!x || !dst) return RIVER_EINVAL;
@@ -1006,8 +1201,18 @@ extern "C" int river_get_debug(river_ctx *x, int32_t what, void *dst, size_t byt
   switch (what) {
     case RIVER_DBG_HIDDEN: src = (const char *)x->dev.hidden; n = (size_t)(x->cfg.n_layers + 1) * x->cfg.d_model * 4; break;
     case RIVER_DBG_LOGITS: src = (const char *)x->dev.logits; n = (size_t)x->cfg.vocab * 4; break;
-    case RIVER_DBG_KCACHE: src = (const char *)x->dev.kcache; n = x->lay.cache_bytes; break;
-    case RIVER_DBG_VCACHE: src = (const char *)x->dev.vcache; n = x->lay.cache_bytes; break;
+    case RIVER_DBG_KCACHE: src = (const char *)x->dev.kcache; n = x->lay.cache_bytes * x->cfg.max_batch; break;
+    case RIVER_DBG_VCACHE: src = (const char *)x->dev.vcache; n = x->lay.cache_bytes * x->cfg.max_batch; break;
+    case RIVER_DBG_BATCH_HIDDEN:
+      if (x->cfg.max_batch < 2) { x->err = "not a batched context"; return RIVER_EINVAL; }
+      src = x->ws + x->lay.bd_hist;
+      n = (size_t)(x->cfg.n_layers + 1) * x->cfg.max_batch * x->cfg.d_model * 4;
+      break;
+    case RIVER_DBG_BATCH_LOGITS:
+      if (x->cfg.max_batch < 2) { x->err = "not a batched context"; return RIVER_EINVAL; }
+      src = x->ws + x->lay.bd_logits;
+      n = (size_t)x->cfg.max_batch * x->cfg.vocab * 4;
+      break;
     case RIVER_DBG_TRACE: src = (const char *)x->dev.trace; n = ((size_t)5 * x->cfg.n_layers * 2 * x->grid_persist + 64) * 8; break;
     default: x->err = "unknown debug buffer"; return RIVER_EINVAL;
   }
@@ -1021,7 +1226,7 @@ extern "C" int river_fill_cache(river_ctx *x, int32_t value) {
   CHECK_CTX(x);
   const uint32_t b = (uint32_t)value & 0xffu;
   const uint32_t word = b | (b << 8) | (b << 16) | (b << 24);
-  const size_t n16 = 2 * align_up(x->lay.cache_bytes, 256) / 16;
+  const size_t n16 = (x->lay.vcache - x->lay.kcache + align_up(x->lay.cache_bytes * x->cfg.max_batch, 256)) / 16;
   k_fill_bytes<<<dim3(1024), dim3(256), 0, x->stream>>>((uint4 *)x->dev.kcache, n16, word);
   HIP_TRY(x, hipGetLastError());
   return RIVER_OK;

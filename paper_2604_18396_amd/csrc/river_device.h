@@ -739,7 +739,10 @@ __device__ __forceinline__ int fresh_lane() {
   asm volatile("" : "+v"(t));
   return t;
 }
-constexpr int kSets = 2;          // register sets of the streaming pipeline (a third one only delayed the phases)
+#ifndef RIVER_SETS
+#define RIVER_SETS 2
+#endif
+constexpr int kSets = RIVER_SETS;  // register sets of the streaming pipeline (a third one only delayed the phases)
 template <int DT> struct Pre {
   Regs<DT> set[kSets];
   float rh[2], r1[2];      // residual inputs of this wavefront's first two tasks (O, down phases)

@@ -415,4 +415,371 @@ __global__ __launch_bounds__(256) void k_pf_attn(const _Float16 *__restrict__ q1
 }
 
 }  // namespace pf
+
+// =====================================================================================
+// Batched decode step (several sequences, each at its own position and exit depth)
+// =====================================================================================
+//
+// One decode step for n sequences: every block runs once for the rows (sequences) still in
+// the backbone and once for the rows that have left it, as two GEMMs over the same 32-row
+// activation tile -- bf16 backbone matrices and the 4-bit river twins -- each touching only
+// its own rows and returning at once when it has none (so a block whose rows all sit on one
+// side reads one weight set).  With depths drawn independently per sequence most blocks read
+// both sets: the reason Eq. 1 takes the minimum over the batch.  Which side a row is on is
+// decided on the device after every backbone block (k_bd_exit), per sequence or by Eq. 1's
+// batch rule; the host never waits inside a step.
+namespace bd {
+
+using namespace pf;
+
+constexpr int kRows = 32;             // rows of the activation tile (sequences per step, padded)
+constexpr int kRecordsB = 1024;       // ring of per-step records of a batched context
+
+struct SeqState {                     // device-side state of the sequences, [max_batch] each
+  int *pos;                           // positions in the cache = position the next token is written to
+  int *token;                         // token to consume next (produced by the last step / prefill)
+  int *river;                         // 1: the sequence has left the backbone in the current step
+  int *exit_pos;                      // exit position of the current step
+  int *forced;                        // forced exit position of the current step (< 0: Eq. 1 decides)
+};
+
+// C[rows, N] (+)= A[rows, K] B^T for the rows r < n_rows with river[r] == want (want < 0: all
+// rows); nothing is read if there is none.  Workgroup = four wavefronts on one 32 x 32 tile of C, each wavefront
+// taking every fourth 64-column K tile through its own LDS buffers; the four partial tiles
+// are summed in wavefront order.  N / 32 workgroups keep every CU streaming weights.
+template <bool W4, bool ADD>
+__global__ __launch_bounds__(256) void k_bd_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int N, int K,
+                                                 int group, float *C, int ldc, const int *__restrict__ river,
+                                                 int want, int n_rows) {
+  __shared__ __attribute__((aligned(16))) _Float16 As[4][kRows * LDK];
+  __shared__ __attribute__((aligned(16))) _Float16 Bs[4][32 * LDK];
+  __shared__ int any;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid == 0) any = 0;
+  __syncthreads();
+  if (tid < n_rows && (want < 0 || river[tid] == want)) any = 1;
+  __syncthreads();
+  if (!any) return;
+  const int n0 = blockIdx.x * 32;
+  const char *a_src[4];
+  int a_dst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int seg = lane + 64 * i, row = seg >> 3, ks = seg & 7;
+    a_src[i] = (const char *)(A + (size_t)row * lda + ks * 8);
+    a_dst[i] = row * LDK + ks * 8;
+  }
+  const char *b_src[W4 ? 1 : 4];
+  const char *b_sz = nullptr;
+  int b_dst[W4 ? 1 : 4];
+  if constexpr (W4) {
+    const int row = lane >> 1, hf = lane & 1;
+    int mat, r;
+    gemm_b_row(B, n0 + row, N, mat, r);
+    b_src[0] = (const char *)B.w[mat] + (size_t)r * (K >> 1) + hf * 16;
+    b_sz = (const char *)B.sz[mat] + (size_t)r * (K / group) * 4;
+    b_dst[0] = row * LDK + hf * 32;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int seg = lane + 64 * i, row = seg >> 3, ks = seg & 7;
+      int mat, r;
+      gemm_b_row(B, n0 + row, N, mat, r);
+      b_src[i] = (const char *)B.w[mat] + ((size_t)r * K + ks * 8) * 2;
+      b_dst[i] = row * LDK + ks * 8;
+    }
+  }
+  // Two K tiles of this wavefront are in flight in registers while a third is multiplied from
+  // its LDS buffers.  The buffers are private to the wavefront, so no workgroup barrier is
+  // needed inside the loop: a wavefront-scope fence orders its own LDS writes and reads.
+  struct Tile { uint4 a[4], b[W4 ? 1 : 4]; uint32_t sz; };
+  Tile t0, t1;
+  auto load = [&](int kt, Tile &t) {
+    const int k0 = kt * TK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t.a[i] = *(const uint4 *)(a_src[i] + (size_t)k0 * 2);
+    if constexpr (W4) {
+      t.b[0] = ld_stream16(b_src[0] + (k0 >> 1));
+      t.sz = *(const uint32_t *)(b_sz + (size_t)(k0 / group) * 4);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) t.b[i] = ld_stream16(b_src[i] + (size_t)k0 * 2);
+      t.sz = 0;
+    }
+  };
+  _Float16 *as = As[wv], *bs = Bs[wv];
+  auto stage = [&](const Tile &t) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *(uint4 *)(as + a_dst[i]) = t.a[i];
+    if constexpr (W4) {
+      const float sc = bf16_lo(t.sz), z = bf16_hi(t.sz);
+      const uint32_t wds[4] = {t.b[0].x, t.b[0].y, t.b[0].z, t.b[0].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        half8 h;
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb) {
+          const uint32_t byte = (wds[w] >> (8 * bb)) & 0xffu;
+          h[2 * bb] = (_Float16)(((float)(byte & 15u) - z) * sc);
+          h[2 * bb + 1] = (_Float16)(((float)(byte >> 4) - z) * sc);
+        }
+        *(half8 *)(bs + b_dst[0] + w * 8) = h;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *(half8 *)(bs + b_dst[i]) = bf16x8_to_half8(t.b[i]);
+    }
+  };
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const int nk = K / TK;
+  const int r32 = lane & 31, g8 = (lane >> 5) * 8;
+  auto wave_fence = [] {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  auto multiply = [&]() {
+#pragma unroll
+    for (int ks = 0; ks < TK / 16; ++ks) {
+      const half8 a = *(const half8 *)(as + r32 * LDK + ks * 16 + g8);
+      const half8 b = *(const half8 *)(bs + r32 * LDK + ks * 16 + g8);
+      acc = mfma16(a, b, acc);
+    }
+  };
+  // tiles of this wavefront: wv, wv + 4, wv + 8, ...
+  if (wv < nk) load(wv, t0);
+  if (wv + 4 < nk) load(wv + 4, t1);
+  for (int kt = wv; kt < nk; kt += 8) {
+    stage(t0);
+    wave_fence();
+    if (kt + 8 < nk) load(kt + 8, t0);
+    multiply();
+    wave_fence();
+    if (kt + 4 < nk) {
+      stage(t1);
+      wave_fence();
+      if (kt + 12 < nk) load(kt + 12, t1);
+      multiply();
+      wave_fence();
+    }
+  }
+  __syncthreads();
+  float *red = (float *)&As[0][0];                       // [4][32][32] floats = 16 KiB (As holds 18 KiB)
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[(wv * 32 + c_row(r, lane)) * 32 + r32] = acc[r];
+  __syncthreads();
+  for (int e = tid; e < 32 * 32; e += 256) {
+    const int row = e >> 5, col = n0 + (e & 31);
+    if (row < n_rows && col < N && (want < 0 || river[row] == want)) {
+      const float v = ((red[e] + red[1024 + e]) + red[2048 + e]) + red[3072 + e];
+      float *p = C + (size_t)row * ldc + col;
+      if constexpr (ADD) *p += v;
+      else *p = v;
+    }
+  }
+}
+
+// h[b, :] = E[token[b], :] (also h_prev and the debug view of h(0)); start-of-step state of
+// sequence b (forced exit position 0 puts it into the river from the first block on)
+__global__ void k_bd_embed(SeqState st, const void *tok_emb, int d, int vocab, int L, float *h, float *h_prev,
+                           float *hist) {
+  const int b = blockIdx.x;
+  const int tok = min(max(st.token[b], 0), vocab - 1);
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const float v = Store<1>::ld(tok_emb, (size_t)tok * d + i);
+    h[(size_t)b * d + i] = v;
+    h_prev[(size_t)b * d + i] = v;
+    hist[(size_t)b * d + i] = v;
+  }
+  if (threadIdx.x == 0) {
+    const bool r0 = st.forced[b] == 0;
+    st.river[b] = r0 ? 1 : 0;
+    st.exit_pos[b] = r0 ? 0 : L;
+  }
+}
+
+__global__ void k_bd_copy(const float *__restrict__ src, float *dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+// RoPE at each sequence's own position; q (scaled by log2(e)/sqrt(hd)) to qf (fp32), k and v
+// rounded to the cache dtype into slot (seq b, block l, pos[b]) of the shared cache.
+__global__ void k_bd_rope_store(const float *__restrict__ qkv, const float2 *__restrict__ rope, int nq, int nkv,
+                                int hd, const int *__restrict__ pos, int l, int max_seq, size_t seq_stride,
+                                void *kcache, void *vcache, float *qf) {
+  const int b = blockIdx.x, p = pos[b], half = hd >> 1;
+  const int qd = nq * hd, kvd = nkv * hd, ld = qd + 2 * kvd;
+  const float *row = qkv + (size_t)b * ld;
+  const float qs = 1.4426950408889634f / sqrtf((float)hd);
+  const size_t slot = (size_t)b * seq_stride + ((size_t)l * max_seq + p) * kvd;
+  for (int i = threadIdx.x; i < (nq + nkv) * half; i += blockDim.x) {
+    const int head = i / half, e = i % half;
+    const float2 cs = rope[(size_t)p * half + e];
+    const float *src = row + head * hd;
+    const float a = src[e], c = src[e + half];
+    const float lo = a * cs.x - c * cs.y, hi = a * cs.y + c * cs.x;
+    if (head < nq) {
+      qf[(size_t)b * qd + head * hd + e] = lo * qs;
+      qf[(size_t)b * qd + head * hd + e + half] = hi * qs;
+    } else {
+      Store<1>::st(kcache, slot + (size_t)(head - nq) * hd + e, lo);
+      Store<1>::st(kcache, slot + (size_t)(head - nq) * hd + e + half, hi);
+    }
+  }
+  for (int i = threadIdx.x; i < kvd; i += blockDim.x) Store<1>::st(vcache, slot + i, row[qd + kvd + i]);
+}
+
+// Single-query attention of sequence b = blockIdx.y, query head blockIdx.x, over its cache
+// positions 0 .. pos[b].  Sixteen lanes share a cached row (HD/16 elements each, one 16- or
+// 8-byte load), so a wavefront load covers four positions with whole rows; the workgroup's 16
+// lane groups stride over the positions.  Pass 1: scores (DPP row sums) to LDS and the block
+// maximum; pass 2: probabilities and their sum; pass 3: each lane group accumulates its
+// positions' value rows, the 16 partial vectors are summed in group order.
+// Dynamic LDS: attn_lds_bytes(max_seq).
+__host__ __device__ inline size_t attn_lds_bytes(int max_seq) { return ((size_t)max_seq + 32 + 16 * 128 + 32) * 4; }
+template <int HD>
+__global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, const void *kcache, const void *vcache,
+                                                 int nq, int nkv, int l, int max_seq, size_t seq_stride,
+                                                 const int *__restrict__ pos, _Float16 *o16) {
+  constexpr int EL = HD / 16;                                  // elements per lane of a cached row
+  extern __shared__ float sm[];
+  float *red = sm, *part = sm + 32, *sc = sm + 32 + 16 * 128;
+  const int b = blockIdx.y, h = blockIdx.x, kvh = h / (nq / nkv), tid = threadIdx.x;
+  const int grp = tid >> 4, dl = tid & 15;
+  const int T = pos[b] + 1, qd = nq * HD, kvd = nkv * HD;
+  const size_t base = (size_t)b * seq_stride + (size_t)l * max_seq * kvd + (size_t)kvh * HD + dl * EL;
+  float q[EL];
+#pragma unroll
+  for (int e = 0; e < EL; ++e) q[e] = qf[(size_t)b * qd + h * HD + dl * EL + e];
+  auto row = [&](const void *cache, int j, float (&f)[EL]) {
+    const char *p = (const char *)cache + (base + (size_t)j * kvd) * 2;
+    if constexpr (EL == 8) {
+      const uint4 w = *(const uint4 *)p;
+      f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x); f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
+      f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z); f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
+    } else {
+      const uint2 w = *(const uint2 *)p;
+      f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x); f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
+    }
+  };
+  float mx = -1.0e30f;
+  for (int j = grp; j < T; j += 16) {
+    float kf[EL];
+    row(kcache, j, kf);
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < EL; ++e) dot = fmaf(kf[e], q[e], dot);
+    dot = row16_sum(dot);
+    if (dl == 0) sc[j] = dot;
+    mx = fmaxf(mx, dot);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  __syncthreads();
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float ls = 0.f;
+  for (int j = tid; j < T; j += 256) {
+    const float p = __builtin_amdgcn_exp2f(sc[j] - mx);
+    sc[j] = p;
+    ls += p;
+  }
+  const float lsum = block_sum(ls, red + 8);                 // (its barriers also publish sc)
+  float acc[EL];
+#pragma unroll
+  for (int e = 0; e < EL; ++e) acc[e] = 0.f;
+  for (int j = grp; j < T; j += 16) {
+    float vf[EL];
+    row(vcache, j, vf);
+    const float p = sc[j];
+#pragma unroll
+    for (int e = 0; e < EL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+  }
+#pragma unroll
+  for (int e = 0; e < EL; ++e) part[grp * HD + dl * EL + e] = acc[e];
+  __syncthreads();
+  if (tid < HD) {
+    float o = part[tid];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) o += part[k * HD + tid];
+    o16[(size_t)b * qd + h * HD + tid] = (_Float16)(o / lsum);
+  }
+}
+
+// After block l1 (1-based), one workgroup per sequence b: s_b = cos(h_prev[b], h[b]) if the row
+// is still in the backbone (recorded, and kept in s_of for the decision); h(l1) of the row is
+// kept (hist, the debug view) and becomes the next block's h_prev.
+__global__ __launch_bounds__(256) void k_bd_sim(float *h_prev, const float *__restrict__ h, int d, int l1, int L,
+                                                SeqState st, float *s_of, float *sims /* [n][L] of this step */,
+                                                float *hist /* [n][d] */) {
+  __shared__ float red[32];
+  const int b = blockIdx.x;
+  const bool live = st.river[b] == 0;
+  float p3[3] = {0.f, 0.f, 0.f};
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const float a = h_prev[(size_t)b * d + i], c = h[(size_t)b * d + i];
+    p3[0] = fmaf(a, c, p3[0]); p3[1] = fmaf(a, a, p3[1]); p3[2] = fmaf(c, c, p3[2]);
+    h_prev[(size_t)b * d + i] = c;
+    hist[(size_t)b * d + i] = c;
+  }
+  if (!live) return;                                          // uniform per workgroup
+  block_sum_k<3>(p3, red);
+  float s = 0.f;
+  if (p3[1] > 0.f && p3[2] > 0.f) s = fminf(1.0f, fmaxf(-1.0f, p3[0] / (sqrtf(p3[1]) * sqrtf(p3[2]))));
+  if (threadIdx.x == 0) {
+    s_of[b] = s;
+    sims[(size_t)b * L + (l1 - 1)] = s;
+  }
+}
+
+// The exit decision after backbone block l1 from the similarities k_bd_sim left.  rule 0: every
+// sequence for itself (s_b > tau); rule 1: Eq. 1 as printed, the whole batch leaves together
+// once min_b s_b > tau.  A forced exit position overrides the threshold for its sequence.
+// First hit at or above L_s, never at L, strict '>'.  One wavefront.
+__global__ void k_bd_decide(int n, int l1, int L, int min_exit, float tau, int rule, SeqState st,
+                            const float *__restrict__ s_of) {
+  if (threadIdx.x != 0 || l1 < min_exit || l1 >= L) return;
+  bool all_pass = true;                                       // Eq. 1's minimum over the batch
+  for (int b = 0; b < n; ++b)
+    if (!st.river[b] && !(s_of[b] > tau)) all_pass = false;
+  for (int b = 0; b < n; ++b) {
+    if (st.river[b]) continue;
+    const int f = st.forced[b];
+    const bool go = f >= 0 ? f == l1 : (rule == 1 ? all_pass : s_of[b] > tau);
+    if (go) { st.river[b] = 1; st.exit_pos[b] = l1; }
+  }
+}
+
+// Greedy token of every sequence (lowest index on ties), its record, and the step's end:
+// the sequence advances by one position.  One workgroup per sequence.
+__global__ __launch_bounds__(256) void k_bd_argmax(const float *__restrict__ logits, int vocab, SeqState st,
+                                                   int *rec_token, int *rec_exit) {
+  __shared__ float red[64];
+  const int b = blockIdx.x;
+  float best = -INFINITY;
+  int besti = 0x7fffffff;
+  for (int i = threadIdx.x; i < vocab; i += blockDim.x) argmax_take(best, besti, logits[(size_t)b * vocab + i], i);
+  block_argmax(best, besti, red);
+  if (threadIdx.x == 0) {
+    st.token[b] = besti;
+    st.pos[b] += 1;
+    if (rec_token) { rec_token[b] = besti; rec_exit[b] = st.exit_pos[b]; }
+  }
+}
+
+// sims[b][l] = NaN for every block (blocks that run as river twins keep it)
+__global__ void k_bd_fill_nan(float *p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = __uint_as_float(0x7fc00000u);
+}
+
+// after a prefill of sequence `seq`: its next token and length
+__global__ void k_bd_after_prefill(SeqState st, int seq, const int *cur_token, int len) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { st.token[seq] = *cur_token; st.pos[seq] = len; }
+}
+
+}  // namespace bd
 }  // namespace river

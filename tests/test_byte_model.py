@@ -34,3 +34,15 @@ def test_step_bytes_decomposition():
     # ragged last group (C1's 688-column down projection has 11 groups per row)
     t = configs.TINY
     assert bm.block_bytes_river(t) > t.params_per_block // 2
+
+
+def test_batch_step_bytes_reduces_to_the_single_sequence_model():
+    from paper_2604_18396_amd import byte_model, configs
+    cfg = configs.LLAMA_8B
+    for e in (8, 18, 32):
+        assert byte_model.batch_step_bytes(cfg, [e], [700]) == byte_model.step_bytes(cfg, e, 700)
+    # two sequences at depths 10 and 20: blocks 1..10 backbone only, 11..20 both sets, 21..32 river only
+    b = byte_model.batch_step_bytes(cfg, [10, 20], [100, 200])
+    want = (20 * byte_model.block_bytes_backbone(cfg) + 22 * byte_model.block_bytes_river(cfg)
+            + byte_model.head_bytes(cfg) + byte_model.kv_bytes_per_position(cfg) * 300)
+    assert b == want

@@ -98,3 +98,57 @@ def test_1b_shape_whole_model():
     prompt = inputs.make_prompt(cfg.vocab, 64, configs.C2.seed_prompt)
     sched = inputs.make_exit_schedule(cfg.n_layers, 8, configs.C2.seed_exits)
     run(cfg, configs.C2.seed_weights, prompt, [int(e) for e in sched], "1B")
+
+
+def test_8b_shape_batch16_ragged_exits():
+    """The batched step at the 8B shape (two blocks, 16 sequences at ragged positions, exit
+    positions drawn independently per sequence): every sequence against its own oracle."""
+    from oracle import river_oracle as ro
+    cfg = configs.LLAMA_8B.with_(name="8b-2-blocks-batch", n_layers=2, min_exit_layer=0, max_seq=64)
+    t0 = time.time()
+    w = inputs.make_weights(cfg, configs.C5.seed_weights)
+    river = ro.quantize_river(cfg, w)
+    dw = binding.upload_weights(w)
+    dr = binding.quantize_river(cfg, dw)
+    say(f"batch16: weights and rivers {time.time() - t0:.1f}s")
+    g = binding.River(cfg, dw, dr, max_batch=16)
+    rng = np.random.default_rng(configs.C5.seed_exits)
+    os_, toks = [], []
+    t0 = time.time()
+    for b in range(16):
+        prompt = inputs.make_prompt(cfg.vocab, 4 + (5 * b) % 17, configs.C5.seed_prompt + b)
+        o = ro.Oracle(cfg, w, river)
+        to = o.prefill(prompt)
+        tg = g.prefill(prompt, seq=b)
+        if tg != to:
+            lo = o.logits()
+            assert (lo[to] - lo[tg]) / np.abs(lo).max() <= TOL
+            helpers.NEAR_TIES.append(f"batch16 prefill {b}: token {tg} vs oracle {to}")
+        os_.append(o); toks.append(to)
+    say(f"batch16: prefills {time.time() - t0:.1f}s")
+    for step in range(2):
+        t0 = time.time()
+        forced = [int(rng.integers(0, 3)) for _ in range(16)]
+        tg, eg, sg = g.decode_batch(16, toks, forced)
+        hg, lg = g.batch_hidden(), g.batch_logits()
+        assert list(eg) == forced
+        nxt = []
+        for b, o in enumerate(os_):
+            to, eo, so = o.decode_step(toks[b], forced[b])
+            ho = o.hidden()
+            eh = max(relerr(hg[l, b], ho[l]) for l in range(3))
+            el = relerr(lg[b], o.logits())
+            assert eh <= TOL and el <= TOL, f"batch16 step {step} sequence {b}: hidden {eh:.2e} logits {el:.2e}"
+            np.testing.assert_allclose(sg[b][:eo], so[:eo], atol=1e-3)
+            if int(tg[b]) != to:
+                lo = o.logits()
+                assert (lo[to] - lo[int(tg[b])]) / np.abs(lo).max() <= TOL
+                helpers.NEAR_TIES.append(f"batch16 step {step} sequence {b}: token {tg[b]} vs oracle {to}")
+            nxt.append(to)
+        toks = nxt
+        say(f"batch16: step {step} exits {forced} ok ({time.time() - t0:.1f}s)")
+    kg = g.kcache()
+    for b, o in enumerate(os_):
+        for l in range(2):
+            assert relerr(kg[b][l, :o.pos], o.kcache()[l, :o.pos]) <= TOL
+    g.close()
