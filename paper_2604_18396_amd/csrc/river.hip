@@ -1026,8 +1026,12 @@ static void launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, const _Fl
     N += (int)r;
   }
   for (int i = nm; i < 3; ++i) { B.w[i] = B.w[0]; B.sz[i] = B.sz[0]; B.rows[i] = 0; }
-  bd::k_bd_gemm<W4, ADD><<<dim3((N + 31) / 32), dim3(256), 0, x->stream>>>(A, K, B, N, K, x->cfg.river_group, C, N,
-                                                                          x->st_b.river, want, n);
+  if (n <= 16)
+    bd::k_bd_gemm<W4, ADD, 1><<<dim3((N + 15) / 16), dim3(256), 0, x->stream>>>(A, K, B, N, K, x->cfg.river_group, C,
+                                                                               N, x->st_b.river, want, n);
+  else
+    bd::k_bd_gemm<W4, ADD, 2><<<dim3((N + 15) / 16), dim3(256), 0, x->stream>>>(A, K, B, N, K, x->cfg.river_group, C,
+                                                                               N, x->st_b.river, want, n);
 }
 
 extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in_tokens, const int32_t *forced_exit,
@@ -1113,8 +1117,12 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
     pf::GemmB Bh{};
     Bh.w[0] = Bh.w[1] = Bh.w[2] = D.lm_head;
     Bh.rows[0] = c.vocab;
-    bd::k_bd_gemm<false, false><<<dim3((c.vocab + 31) / 32), dim3(256), 0, s>>>(x16, d, Bh, c.vocab, d, c.river_group,
-                                                                              logits, c.vocab, st.river, -1, n);
+    if (n <= 16)
+      bd::k_bd_gemm<false, false, 1><<<dim3((c.vocab + 15) / 16), dim3(256), 0, s>>>(
+          x16, d, Bh, c.vocab, d, c.river_group, logits, c.vocab, st.river, -1, n);
+    else
+      bd::k_bd_gemm<false, false, 2><<<dim3((c.vocab + 15) / 16), dim3(256), 0, s>>>(
+          x16, d, Bh, c.vocab, d, c.river_group, logits, c.vocab, st.river, -1, n);
   }
   bd::k_bd_argmax<<<dim3(n), dim3(256), 0, s>>>(logits, c.vocab, st, rec_token, rec_exit);
   HIP_TRY(x, hipGetLastError());

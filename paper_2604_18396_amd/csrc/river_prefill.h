@@ -432,7 +432,7 @@ namespace bd {
 
 using namespace pf;
 
-constexpr int kRows = 32;             // rows of the activation tile (sequences per step, padded)
+constexpr int kRows = 32;             // most sequences per step (rows of the activation tile)
 constexpr int kRecordsB = 1024;       // ring of per-step records of a batched context
 
 struct SeqState {                     // device-side state of the sequences, [max_batch] each
@@ -443,16 +443,51 @@ struct SeqState {                     // device-side state of the sequences, [ma
   int *forced;                        // forced exit position of the current step (< 0: Eq. 1 decides)
 };
 
+// v_mfma_f32_16x16x32_f16: D[16x16] += A[16x32] B[32x16].  Lane l supplies row l % 16 of A and
+// column l % 16 of B, the eight K values of lane group l / 16 each; D: register r of lane l is
+// row (l / 16) * 4 + r, column l % 16.
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4v mfma16x16(half8 a, half8 b, f32x4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Eight 4-bit codes of one 32-bit word (byte j = column 2j in the low nibble, 2j+1 in the high
+// nibble) -> eight fp16 weights (code - zero) * scale in column order.  A nibble n becomes the
+// half value 1024 + n by placing it in the mantissa of 1024.0; subtracting 1024 is exact, and
+// code * scale - zero * scale is one packed fma; -zero*scale is carried as a high and a low
+// half (nzh2, nzl2), so that its rounding does not add a common offset to a whole group.
+__device__ __forceinline__ half8 dequant8(uint32_t w, half2v sc2, half2v nzh2, half2v nzl2) {
+  const uint32_t lo4 = w & 0x0f0f0f0fu, hi4 = (w >> 4) & 0x0f0f0f0fu;
+  const half2v k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+  half8 out;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    // bytes of the pair: [lo4.byte j, 0, hi4.byte j, 0] (v_perm_b32: selector 0x0c gives 0x00;
+    // bytes 0-3 index the second operand, 4-7 the first)
+    const uint32_t sel = 0x0c000c00u | (uint32_t)j | ((uint32_t)(4 + j) << 16);
+    const uint32_t pr = __builtin_amdgcn_perm(hi4, lo4, sel) | 0x64006400u;
+    half2v q = __builtin_bit_cast(half2v, pr) - k1024;
+    q = (q * sc2 + nzh2) + nzl2;
+    out[2 * j] = q[0];
+    out[2 * j + 1] = q[1];
+  }
+  return out;
+}
+
 // C[rows, N] (+)= A[rows, K] B^T for the rows r < n_rows with river[r] == want (want < 0: all
-// rows); nothing is read if there is none.  Workgroup = four wavefronts on one 32 x 32 tile of C, each wavefront
-// taking every fourth 64-column K tile through its own LDS buffers; the four partial tiles
-// are summed in wavefront order.  N / 32 workgroups keep every CU streaming weights.
-template <bool W4, bool ADD>
+// rows); nothing is read if there is none.  MB = 1: up to 16 rows, MB = 2: up to 32.
+// Workgroup = four wavefronts on one (16 MB) x 16 tile of C, each wavefront taking every
+// fourth 64-column K tile through its own LDS buffers, four tiles in flight in registers; the
+// four partial tiles are summed in wavefront order.  N / 16 workgroups: at least one per CU
+// for every matrix of the 8B shape, so all CUs stream weights.
+template <bool W4, bool ADD, int MB>
 __global__ __launch_bounds__(256) void k_bd_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int N, int K,
                                                  int group, float *C, int ldc, const int *__restrict__ river,
                                                  int want, int n_rows) {
-  __shared__ __attribute__((aligned(16))) _Float16 As[4][kRows * LDK];
-  __shared__ __attribute__((aligned(16))) _Float16 Bs[4][32 * LDK];
+  constexpr int RM = 16 * MB;                                 // rows of the tile
+  constexpr int NT = 4;                                       // K tiles in flight per wavefront
+  __shared__ __attribute__((aligned(16))) _Float16 As[4][RM * LDK];
+  __shared__ __attribute__((aligned(16))) _Float16 Bs[4][16 * LDK];
   __shared__ int any;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   if (tid == 0) any = 0;
@@ -460,28 +495,31 @@ __global__ __launch_bounds__(256) void k_bd_gemm(const _Float16 *__restrict__ A,
   if (tid < n_rows && (want < 0 || river[tid] == want)) any = 1;
   __syncthreads();
   if (!any) return;
-  const int n0 = blockIdx.x * 32;
-  const char *a_src[4];
-  int a_dst[4];
+  const int n0 = blockIdx.x * 16;
+  // per K tile a lane stages 2 MB 16-byte segments of A and, of B, two 16-byte segments (dense)
+  // or one 8-byte run of 16 codes with the (scale, zero) pair of its row (river)
+  const char *a_src[2 * MB];
+  int a_dst[2 * MB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2 * MB; ++i) {
     const int seg = lane + 64 * i, row = seg >> 3, ks = seg & 7;
     a_src[i] = (const char *)(A + (size_t)row * lda + ks * 8);
     a_dst[i] = row * LDK + ks * 8;
   }
-  const char *b_src[W4 ? 1 : 4];
+  const char *b_src[2];
   const char *b_sz = nullptr;
-  int b_dst[W4 ? 1 : 4];
+  int b_dst[2];
   if constexpr (W4) {
-    const int row = lane >> 1, hf = lane & 1;
+    const int row = lane >> 2, qt = lane & 3;
     int mat, r;
     gemm_b_row(B, n0 + row, N, mat, r);
-    b_src[0] = (const char *)B.w[mat] + (size_t)r * (K >> 1) + hf * 16;
+    b_src[0] = (const char *)B.w[mat] + (size_t)r * (K >> 1) + qt * 8;
     b_sz = (const char *)B.sz[mat] + (size_t)r * (K / group) * 4;
-    b_dst[0] = row * LDK + hf * 32;
+    b_dst[0] = row * LDK + qt * 16;
+    b_src[1] = nullptr; b_dst[1] = 0;
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2; ++i) {
       const int seg = lane + 64 * i, row = seg >> 3, ks = seg & 7;
       int mat, r;
       gemm_b_row(B, n0 + row, N, mat, r);
@@ -489,90 +527,80 @@ __global__ __launch_bounds__(256) void k_bd_gemm(const _Float16 *__restrict__ A,
       b_dst[i] = row * LDK + ks * 8;
     }
   }
-  // Two K tiles of this wavefront are in flight in registers while a third is multiplied from
-  // its LDS buffers.  The buffers are private to the wavefront, so no workgroup barrier is
-  // needed inside the loop: a wavefront-scope fence orders its own LDS writes and reads.
-  struct Tile { uint4 a[4], b[W4 ? 1 : 4]; uint32_t sz; };
-  Tile t0, t1;
+  struct Tile { uint4 a[2 * MB], b[2]; uint32_t sz; };
   auto load = [&](int kt, Tile &t) {
     const int k0 = kt * TK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) t.a[i] = *(const uint4 *)(a_src[i] + (size_t)k0 * 2);
+    for (int i = 0; i < 2 * MB; ++i) t.a[i] = *(const uint4 *)(a_src[i] + (size_t)k0 * 2);
     if constexpr (W4) {
-      t.b[0] = ld_stream16(b_src[0] + (k0 >> 1));
+      t.b[0] = ld_stream8(b_src[0] + (k0 >> 1));
       t.sz = *(const uint32_t *)(b_sz + (size_t)(k0 / group) * 4);
     } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) t.b[i] = ld_stream16(b_src[i] + (size_t)k0 * 2);
+      for (int i = 0; i < 2; ++i) t.b[i] = ld_stream16(b_src[i] + (size_t)k0 * 2);
       t.sz = 0;
     }
   };
   _Float16 *as = As[wv], *bs = Bs[wv];
   auto stage = [&](const Tile &t) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(uint4 *)(as + a_dst[i]) = t.a[i];
+    for (int i = 0; i < 2 * MB; ++i) *(uint4 *)(as + a_dst[i]) = t.a[i];
     if constexpr (W4) {
-      const float sc = bf16_lo(t.sz), z = bf16_hi(t.sz);
-      const uint32_t wds[4] = {t.b[0].x, t.b[0].y, t.b[0].z, t.b[0].w};
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        half8 h;
-#pragma unroll
-        for (int bb = 0; bb < 4; ++bb) {
-          const uint32_t byte = (wds[w] >> (8 * bb)) & 0xffu;
-          h[2 * bb] = (_Float16)(((float)(byte & 15u) - z) * sc);
-          h[2 * bb + 1] = (_Float16)(((float)(byte >> 4) - z) * sc);
-        }
-        *(half8 *)(bs + b_dst[0] + w * 8) = h;
-      }
+      const float nz = -bf16_hi(t.sz) * bf16_lo(t.sz);
+      const _Float16 sc = (_Float16)bf16_lo(t.sz), nzh = (_Float16)nz, nzl = (_Float16)(nz - (float)nzh);
+      const half2v sc2 = {sc, sc}, nzh2 = {nzh, nzh}, nzl2 = {nzl, nzl};
+      *(half8 *)(bs + b_dst[0]) = dequant8(t.b[0].x, sc2, nzh2, nzl2);
+      *(half8 *)(bs + b_dst[0] + 8) = dequant8(t.b[0].y, sc2, nzh2, nzl2);
     } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) *(half8 *)(bs + b_dst[i]) = bf16x8_to_half8(t.b[i]);
+      for (int i = 0; i < 2; ++i) *(half8 *)(bs + b_dst[i]) = bf16x8_to_half8(t.b[i]);
     }
   };
-  f32x16 acc;
+  f32x4v acc[MB];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int i = 0; i < MB; ++i) acc[i] = f32x4v{0.f, 0.f, 0.f, 0.f};
   const int nk = K / TK;
-  const int r32 = lane & 31, g8 = (lane >> 5) * 8;
+  const int r16 = lane & 15, g8 = (lane >> 4) * 8;
   auto wave_fence = [] {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
   };
-  auto multiply = [&]() {
+  Tile t[NT];
 #pragma unroll
-    for (int ks = 0; ks < TK / 16; ++ks) {
-      const half8 a = *(const half8 *)(as + r32 * LDK + ks * 16 + g8);
-      const half8 b = *(const half8 *)(bs + r32 * LDK + ks * 16 + g8);
-      acc = mfma16(a, b, acc);
-    }
-  };
-  // tiles of this wavefront: wv, wv + 4, wv + 8, ...
-  if (wv < nk) load(wv, t0);
-  if (wv + 4 < nk) load(wv + 4, t1);
-  for (int kt = wv; kt < nk; kt += 8) {
-    stage(t0);
-    wave_fence();
-    if (kt + 8 < nk) load(kt + 8, t0);
-    multiply();
-    wave_fence();
-    if (kt + 4 < nk) {
-      stage(t1);
-      wave_fence();
-      if (kt + 12 < nk) load(kt + 12, t1);
-      multiply();
-      wave_fence();
+  for (int u = 0; u < NT; ++u)
+    if (wv + 4 * u < nk) load(wv + 4 * u, t[u]);
+  for (int kt = wv; kt < nk; kt += 4 * NT) {
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      const int k = kt + 4 * u;
+      if (k < nk) {
+        stage(t[u]);
+        wave_fence();
+        if (k + 4 * NT < nk) load(k + 4 * NT, t[u]);
+#pragma unroll
+        for (int ks = 0; ks < TK / 32; ++ks) {
+          const half8 b = *(const half8 *)(bs + r16 * LDK + ks * 32 + g8);
+#pragma unroll
+          for (int i = 0; i < MB; ++i) {
+            const half8 a = *(const half8 *)(as + (i * 16 + r16) * LDK + ks * 32 + g8);
+            acc[i] = mfma16x16(a, b, acc[i]);
+          }
+        }
+        wave_fence();
+      }
     }
   }
   __syncthreads();
-  float *red = (float *)&As[0][0];                       // [4][32][32] floats = 16 KiB (As holds 18 KiB)
+  float *red = (float *)&As[0][0];                            // [4][RM][16] floats (As holds more)
 #pragma unroll
-  for (int r = 0; r < 16; ++r) red[(wv * 32 + c_row(r, lane)) * 32 + r32] = acc[r];
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[(wv * RM + i * 16 + (lane >> 4) * 4 + r) * 16 + r16] = acc[i][r];
   __syncthreads();
-  for (int e = tid; e < 32 * 32; e += 256) {
-    const int row = e >> 5, col = n0 + (e & 31);
+  for (int e = tid; e < RM * 16; e += 256) {
+    const int row = e >> 4, col = n0 + (e & 15);
     if (row < n_rows && col < N && (want < 0 || river[row] == want)) {
-      const float v = ((red[e] + red[1024 + e]) + red[2048 + e]) + red[3072 + e];
+      const float v = ((red[e] + red[RM * 16 + e]) + red[2 * RM * 16 + e]) + red[3 * RM * 16 + e];
       float *p = C + (size_t)row * ldc + col;
       if constexpr (ADD) *p += v;
       else *p = v;
