@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kBlock) void k_qkv(const Dev *Dp, StepArgs A, int l
   }
   Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);
-  phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
+  phase_qkv<DT>(D, A, l, ctl.river, lds, pre, [] {});
 }
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_attn(const Dev *Dp, StepArgs A, int l) {
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kBlock) void k_oproj(const Dev *Dp, StepArgs A, int
   const Ctl ctl = load_ctl(D, l);
   Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_O, ctl.river, pre);
-  phase_oproj<DT>(D, A, l, ctl.river, lds, pre);
+  phase_oproj<DT>(D, A, l, ctl.river, lds, pre, [] {});
 }
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_gateup(const Dev *Dp, StepArgs A, int l) {
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kBlock) void k_gateup(const Dev *Dp, StepArgs A, in
   const Ctl ctl = load_ctl(D, l);
   Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_GU, ctl.river, pre);
-  phase_gateup<DT>(D, A, l, ctl.river, lds, pre);
+  phase_gateup<DT>(D, A, l, ctl.river, lds, pre, [] {});
 }
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_down(const Dev *Dp, StepArgs A, int l) {
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kBlock) void k_down(const Dev *Dp, StepArgs A, int 
   const Ctl ctl = load_ctl(D, l);
   Pre<DT> pre;
   prefetch_phase<DT>(D, l, PH_DOWN, ctl.river, pre);
-  phase_down<DT>(D, A, l, ctl.river, lds, pre);
+  phase_down<DT>(D, A, l, ctl.river, lds, pre, [] {});
 }
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_head(const Dev *Dp, StepArgs A) {
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kBlock) void k_head(const Dev *Dp, StepArgs A) {
   const Ctl ctl = load_ctl(D, D.L - 1);
   Pre<DT> pre;
   prefetch_head<DT>(D, pre);
-  phase_head<DT>(D, A, ctl, lds, pre);
+  phase_head<DT>(D, A, ctl, lds, pre, [] {});
 }
 
 #ifdef RIVER_TRACE
@@ -128,13 +128,15 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
   const bool guess = (l == 0) ? ctl.river : guess_river_after(A, ctl, l);
   if (l > 0) { barrier_arrive(D.bar, k); TRACE_ARRIVE(); }
   prefetch_phase<DT>(D, l, PH_QKV, guess, pre, l > 0 ? 0 : 2);
+  bool late_part = false;                 // the late part of the prefetch is still to be issued
   if (l > 0) {
     barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE();
-    prefetch_phase<DT>(D, l, PH_QKV, guess, pre, 1);
     exit_test(D, A, l, ctl, lds);
-    if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess
+    if (ctl.river != guess) prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);   // wrong guess: everything again
+    else late_part = true;
   }
-  phase_qkv<DT>(D, A, l, ctl.river, lds, pre);
+  const bool rv = ctl.river;
+  phase_qkv<DT>(D, A, l, rv, lds, pre, [&] { if (late_part) prefetch_phase<DT>(D, l, PH_QKV, rv, pre, 1); });
   return pack_ctl(ctl);
 }
 template <int DT>
@@ -152,10 +154,11 @@ __device__ RIVER_PSTEP_INLINE void pstep_gemv(const Dev *Dp, StepArgs A, int l, 
   barrier_arrive(D.bar, k); TRACE_ARRIVE();
   prefetch_phase<DT>(D, l, PH, river, pre, 0);
   barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE();
-  prefetch_phase<DT>(D, l, PH, river, pre, 1);
-  if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre);
-  else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre);
-  else phase_down<DT>(D, A, l, river, lds, pre);
+  // the late part of the prefetch goes out behind the first loads of the phase's input vector
+  auto late = [&] { prefetch_phase<DT>(D, l, PH, river, pre, 1); };
+  if (PH == PH_O) phase_oproj<DT>(D, A, l, river, lds, pre, late);
+  else if (PH == PH_GU) phase_gateup<DT>(D, A, l, river, lds, pre, late);
+  else phase_down<DT>(D, A, l, river, lds, pre, late);
 }
 template <int DT>
 __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl_packed, unsigned long long k,
@@ -166,8 +169,7 @@ __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl
   barrier_arrive(D.bar, k); TRACE_ARRIVE();
   prefetch_head<DT>(D, pre, 0);
   barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE();
-  prefetch_head<DT>(D, pre, 1);
-  phase_head<DT>(D, A, ctl, lds, pre);
+  phase_head<DT>(D, A, ctl, lds, pre, [&] { prefetch_head<DT>(D, pre, 1); });
 }
 
 // The number of barriers (5 L - 1, one more with the head) is the same for every workgroup

@@ -425,14 +425,37 @@ __device__ __forceinline__ int x_slot(int c, int lp) {
 
 // xl = h * rsqrt(mean(h^2) + eps) * gain   (fused RMSNorm prologue), stored for runs of
 // 2^lp; h published by other workgroups, n % 4 == 0.
-template <int DT>
+// `mid` is called once, after the first global loads of the vector have been issued and before
+// their data is used: loads issued there (a late part of the weight prefetch) are in flight
+// while the vector arrives, and cannot delay it (a wavefront's loads return in order).
+#define RIVER_PIN_ORDER() __builtin_amdgcn_sched_barrier(0)
+template <int DT, class Mid>
 __device__ __forceinline__ void stage_norm(const float *h, const void *gain, int n, float eps, int lp,
-                                           float *xl, float *red) {
+                                           float *xl, float *red, Mid mid) {
   float ss = 0.f;
-  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) {
-    const float4 v = sub4(h, i);
-    *(float4 *)(xl + x_slot(i, lp)) = v;
-    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+  const int stride = blockDim.x * 4;
+  bool first = true;
+  for (int i0 = threadIdx.x * 4; i0 < n || first; i0 += 4 * stride) {
+    float4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + k * stride;
+      v[k] = i < n ? sub4(h, i) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (first) {
+      RIVER_PIN_ORDER();
+      mid();
+      RIVER_PIN_ORDER();
+      first = false;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + k * stride;
+      if (i < n) {
+        *(float4 *)(xl + x_slot(i, lp)) = v[k];
+        ss += (v[k].x * v[k].x + v[k].y * v[k].y) + (v[k].z * v[k].z + v[k].w * v[k].w);
+      }
+    }
   }
   const float tot = block_sum(ss, red);
   const float r = 1.0f / sqrtf(tot / (float)n + eps);
@@ -479,9 +502,30 @@ __device__ __forceinline__ void stage_norm_embed(DevRef D, int tok, const void *
   lds_barrier();
 }
 
-__device__ __forceinline__ void stage_copy(const float *src, int n, int lp, float *xl) {
+template <class Mid>
+__device__ __forceinline__ void stage_copy(const float *src, int n, int lp, float *xl, Mid mid) {
   lds_barrier();
-  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) *(float4 *)(xl + x_slot(i, lp)) = sub4(src, i);
+  const int stride = blockDim.x * 4;
+  bool first = true;
+  for (int i0 = threadIdx.x * 4; i0 < n || first; i0 += 4 * stride) {
+    float4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + k * stride;
+      v[k] = i < n ? sub4(src, i) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (first) {
+      RIVER_PIN_ORDER();
+      mid();
+      RIVER_PIN_ORDER();
+      first = false;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + k * stride;
+      if (i < n) *(float4 *)(xl + x_slot(i, lp)) = v[k];
+    }
+  }
   lds_barrier();
 }
 
@@ -519,14 +563,33 @@ __device__ __forceinline__ void half_store8(float *xh, int n, int c, const float
 
 // xh = half layout of h * rsqrt(mean(h^2) + eps) * gain; n % 32 == 0.  `xl` (n floats)
 // holds h between the two passes.
-template <int DT>
+template <int DT, class Mid>
 __device__ __forceinline__ void stage_norm_half(const float *h, const void *gain, int n, float eps,
-                                                float *xl, float *xh, float *red) {
+                                                float *xl, float *xh, float *red, Mid mid) {
   float ss = 0.f;
-  for (int i = threadIdx.x * 4; i < n; i += blockDim.x * 4) {
-    const float4 v = sub4(h, i);
-    *(float4 *)(xl + i) = v;
-    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+  const int stride = blockDim.x * 4;
+  bool first = true;
+  for (int i0 = threadIdx.x * 4; i0 < n || first; i0 += 4 * stride) {
+    float4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + k * stride;
+      v[k] = i < n ? sub4(h, i) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (first) {
+      RIVER_PIN_ORDER();
+      mid();
+      RIVER_PIN_ORDER();
+      first = false;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = i0 + k * stride;
+      if (i < n) {
+        *(float4 *)(xl + i) = v[k];
+        ss += (v[k].x * v[k].x + v[k].y * v[k].y) + (v[k].z * v[k].z + v[k].w * v[k].w);
+      }
+    }
   }
   const float tot = block_sum(ss, red);
   const float r = 1.0f / sqrtf(tot / (float)n + eps);
@@ -541,12 +604,33 @@ __device__ __forceinline__ void stage_norm_half(const float *h, const void *gain
   lds_barrier();
 }
 
-__device__ __forceinline__ void stage_copy_half(const float *src, int n, float *xh) {
+template <class Mid>
+__device__ __forceinline__ void stage_copy_half(const float *src, int n, float *xh, Mid mid) {
   lds_barrier();
-  for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
-    const float4 a = sub4(src, i), b = sub4(src, i + 4);
-    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    half_store8(xh, n, i, v);
+  const int stride = blockDim.x * 8;
+  bool first = true;
+  for (int i0 = threadIdx.x * 8; i0 < n || first; i0 += 2 * stride) {
+    float4 a[2], b[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int i = i0 + k * stride;
+      a[k] = i < n ? sub4(src, i) : make_float4(0.f, 0.f, 0.f, 0.f);
+      b[k] = i < n ? sub4(src, i + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (first) {
+      RIVER_PIN_ORDER();
+      mid();
+      RIVER_PIN_ORDER();
+      first = false;
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int i = i0 + k * stride;
+      if (i < n) {                                   // whole quads of threads: n % 32 == 0
+        const float v[8] = {a[k].x, a[k].y, a[k].z, a[k].w, b[k].x, b[k].y, b[k].z, b[k].w};
+        half_store8(xh, n, i, v);
+      }
+    }
   }
   lds_barrier();
 }
@@ -1050,19 +1134,22 @@ __device__ __forceinline__ bool guess_river_after(const StepArgs &A, const Ctl &
 // RoPE, the rounding of k, v to the cache dtype and the write of slot (l, pos) happen in the
 // attention phase (a2 there), which frees the row-to-wavefront assignment here: single rows,
 // three per wavefront at the 8B shape.
-template <int DT>
-__device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+template <int DT, class Late>
+__device__ __forceinline__ void phase_qkv(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre,
+                                          Late late) {
   RIVER_MARK(D, 16);
   LayerRef Lw = layer_of(D, l);
   if (l == 0) {
     int tok = A.token >= 0 ? A.token : D.st->cur_token;
     tok = min(max(tok, 0), D.vocab - 1);       // a NaN-poisoned argmax must not index out of range
+    late();
     stage_norm_embed<DT>(D, tok, Lw.attn_norm, run_log2<DT>(river, D.d), lds, lds_half(D, lds), lds_red(D, lds));
   } else if (run_log2<DT>(river, D.d) < 0) {
-    stage_norm_half<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, lds, lds_half(D, lds), lds_red(D, lds));
+    stage_norm_half<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, lds, lds_half(D, lds), lds_red(D, lds),
+                        late);
   } else {
     stage_norm<DT>(D.hidden + (size_t)l * D.d, Lw.attn_norm, D.d, D.eps, run_log2<DT>(river, D.d), lds,
-                   lds_red(D, lds));
+                   lds_red(D, lds), late);
   }
   RIVER_MARK(D, 17);
   const int qd = D.nq * D.hd, nrows = qd + 2 * D.nkv * D.hd;
@@ -1281,13 +1368,15 @@ __device__ __forceinline__ void combine_splits8(DevRef D, int S, int h, int e8, 
 // Stage the attention output for the output projection: a copy of the finished vector
 // (one split), or the merge of the split partials, done by every workgroup for itself --
 // that costs the consumers some more loads but no extra hand-over between workgroups.
-__device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, int lp, float *xl, float *xh) {
+template <class Mid>
+__device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, int lp, float *xl, float *xh, Mid mid) {
   const int S = A.n_splits, n = D.nq * D.hd;
   if (S == 1) {
-    if (lp < 0) stage_copy_half(D.obuf, n, xh);
-    else stage_copy(D.obuf, n, lp, xl);
+    if (lp < 0) stage_copy_half(D.obuf, n, xh, mid);
+    else stage_copy(D.obuf, n, lp, xl, mid);
     return;
   }
+  mid();
   lds_barrier();
   for (int i = threadIdx.x * 8; i < n; i += blockDim.x * 8) {
     float v[8];
@@ -1485,11 +1574,12 @@ __device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, c
 }
 
 // a4: h1 = h + W_o o
-template <int DT>
-__device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+template <int DT, class Late>
+__device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre,
+                                            Late late) {
   RIVER_MARK(D, 20);
   const int lp = run_log2<DT>(river, D.nq * D.hd);
-  stage_attn_out(D, A, lp, lds, lds_half(D, lds));
+  stage_attn_out(D, A, lp, lds, lds_half(D, lds), late);
   RIVER_MARK(D, 21);
   const float *hin = D.hidden + (size_t)l * D.d;
   const int lane = pre.lane;
@@ -1508,12 +1598,14 @@ __device__ __forceinline__ void phase_oproj(DevRef D, const StepArgs &A, int l, 
 }
 
 // a5: y = RMSNorm(h1) * g2; a = silu(W_g y) * (W_u y); rows come as (gate i, up i) pairs
-template <int DT>
-__device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+template <int DT, class Late>
+__device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre,
+                                             Late late) {
   RIVER_MARK(D, 24);
   const int lp = run_log2<DT>(river, D.d);
-  if (lp < 0) stage_norm_half<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lds, lds_half(D, lds), lds_red(D, lds));
-  else stage_norm<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lp, lds, lds_red(D, lds));
+  if (lp < 0)
+    stage_norm_half<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lds, lds_half(D, lds), lds_red(D, lds), late);
+  else stage_norm<DT>(D.h1, layer_of(D, l).ffn_norm, D.d, D.eps, lp, lds, lds_red(D, lds), late);
   RIVER_MARK(D, 25);
   const int lane = pre.lane;
   auto epi = [&](int n0, auto &acc) {
@@ -1533,12 +1625,13 @@ __device__ __forceinline__ void phase_gateup(DevRef D, const StepArgs &A, int l,
 // Eq. 1's similarity <h,h2>, <h,h>, <h2,h2> reduced over this workgroup's rows.  The
 // reduction over workgroups and the exit decision are taken by every workgroup at the
 // start of the next block (exit_test), so no workgroup waits for another here.
-template <int DT>
-__device__ __forceinline__ void phase_down(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre) {
+template <int DT, class Late>
+__device__ __forceinline__ void phase_down(DevRef D, const StepArgs &A, int l, bool river, float *lds, Pre<DT> &pre,
+                                           Late late) {
   RIVER_MARK(D, 28);
   const int lp = run_log2<DT>(river, D.ffn);
-  if (lp < 0) stage_copy_half(D.abuf, D.ffn, lds_half(D, lds));
-  else stage_copy(D.abuf, D.ffn, lp, lds);
+  if (lp < 0) stage_copy_half(D.abuf, D.ffn, lds_half(D, lds), late);
+  else stage_copy(D.abuf, D.ffn, lp, lds, late);
   RIVER_MARK(D, 29);
   const float *hin = D.hidden + (size_t)l * D.d;
   float *hout = D.hidden + (size_t)(l + 1) * D.d;
@@ -1588,14 +1681,15 @@ __device__ __forceinline__ void prefetch_head(DevRef D, Pre<DT> &g, int part = 2
   const int n = (D.vocab + kRD - 1) / kRD;
   issue_first<Dense<DT, kRD, kUD>, DT, kRD>(part, n, D.d, D.group, g, rows_of);
 }
-template <int DT>
-__device__ __forceinline__ void phase_head(DevRef D, const StepArgs &A, const Ctl &ctl, float *lds, Pre<DT> &pre) {
+template <int DT, class Late>
+__device__ __forceinline__ void phase_head(DevRef D, const StepArgs &A, const Ctl &ctl, float *lds, Pre<DT> &pre,
+                                           Late late) {
   float *red = lds_red(D, lds);
   if (!ctl.river && A.rec_slot >= 0) {      // similarity of the last backbone block: recorded, never tested
     const float s = similarity_from_partials(D, red);
     if (blockIdx.x == 0 && threadIdx.x == 0) pub(D.rec_sims + (size_t)A.rec_slot * D.L + (D.L - 1), s);
   }
-  stage_norm<DT>(D.hidden + (size_t)D.L * D.d, D.final_norm, D.d, D.eps, run_log2<DT>(false, D.d), lds, red);
+  stage_norm<DT>(D.hidden + (size_t)D.L * D.d, D.final_norm, D.d, D.eps, run_log2<DT>(false, D.d), lds, red, late);
   const int lane = pre.lane;
   float best = -INFINITY;
   int besti = 0x7fffffff;
