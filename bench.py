@@ -72,6 +72,60 @@ def cpu_baseline(cfg, weights, sched, budget_steps, budget_seconds=25.0):
                       f"prompt (context 5..{4 + n}); fp64 C oracle with OpenMP"}
 
 
+def phase_trace(ctx_len):
+    """Per-phase timeline of the one-launch kernel at the 8B shape from the diagnostics build
+    (device clock stamps at every device-wide barrier): for a dense and an all-river token, per
+    phase the time until the first / median / last workgroup arrives at the barrier behind it
+    and the time that barrier then takes.  Needs libriver_trace.so
+    (python3 -c "from paper_2604_18396_amd import build; build.build(trace=True)")."""
+    from paper_2604_18396_amd import build
+    os.environ["RIVER_LIB_PATH"] = build.TRACE_LIB
+    import numpy as np
+    import torch
+    from paper_2604_18396_amd import binding, byte_model, configs, inputs
+    cfg = configs.LLAMA_8B.with_(max_seq=ctx_len + 64, min_exit_layer=0)
+    one = cfg.with_(n_layers=1)
+    w1 = inputs.make_weights(one, 7)                      # one block's weights stand for all 32 (timing only)
+    dw1 = binding.upload_weights(w1)
+    dw = {k: dw1[k] for k in ("tok_emb", "final_norm", "lm_head")}
+    dw["layers"] = [dw1["layers"][0]] * cfg.n_layers
+    dr = binding.quantize_river(one, dw1) * cfg.n_layers
+    g = binding.River(cfg, dw, dr, exec_mode=binding.EXEC_PERSISTENT)
+    g.prefill(list(range(1, ctx_len + 1)))
+    L = cfg.n_layers
+    names = ["QKV", "attention", "O-proj", "gate/up", "down"]
+    mats = [("wq", "wk", "wv"), (), ("wo",), ("w_gate", "w_up"), ("w_down",)]
+    print(f"# phase timeline of k_step_persistent<1>, 8B shape, context {ctx_len}, mean over blocks 2..{L}, microseconds")
+    for which, fe in (("dense token (backbone blocks)", L), ("all-river token (4-bit twins)", 0)):
+        for _ in range(4):
+            g.decode_step(None, fe, sync=False)
+        g.decode_step(None, fe, sync=True)
+        t = g.trace(256).astype(np.int64)                # [5L, 2, 256], 10 ns ticks
+        A, R = t[:, 0, :], t[:, 1, :]
+        print(f"## {which}: whole token {(A[-1].max() - R[0].min()) / 100:.1f} us (first release to last arrival, head excluded)")
+        print(f"#  {'phase':10s} {'MB read':>8s} {'first done':>10s} {'median':>8s} {'last done':>9s} {'barrier':>8s} {'span':>7s} {'at 8 TB/s':>9s}")
+        total = 0.0
+        for p in range(5):
+            first, med, last, bar = [], [], [], []
+            for l in range(1, L):
+                b = l * 5 + p
+                start = R[b - 1].max()
+                first.append(A[b].min() - start); med.append(np.median(A[b]) - start)
+                last.append(A[b].max() - start); bar.append(R[b].max() - A[b].max())
+            f = lambda v: float(np.mean(v)) / 100
+            mb = 0.0
+            for m in mats[p]:
+                r_, c_ = configs.matrix_shape(cfg, m)
+                mb += (r_ * c_ * 2 if fe == L else r_ * c_ // 2 + 4 * r_ * (c_ // cfg.river_group)) / 1e6
+            if p == 1:
+                mb = byte_model.kv_bytes_per_position(cfg) / L * (ctx_len + 5) / 1e6
+            span = f(last) + f(bar)
+            total += span
+            print(f"   {names[p]:10s} {mb:8.1f} {f(first):10.2f} {f(med):8.2f} {f(last):9.2f} {f(bar):8.2f} {span:7.2f} {mb / 8.0:9.2f}")
+        print(f"   per block {total:.1f} us")
+    g.close()
+
+
 def calibrate_copy(mib, iters):
     """A plain device copy of known size, for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE
     counters: run `rocprofv3 --pmc FETCH_SIZE -- python3 bench.py --calibrate-copy 1024`."""
@@ -203,7 +257,12 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=24)
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB MiB three times (counter calibration)")
+    ap.add_argument("--phase-trace", type=int, default=0, metavar="CTX",
+                    help="only print the per-phase barrier timeline of the diagnostics build at context CTX")
     args = ap.parse_args()
+    if args.phase_trace:
+        phase_trace(args.phase_trace)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus must be 1 "
               "(no collectives or sharding exist in it).", file=sys.stderr)
