@@ -257,6 +257,9 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=24)
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB MiB three times (counter calibration)")
+    ap.add_argument("--offload-from", type=int, default=0, metavar="BLOCK",
+                    help="Backbone Offloading: keep the matrices of backbone blocks above BLOCK in pinned host "
+                         "memory (read in place over the host link); 0 = everything in HBM")
     ap.add_argument("--phase-trace", type=int, default=0, metavar="CTX",
                     help="only print the per-phase barrier timeline of the diagnostics build at context CTX")
     args = ap.parse_args()
@@ -295,6 +298,12 @@ def main():
     dr = binding.quantize_river(cfg, dw)
     torch.cuda.synchronize()
     log(f"uploaded + river built on the GPU in {time.time() - t0:.1f}s")
+    resident = byte_model.backbone_param_bytes(cfg) + L * byte_model.block_bytes_river(cfg)
+    if args.offload_from:
+        dw = binding.offload_backbone(dw, args.offload_from)
+        resident -= (L - args.offload_from) * (byte_model.block_bytes_backbone(cfg) - 2 * cfg.d_model * 2)
+        log(f"backbone blocks {args.offload_from + 1}..{L} offloaded to pinned host memory; "
+            f"{resident / 2**30:.2f} GiB of parameters resident in HBM")
     mode = binding.EXEC_PERSISTENT if args.mode == "persistent" else binding.EXEC_KERNELS
     # tau = 1: Eq. 1 never fires (s <= 1, strict '>'), so the threshold-mode leg below runs
     # the whole backbone with the exit test taken after every block; forced legs ignore tau
@@ -367,7 +376,8 @@ def main():
         "config": {"workload": wl.name, "shape": cfg.name, "prompt_len": wl.prompt_len,
                    "exit_schedule": "forced, 1/2 U{L/4..L/2} + 1/2 U{L/2+1..L-1}",
                    "mean_exit_position": float(np.mean(sched[W:])), "exec_mode": args.mode,
-                   "batch": 1},
+                   "batch": 1, "offload_from": args.offload_from,
+                   "resident_parameter_GiB": resident / 2**30},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "k_step_persistent<1>" if args.mode == "persistent" else "all step kernels",

@@ -81,7 +81,11 @@ typedef struct {
                               the first block with min over the batch of s_b > tau */
 } river_config;
 
-/* Backbone weights.  DEVICE pointers in HOST arrays of length n_layers. */
+/* Backbone weights.  DEVICE pointers in HOST arrays of length n_layers.  "DEVICE" includes
+ * pinned host memory that the device can address (hipHostMalloc): the paper's Backbone
+ * Offloading keeps deep, rarely reached backbone blocks out of VRAM while the river stays
+ * resident; a caller does that by handing such pointers for those blocks' matrices, which the
+ * kernels then read in place over the host link only when a token reaches them. */
 typedef struct {
   const void *tok_emb;    /* [vocab, d_model] */
   const void *final_norm; /* [d_model] */

@@ -29,10 +29,13 @@ def to_f64(t) -> np.ndarray:
     return np.asarray(t, dtype=np.float64)
 
 
-def round_to(v: np.ndarray, dtype: int) -> np.ndarray:
-    """fp64 values -> values of the storage dtype (0 fp32, 1 bf16), round-to-nearest-even."""
+def round_to(v: np.ndarray, dtype: int, kv_dtype: int = 0) -> np.ndarray:
+    """fp64 values -> values of the cache's storage type (kv_dtype 1: IEEE half; else the
+    weight dtype: 0 fp32, 1 bf16), round-to-nearest-even."""
     t = torch.from_numpy(np.ascontiguousarray(v)).to(torch.float32)
-    if dtype == 1:
+    if kv_dtype == 1:
+        t = t.to(torch.float16)
+    elif dtype == 1:
         t = t.to(torch.bfloat16)
     return t.to(torch.float64).numpy()
 
@@ -128,8 +131,8 @@ def run(cfg, weights: dict, river: list | None, tokens, exits=None):
         qv = _rope(mm("wq", x).reshape(T, nq, hd), pos, hd, base)
         kv = _rope(mm("wk", x).reshape(T, nkv, hd), pos, hd, base)
         vv = mm("wv", x).reshape(T, nkv, hd)
-        kv = round_to(kv, cfg.dtype)                  # what the cache stores
-        vv = round_to(vv, cfg.dtype)
+        kv = round_to(kv, cfg.dtype, getattr(cfg, "kv_dtype", 0))   # what the cache stores
+        vv = round_to(vv, cfg.dtype, getattr(cfg, "kv_dtype", 0))
         rep = nq // nkv
         o = np.zeros((T, nq, hd))
         for i in range(nq):

@@ -55,6 +55,8 @@ typedef struct {
   int32_t min_exit_layer; /* L_s */
   float tau;
   int32_t river_group;
+  int32_t kv_dtype; /* KV-cache storage: 0 = the weight dtype, 1 = IEEE half (fp16), the type the
+                       paper keeps its cache in ("KV-Shared Exit Layer": W4A16, KV cache in FP16) */
 } orc_config;
 
 /* per-layer pointer table, host memory, element type = cfg.dtype */
@@ -109,9 +111,40 @@ static inline double ld(const void *p, int64_t i, int dtype) {
   return dtype ? (double)bf16_to_f32(((const uint16_t *)p)[i]) : (double)((const float *)p)[i];
 }
 
-/* value -> value representable in the cache dtype */
-static inline float round_cache(double v, int dtype) {
+/* round-to-nearest-even float -> IEEE binary16 word (1 sign, 5 exponent, 10 mantissa bits;
+ * subnormals kept, overflow to infinity) */
+uint16_t orc_f32_to_f16(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+  uint32_t a = u & 0x7fffffffu;
+  if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);          /* NaN */
+  if (a >= 0x477ff000u) return (uint16_t)(sign | 0x7c00u);         /* >= 65520 rounds to infinity */
+  if (a < 0x33000001u) return sign;                                /* <= 2^-25 rounds to zero */
+  int e = (int)(a >> 23) - 127;                                    /* unbiased exponent */
+  uint32_t m = (a & 0x7fffffu) | 0x800000u;                        /* 24-bit significand */
+  int shift = e >= -14 ? 13 : 13 + (-14 - e);                      /* bits dropped (subnormal: more) */
+  uint32_t keep = m >> shift, rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1);
+  if (rem > half || (rem == half && (keep & 1u))) keep += 1;
+  /* normal: keep holds 1.mmmmmmmmmm (11 bits), exponent field e + 15; a carry out of the
+   * significand moves into the exponent by plain addition, subnormals likewise */
+  uint32_t h = e >= -14 ? ((uint32_t)(e + 15) << 10) + (keep - 0x400u) : keep;
+  return (uint16_t)(sign | h);
+}
+
+float orc_f16_to_f32(uint16_t h) {
+  int sign = (h >> 15) & 1, e = (h >> 10) & 31, m = h & 1023;
+  double v;
+  if (e == 0) v = ldexp((double)m, -24);
+  else if (e == 31) v = m ? NAN : INFINITY;
+  else v = ldexp((double)(m | 1024), e - 25);
+  return (float)(sign ? -v : v);
+}
+
+/* value -> value representable in the cache's storage type */
+static inline float round_cache(double v, int dtype, int kv_dtype) {
   float f = (float)v;
+  if (kv_dtype == 1) return orc_f16_to_f32(orc_f32_to_f16(f));
   return dtype ? bf16_to_f32(orc_f32_to_bf16(f)) : f;
 }
 
@@ -313,8 +346,8 @@ static void block(orc_ctx *x, int l, int p, int river, const double *h, double *
   orc_rope(k, nkv, hd, p, c->rope_base);
   float *Kl = x->kcache + (int64_t)l * c->max_seq * kvd, *Vl = x->vcache + (int64_t)l * c->max_seq * kvd;
   for (int i = 0; i < kvd; ++i) {
-    Kl[(int64_t)p * kvd + i] = round_cache(k[i], dt);
-    Vl[(int64_t)p * kvd + i] = round_cache(v[i], dt);
+    Kl[(int64_t)p * kvd + i] = round_cache(k[i], dt, c->kv_dtype);
+    Vl[(int64_t)p * kvd + i] = round_cache(v[i], dt, c->kv_dtype);
   }
   if (x->written[(int64_t)l * c->max_seq + p] < 255) x->written[(int64_t)l * c->max_seq + p]++;
   orc_attention(q, Kl, Vl, p + 1, nq, nkv, hd, o);
@@ -351,7 +384,8 @@ int orc_create(const orc_config *cfg, const void *tok_emb, const void *final_nor
                orc_ctx **out) {
   if (!cfg || !tok_emb || !final_norm || !lm_head || !layers || !out) return ORC_EINVAL;
   if (cfg->n_layers < 1 || cfg->n_q_heads % cfg->n_kv_heads || cfg->head_dim % 2 ||
-      cfg->min_exit_layer < 0 || cfg->min_exit_layer > cfg->n_layers || cfg->max_seq < 1)
+      cfg->min_exit_layer < 0 || cfg->min_exit_layer > cfg->n_layers || cfg->max_seq < 1 ||
+      (cfg->kv_dtype != 0 && cfg->kv_dtype != 1))
     return ORC_EINVAL;
   orc_ctx *x = calloc(1, sizeof(*x));
   x->c = *cfg;

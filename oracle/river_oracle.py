@@ -22,7 +22,7 @@ class _Cfg(C.Structure):
                 ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
                 ("max_seq", C.c_int32), ("min_exit_layer", C.c_int32), ("tau", C.c_float),
-                ("river_group", C.c_int32)]
+                ("river_group", C.c_int32), ("kv_dtype", C.c_int32)]
 
 
 class _Layer(C.Structure):
@@ -82,6 +82,10 @@ def lib():
         L.orc_cosine.restype = C.c_double
         L.orc_f32_to_bf16.argtypes = [C.c_float]
         L.orc_f32_to_bf16.restype = C.c_uint16
+        L.orc_f32_to_f16.argtypes = [C.c_float]
+        L.orc_f32_to_f16.restype = C.c_uint16
+        L.orc_f16_to_f32.argtypes = [C.c_uint16]
+        L.orc_f16_to_f32.restype = C.c_float
     return _lib
 
 
@@ -136,7 +140,7 @@ class Oracle:
         self._keep = (weights, river)
         c = _Cfg(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
                  cfg.vocab, cfg.rope_base, cfg.rms_eps, cfg.dtype, cfg.max_seq, cfg.min_exit_layer,
-                 cfg.tau, cfg.river_group)
+                 cfg.tau, cfg.river_group, getattr(cfg, "kv_dtype", 0))
         layers = (_Layer * cfg.n_layers)()
         for i, blk in enumerate(weights["layers"]):
             for n, _ in _Layer._fields_:

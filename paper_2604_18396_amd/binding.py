@@ -138,6 +138,31 @@ def upload_weights(weights: dict, device="cuda:0") -> dict:
     return out
 
 
+def offload_backbone(dev_weights: dict, from_block: int) -> dict:
+    """Backbone Offloading: the seven matrices of backbone blocks from_block+1..L (1-based: the
+    blocks a token only reaches when its exit position exceeds from_block) are moved out of
+    HBM into pinned host memory, which the GPU reads in place over the host link when a token
+    does reach them; norm gains, embedding, head and the whole river stay in HBM.  Build the
+    river first (quantize_river reads the matrices on the device).  Returns a new weight dict."""
+    out = {k: dev_weights[k] for k in ("tok_emb", "final_norm", "lm_head")}
+    out["layers"] = []
+    for l, blk in enumerate(dev_weights["layers"]):
+        if l < from_block:
+            out["layers"].append(blk)
+            continue
+        nb = {}
+        for k, v in blk.items():
+            if k in MATRICES:
+                host = torch.empty(v.shape, dtype=v.dtype, pin_memory=True)
+                host.copy_(v)
+                nb[k] = host
+            else:
+                nb[k] = v
+        out["layers"].append(nb)
+    torch.cuda.synchronize()
+    return out
+
+
 def quantize_river(cfg: ModelConfig, dev_weights: dict) -> list:
     """River construction on the device for every block (list of {name: (codes, scale, zero)})."""
     return [{m: river_quantize_w4(blk[m], cfg.river_group) for m in MATRICES}
@@ -179,6 +204,7 @@ class River:
         if nbytes == 0:
             raise RiverError(RIVER_EINVAL, "invalid configuration")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev_weights["tok_emb"].device)
+        self.workspace_bytes = nbytes
         h = C.c_void_p()
         create = L.river_create_static if static_scratch else L.river_create
         rc = create(C.byref(self._c), C.byref(w), C.byref(q) if q is not None else None,

@@ -15,6 +15,8 @@ from dataclasses import dataclass, replace
 
 DTYPE_F32 = 0
 DTYPE_BF16 = 1
+KV_SAME = 0
+KV_F16 = 1
 
 
 @dataclass(frozen=True)
@@ -34,6 +36,7 @@ class ModelConfig:
     min_exit_layer: int   # L_s
     tau: float
     river_group: int = 64
+    kv_dtype: int = 0     # KV-cache storage: 0 = the weight dtype, 1 = fp16 (bf16 models only)
 
     @property
     def params_per_block(self) -> int:

@@ -636,3 +636,32 @@ def test_gemm_prefill_in_chunks_equals_serial_prefill_closely():
         g.close()
     for a, b in zip(outs[1][1:], outs[0][1:]):
         assert relerr(a, np.asarray(b, np.float64)) <= 5e-3
+
+
+# ------------------------------------------------------------ backbone offloading
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+def test_backbone_offloading_reads_deep_blocks_from_pinned_host_memory(mode):
+    """Backbone Offloading (method section; appendix on memory): the matrices of backbone
+    blocks above a depth cutoff live in pinned host memory instead of HBM; the river stays
+    resident.  Tokens that stay below the cutoff never touch them; tokens that go deeper read
+    them in place.  Results must equal the all-in-HBM context bit for bit and match the oracle."""
+    cfg = MID.with_(min_exit_layer=0)
+    say(f"backbone offloading mode={mode}")
+    w = inputs.make_weights(cfg, 77, gain_std=0.05)
+    pair = Pair(cfg, w, mode)
+    off = binding.offload_backbone(pair.dw, 1)                  # blocks 2 and 3 out of HBM
+    assert not off["layers"][2]["wq"].is_cuda and off["layers"][2]["wq"].is_pinned()
+    assert off["layers"][0]["wq"].is_cuda and off["layers"][2]["attn_norm"].is_cuda
+    g2 = binding.River(cfg, off, pair.dr, exec_mode=mode, prefill_gemm_min_tokens=-1)
+    prompt = inputs.make_prompt(cfg.vocab, 12, 78)
+    tok = pair.prefill(prompt, 1)                               # prefill at depth 1: no offloaded block is read
+    assert g2.prefill(prompt, 1) == pair.g.prefill(prompt, 1)
+    for i, e in enumerate([1, 0, 3, 1, 2, 3]):
+        t2, e2, s2 = g2.decode_step(tok, e)
+        tok, eo, so = pair.step(tok, e, what=f"offloading step {i}")
+        np.testing.assert_array_equal(g2.hidden(), pair.g.hidden())
+        np.testing.assert_array_equal(g2.logits(), pair.g.logits())
+        assert e2 == eo
+    g2.close()
+    pair.close()

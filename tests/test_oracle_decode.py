@@ -335,3 +335,27 @@ def test_prefill_exit_layer_range(tiny_setup):
     with pytest.raises(ValueError):
         o.prefill([1, 2, 3], cfg.n_layers + 1)
     assert 0 <= o.prefill([1, 2, 3], 2) < cfg.vocab
+
+
+def test_fp16_kv_cache_equals_plain_definition():
+    """KV cache kept in IEEE half as the paper states ("KV-Shared Exit Layer": the cache stays in
+    FP16): the cached run must equal the no-cache definition that rounds K/V to half, and must
+    differ from the bf16-cache run (half has three more mantissa bits)."""
+    cfg = TINY_BF16.with_(min_exit_layer=0, kv_dtype=configs.KV_F16)
+    w = inputs.make_weights(cfg, 21)
+    river = ro.quantize_river(cfg, w)
+    prompt = inputs.make_prompt(cfg.vocab, 5, 22)
+    sched = [0, 4, 1, 2, 3, 3, 0, 2]
+    o = ro.Oracle(cfg, w, river)
+    toks, es, sims, hids, logits = _free_run(o, prompt, len(sched), sched)
+    ref = pd.run(cfg, w, river, list(prompt) + toks[:-1], exits=[cfg.n_layers] * 5 + sched)
+    assert list(ref["tokens"][4:]) == toks
+    for i in range(len(sched)):
+        np.testing.assert_allclose(hids[i], ref["hidden"][5 + i], rtol=1e-8, atol=1e-11)
+    # every cached value is a half
+    k = o.kcache()[:, :13]
+    assert np.array_equal(k, k.astype(np.float16).astype(np.float32)) and np.abs(k).max() > 0
+    o2 = ro.Oracle(cfg.with_(kv_dtype=configs.KV_SAME), w, river)
+    _free_run(o2, prompt, len(sched), sched)
+    k2 = o2.kcache()[:, :13]
+    assert not np.array_equal(k, k2) and np.abs(k - k2).max() < 2e-2 * np.abs(k2).max()

@@ -152,3 +152,29 @@ def test_bf16_rounding_matches_library():
     # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
     assert ro.lib().orc_f32_to_bf16(1.00390625) == 0x3F80
     assert ro.lib().orc_f32_to_bf16(1.01171875) == 0x3F82
+
+
+def test_f16_rounding_bit_exact_with_torch():
+    """The oracle's fp32 -> IEEE half rounding (the FP16 KV cache) against torch's conversion:
+    random values over the whole range, ties, subnormals, the overflow boundary, signs."""
+    import ctypes
+    L = ro.lib()
+    rng = np.random.default_rng(3)
+    vals = [0.0, -0.0, 1.0, -1.0, 65504.0, 65519.99, 65520.0, 70000.0, -65520.0, 2.0 ** -24, 2.0 ** -25,
+            2.0 ** -25 * 1.0000001, 2.0 ** -14, 2.0 ** -14 * 0.9999, 6.1e-5, 5.96e-8, 3e-8, 1e-10,
+            1.00048828125, 1.00146484375, 2049.0, 2051.0, 0.333333, 1e-3, 1023.5, 1024.5]
+    vals += list(rng.standard_normal(4000).astype(np.float32) * np.float32(0.7))
+    vals += list((rng.standard_normal(2000) * 10.0 ** rng.uniform(-9, 5, 2000)).astype(np.float32))
+    # exact ties: halfway between two neighbouring halves
+    h = rng.integers(0x0001, 0x7bff, 2000).astype(np.uint16)
+    lo = torch.from_numpy(h.view(np.int16)).view(torch.float16).to(torch.float32)
+    hi = torch.from_numpy((h + 1).astype(np.uint16).view(np.int16)).view(torch.float16).to(torch.float32)
+    vals += list(((lo + hi) / 2).numpy())
+    v = np.array(vals, dtype=np.float32)
+    v = np.concatenate([v, -v])
+    want = torch.from_numpy(v).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([L.orc_f32_to_f16(ctypes.c_float(float(x))) for x in v], dtype=np.uint16)
+    np.testing.assert_array_equal(got, want)
+    back = np.array([L.orc_f16_to_f32(int(x)) for x in want[:5000]], dtype=np.float32)
+    ref = torch.from_numpy(want[:5000].view(np.int16)).view(torch.float16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(back, ref)
