@@ -380,7 +380,7 @@ def main():
                    "resident_parameter_GiB": resident / 2**30},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "k_step_persistent<1>" if args.mode == "persistent" else "all step kernels",
+                     "kernel": "k_step_persistent<1, false>" if args.mode == "persistent" else "all step kernels",
                      "algorithmic_bytes_per_launch": float(np.mean(bytes_river)),
                      "traffic_detail": traffic_detail},
         "dense": {"value": tok_s_dense, "unit": "tokens/s", "ms_per_step": ms_dense / K,

@@ -50,6 +50,10 @@ enum {
 
 enum { RIVER_F32 = 0, RIVER_BF16 = 1 };
 
+/* Storage type of the KV cache: the weight dtype, or IEEE half (the paper keeps the cache in
+ * FP16; "KV-Shared Exit Layer" subsection).  RIVER_KV_F16 needs RIVER_BF16 weights. */
+enum { RIVER_KV_SAME = 0, RIVER_KV_F16 = 1 };
+
 /* How one decode step is issued.  Both run the same device code.
  * KERNELS: one launch per phase (6 + 5 per block), no cross-workgroup waiting.
  * PERSISTENT: one launch per token; workgroups meet at device-wide barriers
@@ -79,6 +83,7 @@ typedef struct {
   int32_t batch_exit_rule; /* batched contexts, when Eq. 1 decides: 0 = every sequence for itself
                               (s_b > tau); 1 = Eq. 1 as printed: the whole batch leaves the backbone together at
                               the first block with min over the batch of s_b > tau */
+  int32_t kv_dtype;        /* RIVER_KV_* */
 } river_config;
 
 /* Backbone weights.  DEVICE pointers in HOST arrays of length n_layers.  "DEVICE" includes
@@ -225,7 +230,7 @@ int river_seq_position(const river_ctx *ctx, int32_t seq); /* the same for seque
 enum {
   RIVER_DBG_HIDDEN = 0, /* fp32 [n_layers+1][d_model]: h(0..L) of the last token processed */
   RIVER_DBG_LOGITS = 1, /* fp32 [vocab] of the last step that ran the head */
-  RIVER_DBG_KCACHE = 2, /* cache dtype [max_batch][n_layers][max_seq][n_kv_heads*head_dim] */
+  RIVER_DBG_KCACHE = 2, /* cache storage type [max_batch][n_layers][max_seq][n_kv_heads*head_dim] */
   RIVER_DBG_VCACHE = 3,
   RIVER_DBG_TRACE = 4,  /* uint64 [5*n_layers][2][workgroups] then [64]: 100 MHz device clock at which each
                            workgroup arrived at / was released from each device-wide barrier of the last

@@ -39,7 +39,7 @@ class river_config(C.Structure):
                 ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("min_exit_layer", C.c_int32),
                 ("tau", C.c_float), ("river_bits", C.c_int32), ("river_group", C.c_int32),
                 ("exec_mode", C.c_int32), ("spin_limit", C.c_int32), ("prefill_gemm_min_tokens", C.c_int32),
-                ("batch_exit_rule", C.c_int32)]
+                ("batch_exit_rule", C.c_int32), ("kv_dtype", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -108,7 +108,7 @@ def make_config(cfg: ModelConfig, exec_mode: int | None = None, spin_limit: int 
     return river_config(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
                         cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps, cfg.dtype, max_batch, cfg.max_seq,
                         cfg.min_exit_layer, cfg.tau, 4, cfg.river_group, exec_mode, spin_limit,
-                        prefill_gemm_min_tokens, batch_exit_rule)
+                        prefill_gemm_min_tokens, batch_exit_rule, cfg.kv_dtype)
 
 
 def _stream_ptr() -> int:
@@ -325,6 +325,8 @@ class River:
         if c.dtype == 1:
             raw = np.empty(shape, dtype=np.uint16)
             self._check(load().river_get_debug(self._h, what, raw.ctypes.data, raw.nbytes))
+            if c.kv_dtype == 1:
+                return raw.view(np.float16).astype(np.float32)         # IEEE half words -> fp32 values
             return (raw.astype(np.uint32) << 16).view(np.float32)      # bf16 words -> fp32 values
         raw = np.empty(shape, dtype=np.float32)
         self._check(load().river_get_debug(self._h, what, raw.ctypes.data, raw.nbytes))

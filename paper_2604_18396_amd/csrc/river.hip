@@ -53,11 +53,13 @@ __global__ __launch_bounds__(kBlock) void k_qkv(const Dev *Dp, StepArgs A, int l
   prefetch_phase<DT>(D, l, PH_QKV, ctl.river, pre);
   phase_qkv<DT>(D, A, l, ctl.river, lds, pre, [] {});
 }
-template <int DT>
+// F16: the 16-bit KV cache of a bf16 model holds IEEE half values (a kernel of its own per
+// cache type, so that no kernel carries both conversions)
+template <int DT, bool F16>
 __global__ __launch_bounds__(kBlock) void k_attn(const Dev *Dp, StepArgs A, int l) {
   extern __shared__ float lds[];
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
-  phase_attn<DT>(D, A, l, load_ctl(D, l), lds, [] {}, [] {});
+  phase_attn<DT, F16>(D, A, l, load_ctl(D, l), lds, [] {}, [] {});
 }
 template <int DT>
 __global__ __launch_bounds__(kBlock) void k_oproj(const Dev *Dp, StepArgs A, int l) {
@@ -139,11 +141,11 @@ __device__ RIVER_PSTEP_INLINE int pstep_qkv(const Dev *Dp, StepArgs A, int l, in
   phase_qkv<DT>(D, A, l, rv, lds, pre, [&] { if (late_part) prefetch_phase<DT>(D, l, PH_QKV, rv, pre, 1); });
   return pack_ctl(ctl);
 }
-template <int DT>
+template <int DT, bool F16>
 __device__ RIVER_PSTEP_INLINE void pstep_attn(const Dev *Dp, StepArgs A, int l, int ctl_packed, unsigned long long k,
                                         float *lds) {
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
-  phase_attn<DT>(D, A, l, unpack_ctl(ctl_packed), lds, [&] { barrier_arrive(D.bar, k); TRACE_ARRIVE(); },
+  phase_attn<DT, F16>(D, A, l, unpack_ctl(ctl_packed), lds, [&] { barrier_arrive(D.bar, k); TRACE_ARRIVE(); },
                  [&] { barrier_wait(D.bar, k, D.spin_limit, D.bar_vector_poll); TRACE_RELEASE(); });
 }
 template <int DT, int PH>
@@ -174,7 +176,7 @@ __device__ RIVER_PSTEP_INLINE void pstep_head(const Dev *Dp, StepArgs A, int ctl
 
 // The number of barriers (5 L - 1, one more with the head) is the same for every workgroup
 // whatever the exit state.
-template <int DT>
+template <int DT, bool F16>
 __global__ __launch_bounds__(kBlock) void k_step_persistent(const Dev *Dp, StepArgs A) {
   extern __shared__ float lds[];
   DevRef D = *RIVER_CONSTANT(Dev, Dp);
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void k_step_persistent(const Dev *Dp, StepA
   for (int l = 0; l < L; ++l) {
     ctl = pstep_qkv<DT>(Dp, A, l, ctl, l ? ++k : 0, lds);
     const bool river = ctl & 1;
-    pstep_attn<DT>(Dp, A, l, ctl, ++k, lds);
+    pstep_attn<DT, F16>(Dp, A, l, ctl, ++k, lds);
     pstep_gemv<DT, PH_O>(Dp, A, l, river, ++k, lds);
     pstep_gemv<DT, PH_GU>(Dp, A, l, river, ++k, lds);
     pstep_gemv<DT, PH_DOWN>(Dp, A, l, river, ++k, lds);
@@ -381,6 +383,8 @@ static bool valid_cfg(const river_config *c, std::string *why) {
   if (c->exec_mode == RIVER_EXEC_PERSISTENT && c->dtype != RIVER_BF16)
     return bad("RIVER_EXEC_PERSISTENT is available for RIVER_BF16 only; use RIVER_EXEC_KERNELS for RIVER_F32");
   if (c->spin_limit < 0) return bad("negative spin_limit");
+  if (c->kv_dtype != RIVER_KV_SAME && c->kv_dtype != RIVER_KV_F16) return bad("bad kv_dtype");
+  if (c->kv_dtype == RIVER_KV_F16 && c->dtype != RIVER_BF16) return bad("RIVER_KV_F16 needs RIVER_BF16 weights");
   if (!(c->rope_base > 0.f) || !(c->rms_eps >= 0.f)) return bad("bad rope_base / rms_eps");
   if (c->max_batch > 1) {
     if (!gemm_prefill_ok(c))
@@ -642,6 +646,7 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
   D.L = L; D.d = cfg->d_model; D.nq = cfg->n_q_heads; D.nkv = cfg->n_kv_heads; D.hd = cfg->head_dim;
   D.ffn = cfg->d_ffn; D.vocab = cfg->vocab; D.max_seq = cfg->max_seq; D.min_exit = cfg->min_exit_layer;
   D.group = cfg->river_group;
+  D.kv_f16 = cfg->kv_dtype == RIVER_KV_F16 ? 1 : 0;
   D.spin_limit = cfg->spin_limit > 0 ? cfg->spin_limit : (1 << 22);
   D.xcap = x_capacity(cfg);
   D.eps = cfg->rms_eps; D.tau = cfg->tau;
@@ -745,10 +750,12 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
   {
     const int lb = (int)x->lds_bytes;
     const void *fns[] = {
-        (const void *)k_qkv<0>, (const void *)k_qkv<1>, (const void *)k_attn<0>, (const void *)k_attn<1>,
+        (const void *)k_qkv<0>, (const void *)k_qkv<1>, (const void *)k_attn<0, false>,
+        (const void *)k_attn<1, false>, (const void *)k_attn<1, true>,
         (const void *)k_oproj<0>, (const void *)k_oproj<1>, (const void *)k_gateup<0>,
         (const void *)k_gateup<1>, (const void *)k_down<0>, (const void *)k_down<1>,
-        (const void *)k_head<0>, (const void *)k_head<1>, (const void *)k_step_persistent<1>};
+        (const void *)k_head<0>, (const void *)k_head<1>, (const void *)k_step_persistent<1, false>,
+        (const void *)k_step_persistent<1, true>};
     for (const void *f : fns)
       if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lb)) != hipSuccess)
         return fail("hipFuncSetAttribute(max dynamic LDS)", e);
@@ -782,7 +789,8 @@ static int launch_step(river_ctx *x, const StepArgs &A0) {
     // bf16 only (river_create refuses the combination with fp32)
     if constexpr (DT == 1) {
       A.bar_base = x->bar_total;
-      k_step_persistent<DT><<<dim3(x->grid_persist), blk, lds, s>>>(Dp, A);
+      if (D.kv_f16) k_step_persistent<DT, true><<<dim3(x->grid_persist), blk, lds, s>>>(Dp, A);
+      else k_step_persistent<DT, false><<<dim3(x->grid_persist), blk, lds, s>>>(Dp, A);
       x->bar_total += 5ull * D.L - 1 + (A.want_head ? 1 : 0);
     } else {
       x->err = "RIVER_EXEC_PERSISTENT is available for RIVER_BF16 only";
@@ -792,7 +800,8 @@ static int launch_step(river_ctx *x, const StepArgs &A0) {
     const dim3 gg(x->grid_gemv);
     for (int l = 0; l < D.L; ++l) {
       k_qkv<DT><<<gg, blk, lds, s>>>(Dp, A, l);
-      k_attn<DT><<<gg, blk, lds, s>>>(Dp, A, l);
+      if (DT == 1 && D.kv_f16) k_attn<DT, DT == 1><<<gg, blk, lds, s>>>(Dp, A, l);
+      else k_attn<DT, false><<<gg, blk, lds, s>>>(Dp, A, l);
       k_oproj<DT><<<gg, blk, lds, s>>>(Dp, A, l);
       k_gateup<DT><<<gg, blk, lds, s>>>(Dp, A, l);
       k_down<DT><<<gg, blk, lds, s>>>(Dp, A, l);
@@ -890,13 +899,13 @@ static int prefill_gemm(river_ctx *x, int seq, const int32_t *tokens, int n, int
       if (river) launch_gemm<true, false>(x, l, m_qkv, 3, x16, d, big, rows);
       else launch_gemm<false, false>(x, l, m_qkv, 3, x16, d, big, rows);
       pf::k_pf_rope_store<<<dim3(m), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, c0, l,
-                                                        c.max_seq, kc, vc, q16);
+                                                        c.max_seq, kc, vc, D.kv_f16, q16);
       const dim3 ga(c.n_q_heads, (m + 127) / 128);
       if (c.head_dim == 128)
-        pf::k_pf_attn<128><<<ga, dim3(256), 0, s>>>(q16, kc, vc, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
+        pf::k_pf_attn<128><<<ga, dim3(256), 0, s>>>(q16, kc, vc, D.kv_f16, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
                                                     c0, m, x16);
       else
-        pf::k_pf_attn<64><<<ga, dim3(256), 0, s>>>(q16, kc, vc, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
+        pf::k_pf_attn<64><<<ga, dim3(256), 0, s>>>(q16, kc, vc, D.kv_f16, c.n_q_heads, c.n_kv_heads, l, c.max_seq,
                                                    c0, m, x16);
       if (river) launch_gemm<true, true>(x, l, m_o, 1, x16, qd, h, rows);
       else launch_gemm<false, true>(x, l, m_o, 1, x16, qd, h, rows);
@@ -1092,13 +1101,13 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
     launch_bd_gemm<false, false>(x, l, m_qkv, 3, x16, d, big, 0, n);
     if (rv && W.qc[M_WQ]) launch_bd_gemm<true, false>(x, l, m_qkv, 3, x16, d, big, 1, n);
     bd::k_bd_rope_store<<<dim3(n), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, st.pos, l,
-                                                      c.max_seq, seq_stride, D.kcache, D.vcache, qf);
+                                                      c.max_seq, seq_stride, D.kcache, D.vcache, D.kv_f16, qf);
     const dim3 ga(c.n_q_heads, n);
     if (c.head_dim == 128)
-      bd::k_bd_attn<128><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l,
+      bd::k_bd_attn<128><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, D.kv_f16, c.n_q_heads, c.n_kv_heads, l,
                                                          c.max_seq, seq_stride, st.pos, o16);
     else
-      bd::k_bd_attn<64><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, l,
+      bd::k_bd_attn<64><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, D.kv_f16, c.n_q_heads, c.n_kv_heads, l,
                                                         c.max_seq, seq_stride, st.pos, o16);
     launch_bd_gemm<false, true>(x, l, m_o, 1, o16, qd, h, 0, n);
     if (rv && W.qc[M_WO]) launch_bd_gemm<true, true>(x, l, m_o, 1, o16, qd, h, 1, n);

@@ -50,6 +50,7 @@ struct DevState {
 
 struct Dev {
   int L, d, nq, nkv, hd, ffn, vocab, max_seq, min_exit, group, spin_limit;
+  int kv_f16;                     // the KV cache of a bf16 model holds IEEE half values instead of bf16
   int bar_vector_poll;            // the barrier block is ordinary (cached) device memory: poll it with vector loads
   int xcap;                       // floats of LDS reserved for the staged input vector
   float eps, tau;
@@ -1223,9 +1224,13 @@ template <int DT, int EL> struct KV {                  // raw cache words of one
 #pragma unroll
     for (int i = 0; i < NW; ++i) w[i] = 0;
   }
-  // round EL values to the cache dtype (nearest even)
+  // round EL values to the cache's storage type (nearest even); F16: IEEE half in a 16-bit cache
+  template <bool F16 = false>
   __device__ __forceinline__ void from(const float (&f)[EL]) {
-    if constexpr (DT == 1) {
+    if constexpr (DT == 1 && F16) {
+#pragma unroll
+      for (int i = 0; i < NW; ++i) w[i] = pack_half2(f[2 * i], f[2 * i + 1]);
+    } else if constexpr (DT == 1) {
 #pragma unroll
       for (int i = 0; i < NW; ++i)
         w[i] = (uint32_t)Store<1>::rne(f[2 * i]) | ((uint32_t)Store<1>::rne(f[2 * i + 1]) << 16);
@@ -1242,8 +1247,16 @@ template <int DT, int EL> struct KV {                  // raw cache words of one
       for (int i = 0; i < NW; i += 4) *(uint4 *)(p + i * 4) = make_uint4(w[i], w[i + 1], w[i + 2], w[i + 3]);
     }
   }
+  template <bool F16 = false>
   __device__ __forceinline__ void unpack(float (&f)[EL]) const {
-    if constexpr (DT == 1) {
+    if constexpr (DT == 1 && F16) {
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+        f[2 * i] = (float)h[0];
+        f[2 * i + 1] = (float)h[1];
+      }
+    } else if constexpr (DT == 1) {
 #pragma unroll
       for (int i = 0; i < NW; ++i) {
         f[2 * i] = __uint_as_float(w[i] << 16);
@@ -1391,7 +1404,7 @@ __device__ __forceinline__ void stage_attn_out(DevRef D, const StepArgs &A, int 
   lds_barrier();
 }
 
-template <int DT, int EL>
+template <int DT, int EL, bool F16>
 __device__ __forceinline__ void attn_items(DevRef D, const StepArgs &A, int l, float *lds, int lane,
                                            AttnPre<DT, EL> &c) {
   typedef AttnShape<DT, EL> SH;
@@ -1441,8 +1454,8 @@ __device__ __forceinline__ void attn_items(DevRef D, const StepArgs &A, int l, f
     if (own) {
       rope_rotate<EL>(kf0, c.cs, dl >= 8);
       KV<DT, EL> tk, tv;
-      tk.from(kf0); tk.unpack(kf0);
-      tv.from(vf0); tv.unpack(vf0);
+      tk.template from<F16>(kf0); tk.template unpack<F16>(kf0);
+      tv.template from<F16>(vf0); tv.template unpack<F16>(vf0);
       if (it.h % (D.nq / D.nkv) == 0) {
         // byte offset of this lane's elements in cache slot (l, pos) of the kv head
         const size_t slot_off = (((size_t)l * D.max_seq + A.pos) * kvd + (size_t)it.kvh * hd + dl * EL) *
@@ -1468,7 +1481,7 @@ __device__ __forceinline__ void attn_items(DevRef D, const StepArgs &A, int l, f
         const int p = pbase + u * NENT + slot;
         const bool ok = p < it.p1 && p != A.pos;       // the own position is already in (m, ls, o)
         float kf[EL];
-        ck.k[u].unpack(kf);
+        ck.k[u].template unpack<F16>(kf);
         float d = 0.f;
 #pragma unroll
         for (int e = 0; e < EL; ++e) d = fmaf(q[e], kf[e], d);
@@ -1486,7 +1499,7 @@ __device__ __forceinline__ void attn_items(DevRef D, const StepArgs &A, int l, f
         const float pg = sc[u] > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(sc[u] - mn) : 0.f;
         ls += pg;
         float vf[EL];
-        ck.v[u].unpack(vf);
+        ck.v[u].template unpack<F16>(vf);
 #pragma unroll
         for (int e = 0; e < EL; ++e) o[e] = fmaf(pg, vf[e], o[e]);
       }
@@ -1556,7 +1569,7 @@ __device__ __forceinline__ void attn_items(DevRef D, const StepArgs &A, int l, f
 // phase mode arrive and wait do nothing): what can be fetched ahead is issued between
 // arriving and waiting.  Register arrays are sized by the elements per lane (head_dim 64
 // or 128).
-template <int DT, class Arrive, class Wait>
+template <int DT, bool F16, class Arrive, class Wait>
 __device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, const Ctl &ctl, float *lds,
                                            Arrive arrive, Wait wait) {
   const int lane = fresh_lane();
@@ -1566,7 +1579,7 @@ __device__ __forceinline__ void phase_attn(DevRef D, const StepArgs &A, int l, c
     arrive();
     attn_prefetch<DT, EL>(D, A, l, blockIdx.x, lane, c);
     wait();
-    attn_items<DT, EL>(D, A, l, lds, lane, c);
+    attn_items<DT, EL, F16>(D, A, l, lds, lane, c);
   };
   if (D.hd == 128) run(IC<8>()); else run(IC<4>());
   lds_barrier();                                   // the merge area of the last item is read

@@ -53,6 +53,22 @@ __device__ __forceinline__ half8 bf16x8_to_half8(const uint4 &w) {
   return h;
 }
 
+// A 16-bit KV cache holds bf16 values, or IEEE half values when the context keeps its cache in
+// FP16 (kv_f16): store one element / fetch eight as fp16 / fetch one as fp32.
+__device__ __forceinline__ void cache_store(void *cache, size_t i, float v, int kv_f16) {
+  if (kv_f16) ((_Float16 *)cache)[i] = (_Float16)v;
+  else Store<1>::st(cache, i, v);
+}
+__device__ __forceinline__ half8 cache_half8(const uint4 &w, int kv_f16) {
+  return kv_f16 ? __builtin_bit_cast(half8, w) : bf16x8_to_half8(w);
+}
+__device__ __forceinline__ float cache_lo(uint32_t w, int kv_f16) {
+  return kv_f16 ? (float)__builtin_bit_cast(half2v, w)[0] : bf16_lo(w);
+}
+__device__ __forceinline__ float cache_hi(uint32_t w, int kv_f16) {
+  return kv_f16 ? (float)__builtin_bit_cast(half2v, w)[1] : bf16_hi(w);
+}
+
 // ------------------------------------------------------------------ GEMM
 //
 // C[M, N] (+)= A[M, K] B^T, B = up to three matrices stacked along N (rows of W_q, W_k, W_v;
@@ -232,7 +248,8 @@ __global__ __launch_bounds__(256) void k_pf_rmsnorm(const float *__restrict__ h,
 // (l, pos0 + t) of the shared cache.  qkv: fp32 [m, qd + 2 kvd] as the QKV GEMM left it.
 // One workgroup per token; thread i handles rotation pair (i, i + hd/2) of one head.
 __global__ void k_pf_rope_store(const float *__restrict__ qkv, const float2 *__restrict__ rope, int nq, int nkv,
-                                int hd, int pos0, int l, int max_seq, void *kcache, void *vcache, _Float16 *q16) {
+                                int hd, int pos0, int l, int max_seq, void *kcache, void *vcache, int kv_f16,
+                                _Float16 *q16) {
   const int t = blockIdx.x, p = pos0 + t, half = hd >> 1;
   const int qd = nq * hd, kvd = nkv * hd, ld = qd + 2 * kvd;
   const float *row = qkv + (size_t)t * ld;
@@ -248,12 +265,12 @@ __global__ void k_pf_rope_store(const float *__restrict__ qkv, const float2 *__r
       q16[(size_t)t * qd + head * hd + e + half] = (_Float16)(hi * qs);
     } else {
       const size_t o = ((size_t)l * max_seq + p) * kvd + (size_t)(head - nq) * hd;
-      Store<1>::st(kcache, o + e, lo);
-      Store<1>::st(kcache, o + e + half, hi);
+      cache_store(kcache, o + e, lo, kv_f16);
+      cache_store(kcache, o + e + half, hi, kv_f16);
     }
   }
   for (int i = threadIdx.x; i < kvd; i += blockDim.x)
-    Store<1>::st(vcache, ((size_t)l * max_seq + p) * kvd + i, row[qd + kvd + i]);
+    cache_store(vcache, ((size_t)l * max_seq + p) * kvd + i, row[qd + kvd + i], kv_f16);
 }
 
 // a16[t, i] = fp16(silu(G[t, i]) * U[t, i]); gu: fp32 [m, 2 ffn], gate columns first
@@ -287,8 +304,8 @@ __global__ void k_pf_copy_row(const float *__restrict__ src, float *dst, int d) 
 // The scores carry log2(e)/sqrt(hd) (folded into q16): base-2 online softmax.
 template <int HD>
 __global__ __launch_bounds__(256) void k_pf_attn(const _Float16 *__restrict__ q16, const void *kcache,
-                                                 const void *vcache, int nq, int nkv, int l, int max_seq, int pos0,
-                                                 int m, _Float16 *o16) {
+                                                 const void *vcache, int kv_f16, int nq, int nkv, int l, int max_seq,
+                                                 int pos0, int m, _Float16 *o16) {
   constexpr int LDH = HD + 8;                 // K tile row stride (halfs)
   constexpr int LDV = 64 + 8;                 // V^T tile row stride (halfs)
   __shared__ __attribute__((aligned(16))) _Float16 Ks[64 * LDH];
@@ -326,13 +343,13 @@ __global__ __launch_bounds__(256) void k_pf_attn(const _Float16 *__restrict__ q1
       const int key = seg / (HD / 8), ds = seg % (HD / 8);
       const int p = min(kt + key, last_pos);
       const uint4 kw = *(const uint4 *)((const char *)kcache + (cbase + (size_t)p * kvd + ds * 8) * 2);
-      *(half8 *)(Ks + key * LDH + ds * 8) = bf16x8_to_half8(kw);
+      *(half8 *)(Ks + key * LDH + ds * 8) = cache_half8(kw, kv_f16);
     }
     for (int seg = tid; seg < 64 * (HD / 8); seg += 256) {
       const int key = seg & 63, ds = seg >> 6;
       const int p = min(kt + key, last_pos);
       const uint4 vw = *(const uint4 *)((const char *)vcache + (cbase + (size_t)p * kvd + ds * 8) * 2);
-      const half8 vh = bf16x8_to_half8(vw);
+      const half8 vh = cache_half8(vw, kv_f16);
 #pragma unroll
       for (int e = 0; e < 8; ++e) Vt[(ds * 8 + e) * LDV + key] = vh[e];
     }
@@ -636,7 +653,7 @@ __global__ void k_bd_copy(const float *__restrict__ src, float *dst, size_t n) {
 // rounded to the cache dtype into slot (seq b, block l, pos[b]) of the shared cache.
 __global__ void k_bd_rope_store(const float *__restrict__ qkv, const float2 *__restrict__ rope, int nq, int nkv,
                                 int hd, const int *__restrict__ pos, int l, int max_seq, size_t seq_stride,
-                                void *kcache, void *vcache, float *qf) {
+                                void *kcache, void *vcache, int kv_f16, float *qf) {
   const int b = blockIdx.x, p = pos[b], half = hd >> 1;
   const int qd = nq * hd, kvd = nkv * hd, ld = qd + 2 * kvd;
   const float *row = qkv + (size_t)b * ld;
@@ -652,11 +669,11 @@ __global__ void k_bd_rope_store(const float *__restrict__ qkv, const float2 *__r
       qf[(size_t)b * qd + head * hd + e] = lo * qs;
       qf[(size_t)b * qd + head * hd + e + half] = hi * qs;
     } else {
-      Store<1>::st(kcache, slot + (size_t)(head - nq) * hd + e, lo);
-      Store<1>::st(kcache, slot + (size_t)(head - nq) * hd + e + half, hi);
+      cache_store(kcache, slot + (size_t)(head - nq) * hd + e, lo, kv_f16);
+      cache_store(kcache, slot + (size_t)(head - nq) * hd + e + half, hi, kv_f16);
     }
   }
-  for (int i = threadIdx.x; i < kvd; i += blockDim.x) Store<1>::st(vcache, slot + i, row[qd + kvd + i]);
+  for (int i = threadIdx.x; i < kvd; i += blockDim.x) cache_store(vcache, slot + i, row[qd + kvd + i], kv_f16);
 }
 
 // Single-query attention of sequence b = blockIdx.y, query head blockIdx.x, over its cache
@@ -669,7 +686,7 @@ __global__ void k_bd_rope_store(const float *__restrict__ qkv, const float2 *__r
 __host__ __device__ inline size_t attn_lds_bytes(int max_seq) { return ((size_t)max_seq + 32 + 16 * 128 + 32) * 4; }
 template <int HD>
 __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, const void *kcache, const void *vcache,
-                                                 int nq, int nkv, int l, int max_seq, size_t seq_stride,
+                                                 int kv_f16, int nq, int nkv, int l, int max_seq, size_t seq_stride,
                                                  const int *__restrict__ pos, _Float16 *o16) {
   constexpr int EL = HD / 16;                                  // elements per lane of a cached row
   extern __shared__ float sm[];
@@ -685,11 +702,13 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, c
     const char *p = (const char *)cache + (base + (size_t)j * kvd) * 2;
     if constexpr (EL == 8) {
       const uint4 w = *(const uint4 *)p;
-      f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x); f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
-      f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z); f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
+      f[0] = cache_lo(w.x, kv_f16); f[1] = cache_hi(w.x, kv_f16); f[2] = cache_lo(w.y, kv_f16);
+      f[3] = cache_hi(w.y, kv_f16); f[4] = cache_lo(w.z, kv_f16); f[5] = cache_hi(w.z, kv_f16);
+      f[6] = cache_lo(w.w, kv_f16); f[7] = cache_hi(w.w, kv_f16);
     } else {
       const uint2 w = *(const uint2 *)p;
-      f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x); f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
+      f[0] = cache_lo(w.x, kv_f16); f[1] = cache_hi(w.x, kv_f16); f[2] = cache_lo(w.y, kv_f16);
+      f[3] = cache_hi(w.y, kv_f16);
     }
   };
   float mx = -1.0e30f;

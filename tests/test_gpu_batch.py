@@ -216,3 +216,19 @@ def test_batch_api_errors_and_partial_batches():
         binding.River(configs.TINY.with_(dtype=configs.DTYPE_BF16), binding.upload_weights(
             inputs.make_weights(configs.TINY.with_(dtype=configs.DTYPE_BF16), 3)), None, max_batch=2)
     assert ei.value.code == binding.RIVER_EINVAL
+
+
+def test_batch_fp16_kv_cache():
+    cfg = HD64B.with_(kv_dtype=configs.KV_F16)
+    say("batched decode, fp16 KV cache")
+    B = Batch(cfg, 3, [9, 40, 70], 221)
+    for step in range(4):
+        forced = [1 + (step + b) % cfg.n_layers for b in range(3)]
+        got = B.g.decode_batch(3, B.toks, forced)
+        res = [o.decode_step(t, f) for o, t, f in zip(B.os, B.toks, forced)]
+        hid = np.array([o.hidden() for o in B.os]).transpose(1, 0, 2)
+        B.compare([r[0] for r in res], [r[1] for r in res], [r[2] for r in res], hid,
+                  [o.logits() for o in B.os], got, f"fp16 cache step {step}")
+        B.toks = [r[0] for r in res]
+    B.compare_caches()
+    B.close()

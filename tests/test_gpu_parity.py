@@ -665,3 +665,28 @@ def test_backbone_offloading_reads_deep_blocks_from_pinned_host_memory(mode):
         assert e2 == eo
     g2.close()
     pair.close()
+
+
+# ------------------------------------------------------------------ FP16 KV cache
+
+@pytest.mark.parametrize("mode", MODES, ids=MODE_IDS)
+@pytest.mark.parametrize("cfg0", [TINY_BF16, MID, MANY_HEADS], ids=lambda c: c.name)
+def test_fp16_kv_cache(mode, cfg0):
+    """KV cache in IEEE half (the paper's cache type) under bf16 weights: decode attention at
+    both head sizes, the per-position and the MFMA prefill, several splits; cache compared as
+    half values with the oracle's."""
+    say(f"fp16 KV cache {cfg0.name} mode={mode}")
+    cfg = cfg0.with_(min_exit_layer=0, kv_dtype=configs.KV_F16, max_seq=700)
+    w = inputs.make_weights(cfg, 97, gain_std=0.05)
+    L = cfg.n_layers
+    for n_prompt, gemm in ((9, -1), (600, 1)):
+        if gemm == 1 and cfg.d_ffn % 64:
+            gemm = -1
+        pair = Pair(cfg, w, mode, prefill_gemm_min_tokens=gemm)
+        tok = pair.prefill(inputs.make_prompt(cfg.vocab, n_prompt, 98), L if n_prompt == 9 else 1)
+        for i, e in enumerate((L, 0, 1, L - 1)):
+            tok, _, _ = pair.step(tok, e, what=f"fp16 cache {cfg.name} prompt {n_prompt} step {i}")
+        pair.compare_cache(n_prompt + 4)
+        kg = pair.g.kcache()[:, :n_prompt + 4]
+        assert np.array_equal(kg, kg.astype(np.float16).astype(np.float32))
+        pair.close()
