@@ -1102,13 +1102,12 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
     if (rv && W.qc[M_WQ]) launch_bd_gemm<true, false>(x, l, m_qkv, 3, x16, d, big, 1, n);
     bd::k_bd_rope_store<<<dim3(n), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, st.pos, l,
                                                       c.max_seq, seq_stride, D.kcache, D.vcache, D.kv_f16, qf);
-    const dim3 ga(c.n_q_heads, n);
-    if (c.head_dim == 128)
-      bd::k_bd_attn<128><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, D.kv_f16, c.n_q_heads, c.n_kv_heads, l,
-                                                         c.max_seq, seq_stride, st.pos, o16);
-    else
-      bd::k_bd_attn<64><<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, D.kv_f16, c.n_q_heads, c.n_kv_heads, l,
-                                                        c.max_seq, seq_stride, st.pos, o16);
+    const int rep = c.n_q_heads / c.n_kv_heads;
+    const dim3 ga((n * c.n_kv_heads + 7) / 8 * 8 * rep);
+    auto attn = c.head_dim == 128 ? (D.kv_f16 ? bd::k_bd_attn<128, true> : bd::k_bd_attn<128, false>)
+                                  : (D.kv_f16 ? bd::k_bd_attn<64, true> : bd::k_bd_attn<64, false>);
+    attn<<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq, seq_stride,
+                                         st.pos, o16);
     launch_bd_gemm<false, true>(x, l, m_o, 1, o16, qd, h, 0, n);
     if (rv && W.qc[M_WO]) launch_bd_gemm<true, true>(x, l, m_o, 1, o16, qd, h, 1, n);
     pf::k_pf_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);

@@ -676,7 +676,7 @@ __global__ void k_bd_rope_store(const float *__restrict__ qkv, const float2 *__r
   for (int i = threadIdx.x; i < kvd; i += blockDim.x) cache_store(vcache, slot + i, row[qd + kvd + i], kv_f16);
 }
 
-// Single-query attention of sequence b = blockIdx.y, query head blockIdx.x, over its cache
+// Single-query attention, one workgroup per (sequence, query head), over the sequence's cache
 // positions 0 .. pos[b].  Sixteen lanes share a cached row (HD/16 elements each, one 16- or
 // 8-byte load), so a wavefront load covers four positions with whole rows; the workgroup's 16
 // lane groups stride over the positions.  Pass 1: scores (DPP row sums) to LDS and the block
@@ -684,14 +684,20 @@ __global__ void k_bd_rope_store(const float *__restrict__ qkv, const float2 *__r
 // positions' value rows, the 16 partial vectors are summed in group order.
 // Dynamic LDS: attn_lds_bytes(max_seq).
 __host__ __device__ inline size_t attn_lds_bytes(int max_seq) { return ((size_t)max_seq + 32 + 16 * 128 + 32) * 4; }
-template <int HD>
+template <int HD, bool KV_F16>
 __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, const void *kcache, const void *vcache,
-                                                 int kv_f16, int nq, int nkv, int l, int max_seq, size_t seq_stride,
-                                                 const int *__restrict__ pos, _Float16 *o16) {
+                                                 int nq, int nkv, int n_seq, int l, int max_seq,
+                                                 size_t seq_stride, const int *__restrict__ pos, _Float16 *o16) {
   constexpr int EL = HD / 16;                                  // elements per lane of a cached row
   extern __shared__ float sm[];
   float *red = sm, *part = sm + 32, *sc = sm + 32 + 16 * 128;
-  const int b = blockIdx.y, h = blockIdx.x, kvh = h / (nq / nkv), tid = threadIdx.x;
+  // Workgroup index -> (sequence, kv head, query head of its group) such that the query heads
+  // that share a kv head run on the same XCD (consecutive workgroup ids go round the 8 XCDs) and
+  // their reads of the same K/V rows meet in that XCD's L2.
+  const int rep = nq / nkv, tid = threadIdx.x;
+  const int i = blockIdx.x, g = (i / (8 * rep)) * 8 + (i & 7), r = (i % (8 * rep)) >> 3;
+  if (g >= n_seq * nkv) return;
+  const int b = g / nkv, kvh = g % nkv, h = kvh * rep + r;
   const int grp = tid >> 4, dl = tid & 15;
   const int T = pos[b] + 1, qd = nq * HD, kvd = nkv * HD;
   const size_t base = (size_t)b * seq_stride + (size_t)l * max_seq * kvd + (size_t)kvh * HD + dl * EL;
@@ -702,25 +708,33 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, c
     const char *p = (const char *)cache + (base + (size_t)j * kvd) * 2;
     if constexpr (EL == 8) {
       const uint4 w = *(const uint4 *)p;
-      f[0] = cache_lo(w.x, kv_f16); f[1] = cache_hi(w.x, kv_f16); f[2] = cache_lo(w.y, kv_f16);
-      f[3] = cache_hi(w.y, kv_f16); f[4] = cache_lo(w.z, kv_f16); f[5] = cache_hi(w.z, kv_f16);
-      f[6] = cache_lo(w.w, kv_f16); f[7] = cache_hi(w.w, kv_f16);
+      f[0] = cache_lo(w.x, KV_F16); f[1] = cache_hi(w.x, KV_F16); f[2] = cache_lo(w.y, KV_F16);
+      f[3] = cache_hi(w.y, KV_F16); f[4] = cache_lo(w.z, KV_F16); f[5] = cache_hi(w.z, KV_F16);
+      f[6] = cache_lo(w.w, KV_F16); f[7] = cache_hi(w.w, KV_F16);
     } else {
       const uint2 w = *(const uint2 *)p;
-      f[0] = cache_lo(w.x, kv_f16); f[1] = cache_hi(w.x, kv_f16); f[2] = cache_lo(w.y, kv_f16);
-      f[3] = cache_hi(w.y, kv_f16);
+      f[0] = cache_lo(w.x, KV_F16); f[1] = cache_hi(w.x, KV_F16); f[2] = cache_lo(w.y, KV_F16);
+      f[3] = cache_hi(w.y, KV_F16);
     }
   };
+  // eight rows of the lane group in flight at a time (positions beyond T read row T - 1 again)
   float mx = -1.0e30f;
-  for (int j = grp; j < T; j += 16) {
-    float kf[EL];
-    row(kcache, j, kf);
-    float dot = 0.f;
+  for (int j0 = grp; j0 < T; j0 += 16 * 8) {
+    float kf[8][EL];
 #pragma unroll
-    for (int e = 0; e < EL; ++e) dot = fmaf(kf[e], q[e], dot);
-    dot = row16_sum(dot);
-    if (dl == 0) sc[j] = dot;
-    mx = fmaxf(mx, dot);
+    for (int u = 0; u < 8; ++u) row(kcache, min(j0 + 16 * u, T - 1), kf[u]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + 16 * u;
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) dot = fmaf(kf[u][e], q[e], dot);
+      dot = row16_sum(dot);
+      if (j < T) {
+        if (dl == 0) sc[j] = dot;
+        mx = fmaxf(mx, dot);
+      }
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
@@ -738,12 +752,17 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, c
   float acc[EL];
 #pragma unroll
   for (int e = 0; e < EL; ++e) acc[e] = 0.f;
-  for (int j = grp; j < T; j += 16) {
-    float vf[EL];
-    row(vcache, j, vf);
-    const float p = sc[j];
+  for (int j0 = grp; j0 < T; j0 += 16 * 8) {
+    float vf[8][EL];
 #pragma unroll
-    for (int e = 0; e < EL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+    for (int u = 0; u < 8; ++u) row(vcache, min(j0 + 16 * u, T - 1), vf[u]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + 16 * u;
+      const float p = j < T ? sc[j] : 0.f;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) acc[e] = fmaf(p, vf[u][e], acc[e]);
+    }
   }
 #pragma unroll
   for (int e = 0; e < EL; ++e) part[grp * HD + dl * EL + e] = acc[e];

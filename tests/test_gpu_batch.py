@@ -232,3 +232,21 @@ def test_batch_fp16_kv_cache():
         B.toks = [r[0] for r in res]
     B.compare_caches()
     B.close()
+
+
+def test_batch_of_twenty_sequences_two_row_blocks():
+    """More than 16 sequences: the batched GEMM runs with two 16-row MFMA blocks per tile."""
+    cfg = HD64B.with_(n_layers=2, max_seq=64)
+    say("batched decode, 20 sequences")
+    B = Batch(cfg, 20, [3 + (7 * b) % 23 for b in range(20)], 231)
+    rng = np.random.default_rng(9)
+    for step in range(3):
+        forced = [int(rng.integers(1, 3)) for _ in range(20)]
+        got = B.g.decode_batch(20, B.toks, forced)
+        res = [o.decode_step(t, f) for o, t, f in zip(B.os, B.toks, forced)]
+        hid = np.array([o.hidden() for o in B.os]).transpose(1, 0, 2)
+        B.compare([r[0] for r in res], [r[1] for r in res], [r[2] for r in res], hid,
+                  [o.logits() for o in B.os], got, f"20 sequences step {step}")
+        B.toks = [r[0] for r in res]
+    B.compare_caches()
+    B.close()
