@@ -491,20 +491,40 @@ __device__ __forceinline__ half8 dequant8(uint32_t w, half2v sc2, half2v nzh2, h
   return out;
 }
 
-// C[rows, N] (+)= A[rows, K] B^T for the rows r < n_rows with river[r] == want (want < 0: all
+// C[rows, N] (op)= A[rows, K] B^T for the rows r < n_rows with river[r] == want (want < 0: all
 // rows); nothing is read if there is none.  MB = 1: up to 16 rows, MB = 2: up to 32.
-// Workgroup = four wavefronts on one (16 MB) x 16 tile of C, each wavefront taking every
-// fourth 64-column K tile through its own LDS buffers, four tiles in flight in registers; the
-// four partial tiles are summed in wavefront order.  N / 16 workgroups: at least one per CU
-// for every matrix of the 8B shape, so all CUs stream weights.
-template <bool W4, bool ADD, int MB>
-__global__ __launch_bounds__(256) void k_bd_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int N, int K,
-                                                 int group, float *C, int ldc, const int *__restrict__ river,
-                                                 int want, int n_rows) {
-  constexpr int RM = 16 * MB;                                 // rows of the tile
-  constexpr int NT = 4;                                       // K tiles in flight per wavefront
-  __shared__ __attribute__((aligned(16))) _Float16 As[4][RM * LDK];
-  __shared__ __attribute__((aligned(16))) _Float16 Bs[4][16 * LDK];
+//
+// The weights are read once, so the kernel is a weight stream with the matrix cores doing the
+// arithmetic.  Workgroup = eight wavefronts on `rows_per_wg` consecutive rows of B (a multiple
+// of 8, chosen by the host so that the rows divide evenly over the CUs), taken in passes of
+// RBW blocks of 16 rows; rows of a block beyond the workgroup's range are not loaded.  The
+// wavefronts split K: wavefront w takes every eighth K tile (64 columns dense, 128 columns of
+// 4-bit codes).  A lane loads its MFMA operands directly in the layout the instruction wants --
+// no LDS on the way: for B, lane (n = lane % 16, g = lane / 16) fetches 16 bytes of row n (dense:
+// columns k0 + 32 s + 8 g .. + 7 for the tile's two steps s; codes: the 32 columns
+// k0 + 32 g .. + 31, one step per code word, which lie in one quantisation group), for A the
+// same columns of sequence row n (fp16, from the L2: the activation tile is small and every
+// workgroup reads all of it once per K tile, shared by its RBW row blocks).  P tiles are in flight per
+// wavefront in registers.  The eight partial tiles are summed in wavefront order through LDS.
+// op (epi): store fp32, add into fp32, or -- with B's rows interleaved as (gate i, up i) --
+// silu(gate) * up stored as fp16 (the activation of the down projection).
+enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
+constexpr int kBdWaves = 8;
+template <int RBW, int MB> struct BdDepth {                 // K tiles in flight per wavefront (register budget)
+  static constexpr int dense = MB == 1 ? (RBW == 1 ? 8 : RBW == 2 ? 5 : 2) : (RBW == 1 ? 5 : 3);
+  static constexpr int w4 = MB == 1 ? (RBW == 1 ? 6 : RBW == 2 ? 4 : 2) : (RBW == 1 ? 4 : 3);
+};
+__host__ __device__ inline size_t bd_gemm_lds_bytes(int rbw, int mb) { return (size_t)kBdWaves * rbw * mb * 256 * 4; }
+
+template <bool W4, int MB, int RBW>
+__global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int interleaved,
+                                                 int N, int K, int group, void *C, int ldc, int epi,
+                                                 const int *__restrict__ river, int want, int n_rows,
+                                                 int rows_per_wg) {
+  constexpr int P = W4 ? BdDepth<RBW, MB>::w4 : BdDepth<RBW, MB>::dense;
+  constexpr int TILE = W4 ? 128 : 64;                         // columns per K tile
+  constexpr int NA = W4 ? 4 : 2;                              // MFMA steps (16-byte A fragments) per tile
+  extern __shared__ float red[];                              // [kBdWaves][RBW][MB][256]
   __shared__ int any;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   if (tid == 0) any = 0;
@@ -512,115 +532,130 @@ __global__ __launch_bounds__(256) void k_bd_gemm(const _Float16 *__restrict__ A,
   if (tid < n_rows && (want < 0 || river[tid] == want)) any = 1;
   __syncthreads();
   if (!any) return;
-  const int n0 = blockIdx.x * 16;
-  // per K tile a lane stages 2 MB 16-byte segments of A and, of B, two 16-byte segments (dense)
-  // or one 8-byte run of 16 codes with the (scale, zero) pair of its row (river)
-  const char *a_src[2 * MB];
-  int a_dst[2 * MB];
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int wg_r0 = blockIdx.x * rows_per_wg, wg_r1 = min(N, wg_r0 + rows_per_wg);
+  const int nkt = (K + TILE - 1) / TILE;
+  // this lane's column offset inside a K tile (elements) and its A rows
+  const int kl = W4 ? kg * 32 : kg * 8;
+  const _Float16 *a_row[MB];
 #pragma unroll
-  for (int i = 0; i < 2 * MB; ++i) {
-    const int seg = lane + 64 * i, row = seg >> 3, ks = seg & 7;
-    a_src[i] = (const char *)(A + (size_t)row * lda + ks * 8);
-    a_dst[i] = row * LDK + ks * 8;
-  }
-  const char *b_src[2];
-  const char *b_sz = nullptr;
-  int b_dst[2];
-  if constexpr (W4) {
-    const int row = lane >> 2, qt = lane & 3;
-    int mat, r;
-    gemm_b_row(B, n0 + row, N, mat, r);
-    b_src[0] = (const char *)B.w[mat] + (size_t)r * (K >> 1) + qt * 8;
-    b_sz = (const char *)B.sz[mat] + (size_t)r * (K / group) * 4;
-    b_dst[0] = row * LDK + qt * 16;
-    b_src[1] = nullptr; b_dst[1] = 0;
-  } else {
+  for (int i = 0; i < MB; ++i) a_row[i] = A + (size_t)(i * 16 + r16) * lda + kl;
+  struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint32_t sz[W4 ? RBW : 1]; };
+  for (int p0 = wg_r0; p0 < wg_r1; p0 += RBW * 16) {
+    const char *bp[RBW], *szp[RBW];
+    bool ok[RBW];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int seg = lane + 64 * i, row = seg >> 3, ks = seg & 7;
+    for (int rb = 0; rb < RBW; ++rb) {
+      const int n = p0 + rb * 16 + r16;
+      ok[rb] = n < wg_r1;
       int mat, r;
-      gemm_b_row(B, n0 + row, N, mat, r);
-      b_src[i] = (const char *)B.w[mat] + ((size_t)r * K + ks * 8) * 2;
-      b_dst[i] = row * LDK + ks * 8;
-    }
-  }
-  struct Tile { uint4 a[2 * MB], b[2]; uint32_t sz; };
-  auto load = [&](int kt, Tile &t) {
-    const int k0 = kt * TK;
-#pragma unroll
-    for (int i = 0; i < 2 * MB; ++i) t.a[i] = *(const uint4 *)(a_src[i] + (size_t)k0 * 2);
-    if constexpr (W4) {
-      t.b[0] = ld_stream8(b_src[0] + (k0 >> 1));
-      t.sz = *(const uint32_t *)(b_sz + (size_t)(k0 / group) * 4);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) t.b[i] = ld_stream16(b_src[i] + (size_t)k0 * 2);
-      t.sz = 0;
-    }
-  };
-  _Float16 *as = As[wv], *bs = Bs[wv];
-  auto stage = [&](const Tile &t) {
-#pragma unroll
-    for (int i = 0; i < 2 * MB; ++i) *(uint4 *)(as + a_dst[i]) = t.a[i];
-    if constexpr (W4) {
-      const float nz = -bf16_hi(t.sz) * bf16_lo(t.sz);
-      const _Float16 sc = (_Float16)bf16_lo(t.sz), nzh = (_Float16)nz, nzl = (_Float16)(nz - (float)nzh);
-      const half2v sc2 = {sc, sc}, nzh2 = {nzh, nzh}, nzl2 = {nzl, nzl};
-      *(half8 *)(bs + b_dst[0]) = dequant8(t.b[0].x, sc2, nzh2, nzl2);
-      *(half8 *)(bs + b_dst[0] + 8) = dequant8(t.b[0].y, sc2, nzh2, nzl2);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) *(half8 *)(bs + b_dst[i]) = bf16x8_to_half8(t.b[i]);
-    }
-  };
-  f32x4v acc[MB];
-#pragma unroll
-  for (int i = 0; i < MB; ++i) acc[i] = f32x4v{0.f, 0.f, 0.f, 0.f};
-  const int nk = K / TK;
-  const int r16 = lane & 15, g8 = (lane >> 4) * 8;
-  auto wave_fence = [] {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-  };
-  Tile t[NT];
-#pragma unroll
-  for (int u = 0; u < NT; ++u)
-    if (wv + 4 * u < nk) load(wv + 4 * u, t[u]);
-  for (int kt = wv; kt < nk; kt += 4 * NT) {
-#pragma unroll
-    for (int u = 0; u < NT; ++u) {
-      const int k = kt + 4 * u;
-      if (k < nk) {
-        stage(t[u]);
-        wave_fence();
-        if (k + 4 * NT < nk) load(k + 4 * NT, t[u]);
-#pragma unroll
-        for (int ks = 0; ks < TK / 32; ++ks) {
-          const half8 b = *(const half8 *)(bs + r16 * LDK + ks * 32 + g8);
-#pragma unroll
-          for (int i = 0; i < MB; ++i) {
-            const half8 a = *(const half8 *)(as + (i * 16 + r16) * LDK + ks * 32 + g8);
-            acc[i] = mfma16x16(a, b, acc[i]);
-          }
-        }
-        wave_fence();
+      if (interleaved) { mat = min(n, N - 1) & 1; r = min(n, N - 1) >> 1; }
+      else gemm_b_row(B, n, N, mat, r);
+      if constexpr (W4) {
+        bp[rb] = (const char *)B.w[mat] + (size_t)r * (K >> 1) + (kl >> 1);
+        szp[rb] = (const char *)B.sz[mat] + (size_t)r * (K / group) * 4;
+      } else {
+        bp[rb] = (const char *)B.w[mat] + ((size_t)r * K + kl) * 2;
+        szp[rb] = nullptr;
       }
     }
-  }
-  __syncthreads();
-  float *red = (float *)&As[0][0];                            // [4][RM][16] floats (As holds more)
+    auto load = [&](int kt, Stage &t) {
+      const int k0 = kt * TILE;
+      const bool kok = k0 + kl + (W4 ? 32 : 8) <= K;          // dense: also the second step's columns, K % 64 == 0
 #pragma unroll
-  for (int i = 0; i < MB; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[(wv * RM + i * 16 + (lane >> 4) * 4 + r) * 16 + r16] = acc[i][r];
-  __syncthreads();
-  for (int e = tid; e < RM * 16; e += 256) {
-    const int row = e >> 4, col = n0 + (e & 15);
-    if (row < n_rows && col < N && (want < 0 || river[row] == want)) {
-      const float v = ((red[e] + red[RM * 16 + e]) + red[2 * RM * 16 + e]) + red[3 * RM * 16 + e];
-      float *p = C + (size_t)row * ldc + col;
-      if constexpr (ADD) *p += v;
-      else *p = v;
+        for (int s = 0; s < NA; ++s)
+          t.a[i * NA + s] = kok ? *(const uint4 *)(a_row[i] + k0 + (W4 ? s * 8 : s * 32)) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        if constexpr (W4) {
+          const bool v = ok[rb] && kok;
+          t.b[rb] = v ? ld_stream16(bp[rb] + (k0 >> 1)) : make_uint4(0, 0, 0, 0);
+          t.sz[rb] = v ? *RIVER_GLOBAL(uint32_t, szp[rb] + (size_t)((k0 + kl) / group) * 4) : 0u;
+        } else {
+#pragma unroll
+          for (int s = 0; s < 2; ++s)
+            t.b[rb * 2 + s] = ok[rb] && kok ? ld_stream16(bp[rb] + (size_t)(k0 + s * 32) * 2) : make_uint4(0, 0, 0, 0);
+        }
+      }
+    };
+    f32x4v acc[RBW][MB];
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int i = 0; i < MB; ++i) acc[rb][i] = f32x4v{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](const Stage &t) {
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        if constexpr (W4) {
+          const float nz = -bf16_hi(t.sz[rb]) * bf16_lo(t.sz[rb]);
+          const _Float16 sc = (_Float16)bf16_lo(t.sz[rb]), nzh = (_Float16)nz, nzl = (_Float16)(nz - (float)nzh);
+          const half2v sc2 = {sc, sc}, nzh2 = {nzh, nzh}, nzl2 = {nzl, nzl};
+          const uint32_t w[4] = {t.b[rb].x, t.b[rb].y, t.b[rb].z, t.b[rb].w};
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const half8 b = dequant8(w[s], sc2, nzh2, nzl2);
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+              acc[rb][i] = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + s]), b, acc[rb][i]);
+          }
+        } else {
+#pragma unroll
+          for (int s = 0; s < 2; ++s) {
+            const half8 b = bf16x8_to_half8(t.b[rb * 2 + s]);
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+              acc[rb][i] = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + s]), b, acc[rb][i]);
+          }
+        }
+      }
+    };
+    Stage st[P];
+#pragma unroll
+    for (int u = 0; u < P; ++u)
+      if (wv + kBdWaves * u < nkt) load(wv + kBdWaves * u, st[u]);
+    for (int kt = wv; kt < nkt; kt += kBdWaves * P) {
+#pragma unroll
+      for (int u = 0; u < P; ++u) {
+        const int k = kt + kBdWaves * u;
+        if (k < nkt) {
+          compute(st[u]);
+          if (k + kBdWaves * P < nkt) load(k + kBdWaves * P, st[u]);
+        }
+      }
+    }
+    // the eight partial tiles -> one, in wavefront order; D: register r of lane l is sequence row
+    // (l / 16) * 4 + r, B row l % 16
+    __syncthreads();                                          // the previous pass has been read
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          red[((wv * RBW + rb) * MB + i) * 256 + (kg * 4 + r) * 16 + r16] = acc[rb][i][r];
+    __syncthreads();
+    constexpr int TILE_F = RBW * MB * 256;
+    for (int e = tid; e < TILE_F; e += 512) {
+      const int rb = e / (MB * 256), i = (e / 256) % MB, row = i * 16 + ((e & 255) >> 4), n = p0 + rb * 16 + (e & 15);
+      if (row >= n_rows || n >= wg_r1 || !(want < 0 || river[row] == want)) continue;
+      auto total = [&](int idx) {
+        float v = red[idx];
+#pragma unroll
+        for (int w = 1; w < kBdWaves; ++w) v += red[w * TILE_F + idx];
+        return v;
+      };
+      if (epi == EPI_SWIGLU) {
+        if (n & 1) continue;
+        const float g = total(e), u = total(e + 1);
+        ((_Float16 *)C)[(size_t)row * ldc + (n >> 1)] = (_Float16)(g / (1.0f + expf(-g)) * u);
+      } else {
+        float *p = (float *)C + (size_t)row * ldc + n;
+        const float v = total(e);
+        if (epi == EPI_ADD) *p += v;
+        else *p = v;
+      }
     }
   }
 }

@@ -250,3 +250,28 @@ def test_batch_of_twenty_sequences_two_row_blocks():
         B.toks = [r[0] for r in res]
     B.compare_caches()
     B.close()
+
+
+WIDEB = configs.ModelConfig("wide-batch-bf16", 2, 256, 32, 8, 128, 8192, 40000, 500000.0, 1e-5,
+                            configs.DTYPE_BF16, 96, 0, 2.0)
+
+
+@pytest.mark.parametrize("n_seq", [6, 19])
+def test_batch_wide_matrices_several_row_blocks_per_workgroup(n_seq):
+    """Matrices with more rows than 16 per CU: the batched GEMM takes two (QKV: 6144 rows) and
+    up to eight (gate/up: 16384 rows) row blocks per pass, and the LM head (40000 rows) several
+    passes; with 19 sequences the 32-row activation tile."""
+    cfg = WIDEB
+    say(f"batched decode, wide matrices, {n_seq} sequences")
+    B = Batch(cfg, n_seq, [3 + (5 * b) % 29 for b in range(n_seq)], 241)
+    rng = np.random.default_rng(11)
+    for step in range(3):
+        forced = [int(rng.integers(0, 3)) for _ in range(n_seq)]
+        got = B.g.decode_batch(n_seq, B.toks, forced)
+        res = [o.decode_step(t, f) for o, t, f in zip(B.os, B.toks, forced)]
+        hid = np.array([o.hidden() for o in B.os]).transpose(1, 0, 2)
+        B.compare([r[0] for r in res], [r[1] for r in res], [r[2] for r in res], hid,
+                  [o.logits() for o in B.os], got, f"wide step {step}")
+        B.toks = [r[0] for r in res]
+    B.compare_caches()
+    B.close()
