@@ -1042,9 +1042,10 @@ static void launch_bd_gemm_b(river_ctx *x, const pf::GemmB &B, int interleaved, 
   hipStream_t s = x->stream;
   const int g = x->cfg.river_group;
   const int *rv = x->st_b.river;
+  const _Float16 *Af = A + (W4 ? bd::frag_halfs(K) : 0);       // the buffer holds both fragment orders
 #define RIVER_BD_LAUNCH(MB, RBW)                                                                         \
-  bd::k_bd_gemm<W4, MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(A, K, B, interleaved, N, K, g, C, ldc, \
-                                                                              epi, rv, want, n, rows_per_wg)
+  bd::k_bd_gemm<W4, MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, B, interleaved, N, K, g, C, ldc, epi, \
+                                                                              rv, want, n, rows_per_wg)
   if (n <= 16) {
     if (blocks <= 1) RIVER_BD_LAUNCH(1, 1);
     else if (blocks <= 2) RIVER_BD_LAUNCH(1, 2);
@@ -1133,7 +1134,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
     bool dense = !all_forced, river = !all_forced;
     for (int b = 0; b < n && all_forced; ++b) { dense = dense || fe[b] > l; river = river || fe[b] <= l; }
     river = river && rv && W.qc[M_WQ];
-    pf::k_pf_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
+    bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
     if (dense) launch_bd_gemm<false>(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, 0, n);
     if (river) launch_bd_gemm<true>(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, 1, n);
     bd::k_bd_rope_store<<<dim3(n), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, st.pos, l,
@@ -1146,7 +1147,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
                                          st.pos, o16);
     if (dense) launch_bd_gemm<false>(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, 0, n);
     if (river) launch_bd_gemm<true>(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, 1, n);
-    pf::k_pf_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);
+    bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);
     // gate and up rows interleaved, SwiGLU in the epilogue: the down projection's input as fp16
     if (dense) launch_bd_gemm<false>(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, 0, n);
     if (river) launch_bd_gemm<true>(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, 1, n);
@@ -1158,7 +1159,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
       bd::k_bd_decide<<<dim3(1), dim3(64), 0, s>>>(n, l + 1, L, c.min_exit_layer, c.tau, c.batch_exit_rule, st, s_of);
   }
   // the original final norm + LM head, greedy token per sequence
-  pf::k_pf_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, D.final_norm, d, c.rms_eps, x16);
+  bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, D.final_norm, d, c.rms_eps, x16);
   {
     pf::GemmB Bh{};
     Bh.w[0] = Bh.w[1] = Bh.w[2] = D.lm_head;

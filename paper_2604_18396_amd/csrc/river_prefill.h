@@ -491,6 +491,54 @@ __device__ __forceinline__ half8 dequant8(uint32_t w, half2v sc2, half2v nzh2, h
   return out;
 }
 
+// The activations of a batched step (up to 32 sequence rows x K) are kept in the order the
+// matrix-core operands are fetched in, so that a wavefront's A fragment of one MFMA step is one
+// contiguous 1 KiB load: [K tile][step][row block of 16][lane group g][row % 16][8 columns].
+// Two such orders, one per weight format: dense tiles are 64 columns (step s, group g: columns
+// k0 + 32 s + 8 g .. + 7), 4-bit tiles 128 columns (k0 + 32 g + 8 s .. + 7: a lane's four code
+// words are four steps).  A buffer holds both, the dense order first; K is padded to 128.
+__host__ __device__ inline size_t frag_halfs(int K) { return (size_t)32 * ((K + 127) / 128 * 128); }
+__host__ __device__ inline size_t frag_index_dense(int m, int k) {
+  return ((((size_t)(k >> 6) * 2 + ((k >> 5) & 1)) * 2 + (m >> 4)) * 64 + ((k >> 3) & 3) * 16 + (m & 15)) * 8 + (k & 7);
+}
+__host__ __device__ inline size_t frag_index_w4(int m, int k) {
+  return ((((size_t)(k >> 7) * 4 + ((k >> 3) & 3)) * 2 + (m >> 4)) * 64 + ((k >> 5) & 3) * 16 + (m & 15)) * 8 + (k & 7);
+}
+// element (m, k) into both orders of the buffer xf (K columns)
+__device__ __forceinline__ void frag_store(_Float16 *xf, int K, int m, int k, _Float16 v) {
+  xf[frag_index_dense(m, k)] = v;
+  xf[frag_halfs(K) + frag_index_w4(m, k)] = v;
+}
+// eight consecutive elements (m, k .. k+7), k % 8 == 0: one 16-byte store per order
+__device__ __forceinline__ void frag_store8(_Float16 *xf, int K, int m, int k, half8 v) {
+  *(half8 *)(xf + frag_index_dense(m, k)) = v;
+  *(half8 *)(xf + frag_halfs(K) + frag_index_w4(m, k)) = v;
+}
+
+// xf[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain) in fragment order (both);
+// one workgroup (256) per sequence row; d % 8 == 0
+__global__ __launch_bounds__(256) void k_bd_rmsnorm(const float *__restrict__ h, const void *gain, int d, float eps,
+                                                    _Float16 *xf) {
+  __shared__ float red[16];
+  const int t = blockIdx.x;
+  const float *row = h + (size_t)t * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {
+    const float4 v = *(const float4 *)(row + i);
+    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+  }
+  const float tot = block_sum(ss, red);
+  const float r = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
+    const float4 a = *(const float4 *)(row + k), b = *(const float4 *)(row + k + 4);
+    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    half8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (_Float16)(v[j] * r * Store<1>::ld(gain, k + j));
+    frag_store8(xf, d, t, k, o);
+  }
+}
+
 // C[rows, N] (op)= A[rows, K] B^T for the rows r < n_rows with river[r] == want (want < 0: all
 // rows); nothing is read if there is none.  MB = 1: up to 16 rows, MB = 2: up to 32.
 //
@@ -503,11 +551,13 @@ __device__ __forceinline__ half8 dequant8(uint32_t w, half2v sc2, half2v nzh2, h
 // no LDS on the way: for B, lane (n = lane % 16, g = lane / 16) fetches 16 bytes of row n (dense:
 // columns k0 + 32 s + 8 g .. + 7 for the tile's two steps s; codes: the 32 columns
 // k0 + 32 g .. + 31, one step per code word, which lie in one quantisation group), for A the
-// same columns of sequence row n (fp16, from the L2: the activation tile is small and every
-// workgroup reads all of it once per K tile, shared by its RBW row blocks).  P tiles are in flight per
+// same columns of sequence row n (fp16, kept in fragment order: one contiguous 1 KiB per
+// wavefront and step, from the L2; every workgroup reads the whole tile once, shared by its RBW
+// row blocks).  P tiles are in flight per
 // wavefront in registers.  The eight partial tiles are summed in wavefront order through LDS.
 // op (epi): store fp32, add into fp32, or -- with B's rows interleaved as (gate i, up i) --
-// silu(gate) * up stored as fp16 (the activation of the down projection).
+// silu(gate) * up stored as fp16 in fragment order (the activation of the down projection; ldc is
+// then its column count).
 enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
 constexpr int kBdWaves = 8;
 template <int RBW, int MB> struct BdDepth {                 // K tiles in flight per wavefront (register budget)
@@ -517,7 +567,7 @@ template <int RBW, int MB> struct BdDepth {                 // K tiles in flight
 __host__ __device__ inline size_t bd_gemm_lds_bytes(int rbw, int mb) { return (size_t)kBdWaves * rbw * mb * 256 * 4; }
 
 template <bool W4, int MB, int RBW>
-__global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int interleaved,
+__global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af, GemmB B, int interleaved,
                                                  int N, int K, int group, void *C, int ldc, int epi,
                                                  const int *__restrict__ river, int want, int n_rows,
                                                  int rows_per_wg) {
@@ -535,11 +585,8 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ A,
   const int r16 = lane & 15, kg = lane >> 4;
   const int wg_r0 = blockIdx.x * rows_per_wg, wg_r1 = min(N, wg_r0 + rows_per_wg);
   const int nkt = (K + TILE - 1) / TILE;
-  // this lane's column offset inside a K tile (elements) and its A rows
+  // this lane's column offset inside a K tile (elements)
   const int kl = W4 ? kg * 32 : kg * 8;
-  const _Float16 *a_row[MB];
-#pragma unroll
-  for (int i = 0; i < MB; ++i) a_row[i] = A + (size_t)(i * 16 + r16) * lda + kl;
   struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint32_t sz[W4 ? RBW : 1]; };
   for (int p0 = wg_r0; p0 < wg_r1; p0 += RBW * 16) {
     const char *bp[RBW], *szp[RBW];
@@ -566,7 +613,7 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ A,
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int s = 0; s < NA; ++s)
-          t.a[i * NA + s] = kok ? *(const uint4 *)(a_row[i] + k0 + (W4 ? s * 8 : s * 32)) : make_uint4(0, 0, 0, 0);
+          t.a[i * NA + s] = kok ? *(const uint4 *)(Af + ((size_t)((kt * NA + s) * 2 + i) * 64 + lane) * 8) : make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb) {
         if constexpr (W4) {
@@ -649,7 +696,7 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ A,
       if (epi == EPI_SWIGLU) {
         if (n & 1) continue;
         const float g = total(e), u = total(e + 1);
-        ((_Float16 *)C)[(size_t)row * ldc + (n >> 1)] = (_Float16)(g / (1.0f + expf(-g)) * u);
+        frag_store((_Float16 *)C, ldc, row, n >> 1, (_Float16)(g / (1.0f + expf(-g)) * u));
       } else {
         float *p = (float *)C + (size_t)row * ldc + n;
         const float v = total(e);
@@ -806,7 +853,7 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, c
     float o = part[tid];
 #pragma unroll
     for (int k = 1; k < 16; ++k) o += part[k * HD + tid];
-    o16[(size_t)b * qd + h * HD + tid] = (_Float16)(o / lsum);
+    frag_store(o16, qd, b, h * HD + tid, (_Float16)(o / lsum));
   }
 }
 
