@@ -761,11 +761,9 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
         return fail("hipFuncSetAttribute(max dynamic LDS)", e);
     if (cfg->max_batch > 1) {
       // the widest batched GEMM keeps 64 KiB of partial tiles beside its static LDS
-      const void *wide[] = {(const void *)bd::k_bd_gemm<false, 1, 8>, (const void *)bd::k_bd_gemm<true, 1, 8>};
-      for (const void *f : wide)
-        if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)bd::bd_gemm_lds_bytes(8, 1))) != hipSuccess)
-          return fail("hipFuncSetAttribute(batched GEMM LDS)", e);
+      if ((e = hipFuncSetAttribute((const void *)bd::k_bd_gemm<1, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)bd::bd_gemm_lds_bytes(8, 1))) != hipSuccess)
+        return fail("hipFuncSetAttribute(batched GEMM LDS)", e);
     }
   }
   *out = x;
@@ -1030,11 +1028,11 @@ extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const in
 }
 
 // GEMM of a batched decode step over the matrices ms[0..nm) of block l (stacked along N, or
-// interleaved row by row for the gate/up pair), for the rows whose river flag equals `want`
-// (see bd::k_bd_gemm).  The rows of B are dealt out to one workgroup per CU, eight at a time.
-template <bool W4>
-static void launch_bd_gemm_b(river_ctx *x, const pf::GemmB &B, int interleaved, int N, const _Float16 *A, int K,
-                             void *C, int ldc, int epi, int want, int n) {
+// interleaved row by row for the gate/up pair): bf16 matrices for the rows in the backbone,
+// 4-bit twins for the others (see bd::k_bd_gemm).  The rows of B are dealt out to one
+// workgroup per CU, eight at a time.
+static void launch_bd_gemm_b(river_ctx *x, const pf::GemmB &Bd, const pf::GemmB &Bq, int interleaved, int N,
+                             const _Float16 *Af, int K, void *C, int ldc, int epi, int by_flag, int n) {
   const int per_cu = (N + x->grid_persist - 1) / x->grid_persist;
   const int rows_per_wg = std::max(8, (per_cu + 7) / 8 * 8);
   const int blocks = (rows_per_wg + 15) / 16;
@@ -1042,10 +1040,9 @@ static void launch_bd_gemm_b(river_ctx *x, const pf::GemmB &B, int interleaved, 
   hipStream_t s = x->stream;
   const int g = x->cfg.river_group;
   const int *rv = x->st_b.river;
-  const _Float16 *Af = A + (W4 ? bd::frag_halfs(K) : 0);       // the buffer holds both fragment orders
-#define RIVER_BD_LAUNCH(MB, RBW)                                                                         \
-  bd::k_bd_gemm<W4, MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, B, interleaved, N, K, g, C, ldc, epi, \
-                                                                              rv, want, n, rows_per_wg)
+#define RIVER_BD_LAUNCH(MB, RBW)                                                                                      \
+  bd::k_bd_gemm<MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, Bd, Bq, interleaved, N, K, g, C, ldc, epi, \
+                                                                          rv, by_flag, n, rows_per_wg)
   if (n <= 16) {
     if (blocks <= 1) RIVER_BD_LAUNCH(1, 1);
     else if (blocks <= 2) RIVER_BD_LAUNCH(1, 2);
@@ -1056,21 +1053,21 @@ static void launch_bd_gemm_b(river_ctx *x, const pf::GemmB &B, int interleaved, 
   }
 #undef RIVER_BD_LAUNCH
 }
-template <bool W4>
-static void launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, int interleaved, const _Float16 *A, int K,
-                           void *C, int ldc, int epi, int want, int n) {
-  pf::GemmB B{};
+static void launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, int interleaved, const _Float16 *Af, int K,
+                           void *C, int ldc, int epi, int n) {
+  pf::GemmB Bd{}, Bq{};
   int N = 0;
   for (int i = 0; i < nm; ++i) {
     long long r, c;
     matrix_shape(&x->cfg, ms[i], &r, &c);
-    B.w[i] = W4 ? (const void *)x->layers_h[l].qc[ms[i]] : x->layers_h[l].w[ms[i]];
-    B.sz[i] = x->layers_h[l].qsz[ms[i]];
-    B.rows[i] = (int)r;
+    Bd.w[i] = x->layers_h[l].w[ms[i]];
+    Bq.w[i] = x->layers_h[l].qc[ms[i]];
+    Bq.sz[i] = x->layers_h[l].qsz[ms[i]];
+    Bd.rows[i] = Bq.rows[i] = (int)r;
     N += (int)r;
   }
-  for (int i = nm; i < 3; ++i) { B.w[i] = B.w[0]; B.sz[i] = B.sz[0]; B.rows[i] = 0; }
-  launch_bd_gemm_b<W4>(x, B, interleaved, N, A, K, C, ldc, epi, want, n);
+  for (int i = nm; i < 3; ++i) { Bd.w[i] = Bd.w[0]; Bq.w[i] = Bq.w[0]; Bq.sz[i] = Bq.sz[0]; }
+  launch_bd_gemm_b(x, Bd, Bq, interleaved, N, Af, K, C, ldc, epi, 1, n);
 }
 
 extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in_tokens, const int32_t *forced_exit,
@@ -1120,23 +1117,13 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   bd::k_bd_fill_nan<<<dim3((n * L + 255) / 256), dim3(256), 0, s>>>(rec_sims, n * L);
   bd::k_bd_embed<<<dim3(n), dim3(256), 0, s>>>(st, D.tok_emb, d, c.vocab, L, h, hprev, hist);
   const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
-  const bool rv = x->have_river;
   const size_t seq_stride = y.cache_bytes / 2;               // elements (bf16)
   const size_t attn_lds = bd::attn_lds_bytes(c.max_seq);
-  // Which weight sets can a block need?  With every exit position forced the host knows, and
-  // the launches that would find no row are not made; otherwise both are launched and the one
-  // without rows returns at once.
-  bool all_forced = true;
-  for (int b = 0; b < n; ++b) all_forced = all_forced && fe[b] >= 0;
   const int qkv_ld = qd + 2 * c.n_kv_heads * c.head_dim;
   for (int l = 0; l < L; ++l) {
     const DevLayer &W = x->layers_h[l];
-    bool dense = !all_forced, river = !all_forced;
-    for (int b = 0; b < n && all_forced; ++b) { dense = dense || fe[b] > l; river = river || fe[b] <= l; }
-    river = river && rv && W.qc[M_WQ];
     bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
-    if (dense) launch_bd_gemm<false>(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, 0, n);
-    if (river) launch_bd_gemm<true>(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, 1, n);
+    launch_bd_gemm(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, n);
     bd::k_bd_rope_store<<<dim3(n), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, st.pos, l,
                                                       c.max_seq, seq_stride, D.kcache, D.vcache, D.kv_f16, qf);
     const int rep = c.n_q_heads / c.n_kv_heads;
@@ -1145,14 +1132,11 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
                                   : (D.kv_f16 ? bd::k_bd_attn<64, true> : bd::k_bd_attn<64, false>);
     attn<<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq, seq_stride,
                                          st.pos, o16);
-    if (dense) launch_bd_gemm<false>(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, 0, n);
-    if (river) launch_bd_gemm<true>(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, 1, n);
+    launch_bd_gemm(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, n);
     bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);
     // gate and up rows interleaved, SwiGLU in the epilogue: the down projection's input as fp16
-    if (dense) launch_bd_gemm<false>(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, 0, n);
-    if (river) launch_bd_gemm<true>(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, 1, n);
-    if (dense) launch_bd_gemm<false>(x, l, m_d, 1, 0, a16, ffn, h, d, bd::EPI_ADD, 0, n);
-    if (river) launch_bd_gemm<true>(x, l, m_d, 1, 0, a16, ffn, h, d, bd::EPI_ADD, 1, n);
+    launch_bd_gemm(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, n);
+    launch_bd_gemm(x, l, m_d, 1, 0, a16, ffn, h, d, bd::EPI_ADD, n);
     bd::k_bd_sim<<<dim3(n), dim3(256), 0, s>>>(hprev, h, d, l + 1, L, st, s_of, rec_sims,
                                                hist + (size_t)(l + 1) * B * d);
     if (l + 1 >= c.min_exit_layer && l + 1 < L)
@@ -1164,7 +1148,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
     pf::GemmB Bh{};
     Bh.w[0] = Bh.w[1] = Bh.w[2] = D.lm_head;
     Bh.rows[0] = c.vocab;
-    launch_bd_gemm_b<false>(x, Bh, 0, c.vocab, x16, d, logits, c.vocab, bd::EPI_STORE, -1, n);
+    launch_bd_gemm_b(x, Bh, Bh, 0, c.vocab, x16, d, logits, c.vocab, bd::EPI_STORE, 0, n);
   }
   bd::k_bd_argmax<<<dim3(n), dim3(256), 0, s>>>(logits, c.vocab, st, rec_token, rec_exit);
   HIP_TRY(x, hipGetLastError());

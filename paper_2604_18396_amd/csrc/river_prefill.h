@@ -567,21 +567,14 @@ template <int RBW, int MB> struct BdDepth {                 // K tiles in flight
 __host__ __device__ inline size_t bd_gemm_lds_bytes(int rbw, int mb) { return (size_t)kBdWaves * rbw * mb * 256 * 4; }
 
 template <bool W4, int MB, int RBW>
-__global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af, GemmB B, int interleaved,
-                                                 int N, int K, int group, void *C, int ldc, int epi,
-                                                 const int *__restrict__ river, int want, int n_rows,
-                                                 int rows_per_wg) {
+__device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, const GemmB &B, int interleaved, int N,
+                                             int K, int group, void *C, int ldc, int epi,
+                                             const int *__restrict__ river, int want, int n_rows, int rows_per_wg,
+                                             float *red /* [kBdWaves][RBW][MB][256] */) {
   constexpr int P = W4 ? BdDepth<RBW, MB>::w4 : BdDepth<RBW, MB>::dense;
   constexpr int TILE = W4 ? 128 : 64;                         // columns per K tile
   constexpr int NA = W4 ? 4 : 2;                              // MFMA steps (16-byte A fragments) per tile
-  extern __shared__ float red[];                              // [kBdWaves][RBW][MB][256]
-  __shared__ int any;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  if (tid == 0) any = 0;
-  __syncthreads();
-  if (tid < n_rows && (want < 0 || river[tid] == want)) any = 1;
-  __syncthreads();
-  if (!any) return;
   const int r16 = lane & 15, kg = lane >> 4;
   const int wg_r0 = blockIdx.x * rows_per_wg, wg_r1 = min(N, wg_r0 + rows_per_wg);
   const int nkt = (K + TILE - 1) / TILE;
@@ -704,6 +697,31 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af
         else *p = v;
       }
     }
+  }
+}
+
+// One launch per GEMM of a step: the bf16 matrices for the rows still in the backbone, then the
+// 4-bit twins for the rows that have left it (by_flag; otherwise the bf16 matrices for all
+// rows, as the LM head needs).  A side without rows is not read.  Af: both fragment orders of
+// the activations (see frag_halfs).
+template <int MB, int RBW>
+__global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af, GemmB Bd, GemmB Bq, int interleaved,
+                                                 int N, int K, int group, void *C, int ldc, int epi,
+                                                 const int *__restrict__ river, int by_flag, int n_rows,
+                                                 int rows_per_wg) {
+  extern __shared__ float red[];
+  __shared__ int any[2];
+  if (threadIdx.x < 2) any[threadIdx.x] = 0;
+  __syncthreads();
+  if ((int)threadIdx.x < n_rows) any[by_flag && river[threadIdx.x] != 0] = 1;
+  __syncthreads();
+  const bool dense = any[0] != 0, twin = any[1] != 0;
+  if (dense) bd_gemm_pass<false, MB, RBW>(Af, Bd, interleaved, N, K, group, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
+                                          rows_per_wg, red);
+  if (twin) {
+    __syncthreads();                                          // the partial tiles of the first pass have been read
+    bd_gemm_pass<true, MB, RBW>(Af + frag_halfs(K), Bq, interleaved, N, K, group, C, ldc, epi, river, 1, n_rows,
+                                rows_per_wg, red);
   }
 }
 
