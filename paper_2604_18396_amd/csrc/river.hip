@@ -254,7 +254,8 @@ struct Layout {
   size_t pf_tok, pf_h, pf_x16, pf_q16, pf_a16, pf_big;
   int pf_rows;
   // batched contexts (max_batch > 1): per-sequence state, step buffers, records
-  size_t bd_state, bd_hprev, bd_qf, bd_logits, bd_hist, bd_rec_token, bd_rec_exit, bd_rec_sims;
+  size_t bd_state, bd_hprev, bd_part_o, bd_part_ml, bd_tickets, bd_logits, bd_hist, bd_rec_token, bd_rec_exit,
+      bd_rec_sims;
 };
 
 
@@ -390,7 +391,7 @@ static bool valid_cfg(const river_config *c, std::string *why) {
     if (!gemm_prefill_ok(c))
       return bad("max_batch > 1 needs RIVER_BF16 with d_model, d_ffn and river_group multiples of 64 and the GEMM "
                  "prefill enabled");
-    if (bd::attn_lds_bytes(c->max_seq) > 65536) return bad("max_batch > 1 supports max_seq up to about 15900");
+    if (c->max_seq > bd::kBdAttnMaxSplits * bd::kBdAttnSplitCap) return bad("max_batch > 1 supports max_seq up to 16384");
   }
   return true;
 }
@@ -470,7 +471,9 @@ static Layout make_layout(const river_config *c) {
     const size_t B = c->max_batch, qd = (size_t)c->n_q_heads * c->head_dim;
     y.bd_state = take(6 * B * 4);
     y.bd_hprev = take((size_t)bd::kRows * c->d_model * 4);
-    y.bd_qf = take((size_t)bd::kRows * qd * 4);
+    y.bd_part_o = take((size_t)bd::kRows * qd * bd::kBdAttnMaxSplits * 4);      // attention split partials
+    y.bd_part_ml = take((size_t)bd::kRows * c->n_q_heads * bd::kBdAttnMaxSplits * 2 * 4);
+    y.bd_tickets = take((size_t)bd::kRows * c->n_q_heads * 4);
     y.bd_logits = take(B * c->vocab * 4);
     y.bd_hist = take((size_t)(c->n_layers + 1) * B * c->d_model * 4);
     y.bd_rec_token = take((size_t)bd::kRecordsB * B * 4);
@@ -732,6 +735,8 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
     x->st_b.forced = sp + 4 * B;
     if ((e = hipMemsetAsync(ws + lay.bd_state, 0, (size_t)6 * B * 4, x->stream)) != hipSuccess)
       return fail("sequence state clear", e);
+    if ((e = hipMemsetAsync(ws + lay.bd_tickets, 0, (size_t)bd::kRows * cfg->n_q_heads * 4, x->stream)) != hipSuccess)
+      return fail("attention ticket clear", e);
   }
   if ((e = hipMemcpyAsync(act + lay.layers, hl.data(), hl.size() * sizeof(DevLayer),
                           hipMemcpyHostToDevice, x->stream)) != hipSuccess)
@@ -1101,7 +1106,9 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   hipStream_t s = x->stream;
   const int d = c.d_model, qd = c.n_q_heads * c.head_dim, ffn = c.d_ffn;
   float *h = (float *)(x->ws + y.pf_h), *big = (float *)(x->ws + y.pf_big);
-  float *hprev = (float *)(x->ws + y.bd_hprev), *qf = (float *)(x->ws + y.bd_qf);
+  float *hprev = (float *)(x->ws + y.bd_hprev);
+  float *part_o = (float *)(x->ws + y.bd_part_o), *part_ml = (float *)(x->ws + y.bd_part_ml);
+  unsigned int *tickets = (unsigned int *)(x->ws + y.bd_tickets);
   float *logits = (float *)(x->ws + y.bd_logits), *hist = (float *)(x->ws + y.bd_hist);
   _Float16 *x16 = (_Float16 *)(x->ws + y.pf_x16), *o16 = (_Float16 *)(x->ws + y.pf_q16);
   _Float16 *a16 = (_Float16 *)(x->ws + y.pf_a16);
@@ -1118,20 +1125,32 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   bd::k_bd_embed<<<dim3(n), dim3(256), 0, s>>>(st, D.tok_emb, d, c.vocab, L, h, hprev, hist);
   const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
   const size_t seq_stride = y.cache_bytes / 2;               // elements (bf16)
-  const size_t attn_lds = bd::attn_lds_bytes(c.max_seq);
+  // attention: one workgroup per (sequence, kv head, group of query heads, split of the positions);
+  // splits so that every CU has two workgroups (measured best) and no split exceeds its LDS score area
+  const int rep = c.n_q_heads / c.n_kv_heads, arep = rep % 4 == 0 ? 4 : 1;
+  int t_max = 1;
+  for (int b = 0; b < n; ++b) t_max = std::max(t_max, x->pos_b[b] + 1);
+  const int hgs = rep / arep, groups = n * c.n_kv_heads * hgs;
+  int n_splits = std::max((2 * x->grid_persist + groups - 1) / groups,
+                          (t_max + bd::kBdAttnSplitCap - 1) / bd::kBdAttnSplitCap);
+  n_splits = std::max(1, std::min({n_splits, bd::kBdAttnMaxSplits, (t_max + 127) / 128}));
+  const int attn_cap = (t_max + n_splits - 1) / n_splits;
+  const size_t attn_lds = bd::bd_attn_lds_bytes(arep, c.head_dim, attn_cap);
   const int qkv_ld = qd + 2 * c.n_kv_heads * c.head_dim;
   for (int l = 0; l < L; ++l) {
     const DevLayer &W = x->layers_h[l];
     bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
     launch_bd_gemm(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, n);
-    bd::k_bd_rope_store<<<dim3(n), dim3(256), 0, s>>>(big, D.rope, c.n_q_heads, c.n_kv_heads, c.head_dim, st.pos, l,
-                                                      c.max_seq, seq_stride, D.kcache, D.vcache, D.kv_f16, qf);
-    const int rep = c.n_q_heads / c.n_kv_heads;
-    const dim3 ga((n * c.n_kv_heads + 7) / 8 * 8 * rep);
-    auto attn = c.head_dim == 128 ? (D.kv_f16 ? bd::k_bd_attn<128, true> : bd::k_bd_attn<128, false>)
-                                  : (D.kv_f16 ? bd::k_bd_attn<64, true> : bd::k_bd_attn<64, false>);
-    attn<<<ga, dim3(256), attn_lds, s>>>(qf, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq, seq_stride,
-                                         st.pos, o16);
+    {
+      const dim3 ga((n * c.n_kv_heads * n_splits + 7) / 8 * 8 * hgs);
+      auto attn = c.head_dim == 128
+                      ? (arep == 4 ? (D.kv_f16 ? bd::k_bd_attn<128, true, 4> : bd::k_bd_attn<128, false, 4>)
+                                   : (D.kv_f16 ? bd::k_bd_attn<128, true, 1> : bd::k_bd_attn<128, false, 1>))
+                      : (arep == 4 ? (D.kv_f16 ? bd::k_bd_attn<64, true, 4> : bd::k_bd_attn<64, false, 4>)
+                                   : (D.kv_f16 ? bd::k_bd_attn<64, true, 1> : bd::k_bd_attn<64, false, 1>));
+      attn<<<ga, dim3(256), attn_lds, s>>>(big, D.rope, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq,
+                                           seq_stride, st.pos, n_splits, attn_cap, part_o, part_ml, tickets, o16);
+    }
     launch_bd_gemm(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, n);
     bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);
     // gate and up rows interleaved, SwiGLU in the epilogue: the down projection's input as fp16

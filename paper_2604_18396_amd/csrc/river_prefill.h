@@ -749,63 +749,94 @@ __global__ void k_bd_copy(const float *__restrict__ src, float *dst, size_t n) {
     dst[i] = src[i];
 }
 
-// RoPE at each sequence's own position; q (scaled by log2(e)/sqrt(hd)) to qf (fp32), k and v
-// rounded to the cache dtype into slot (seq b, block l, pos[b]) of the shared cache.
-__global__ void k_bd_rope_store(const float *__restrict__ qkv, const float2 *__restrict__ rope, int nq, int nkv,
-                                int hd, const int *__restrict__ pos, int l, int max_seq, size_t seq_stride,
-                                void *kcache, void *vcache, int kv_f16, float *qf) {
-  const int b = blockIdx.x, p = pos[b], half = hd >> 1;
-  const int qd = nq * hd, kvd = nkv * hd, ld = qd + 2 * kvd;
-  const float *row = qkv + (size_t)b * ld;
-  const float qs = 1.4426950408889634f / sqrtf((float)hd);
-  const size_t slot = (size_t)b * seq_stride + ((size_t)l * max_seq + p) * kvd;
-  for (int i = threadIdx.x; i < (nq + nkv) * half; i += blockDim.x) {
-    const int head = i / half, e = i % half;
-    const float2 cs = rope[(size_t)p * half + e];
-    const float *src = row + head * hd;
-    const float a = src[e], c = src[e + half];
-    const float lo = a * cs.x - c * cs.y, hi = a * cs.y + c * cs.x;
-    if (head < nq) {
-      qf[(size_t)b * qd + head * hd + e] = lo * qs;
-      qf[(size_t)b * qd + head * hd + e + half] = hi * qs;
-    } else {
-      cache_store(kcache, slot + (size_t)(head - nq) * hd + e, lo, kv_f16);
-      cache_store(kcache, slot + (size_t)(head - nq) * hd + e + half, hi, kv_f16);
+// Single-query attention of a batched step with RoPE and the KV write in front of it.  One
+// workgroup per (sequence b, kv head, group of REP query heads of that kv head, split of the
+// positions 0 .. pos[b]): the K/V rows of the kv head are read once for the REP heads.
+//
+// Prologue (from the raw QKV rows the GEMM left): the REP query vectors rotated at position
+// pos[b] and scaled by log2(e)/sqrt(hd), this token's k (rotated) and v rounded to the cache
+// dtype, all into LDS; the workgroup whose split holds position pos[b] (the first head group)
+// also writes them to slot (b, l, pos[b]) of the shared cache -- the same slot for backbone and
+// river rows -- and nobody reads that slot from the cache in this launch.
+// Sixteen lanes share a cached row (HD/16 elements each, one 16- or 8-byte load), the 16 lane
+// groups stride over the split's positions, eight rows in flight per group.  Pass 1: scores (DPP
+// row sums) to LDS and the maxima; pass 2: probabilities and their sums; pass 3: the weighted
+// value rows; lane groups and wavefronts are summed in a fixed order.  With several splits every
+// workgroup publishes (max, sum, unnormalised output) per head and the last one to arrive of
+// the group merges them in split order (device-coherent stores and loads, no fences).  The
+// result goes to o16 in fragment order (frag_store), the output projection's input.
+constexpr int kBdAttnMaxSplits = 8;
+constexpr int kBdAttnSplitCap = 2048;                        // most positions per split
+__host__ __device__ inline size_t bd_attn_lds_bytes(int rep, int hd, int cap) {
+  return ((size_t)rep * hd + 2 * hd + 64 + 4 * rep * hd + (size_t)rep * cap) * 4;
+}
+template <int HD, bool KV_F16, int REP>
+__global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, const float2 *__restrict__ rope,
+                                                 void *kcache, void *vcache, int nq, int nkv, int n_seq, int l,
+                                                 int max_seq, size_t seq_stride, const int *__restrict__ pos,
+                                                 int n_splits, int cap, float *part_o, float *part_ml,
+                                                 unsigned int *tickets, _Float16 *o16) {
+  constexpr int EL = HD / 16, HALF = HD / 2;                   // EL: elements per lane of a cached row
+  extern __shared__ float sm[];
+  float *qs = sm;                                              // [REP][HD]
+  float *kc = qs + REP * HD, *vc = kc + HD;                    // this token's k, v (cache-rounded values)
+  float *red = vc + HD;                                        // [64]
+  float *part = red + 64;                                      // [4 wavefronts][REP][HD]
+  float *sc = part + 4 * REP * HD;                             // [REP][cap]
+  const int tid = threadIdx.x, grp = tid >> 4, dl = tid & 15, wv = tid >> 6;
+  const int rep = nq / nkv, hgs = rep / REP;
+  // Workgroup index -> (data group g = (sequence, kv head, split), head group hg) such that the head
+  // groups that read the same K/V rows run on the same XCD (consecutive workgroup ids go round the
+  // 8 XCDs) and meet in that XCD's L2.
+  const int bi = blockIdx.x, g = (bi / (8 * hgs)) * 8 + (bi & 7), hg = (bi % (8 * hgs)) >> 3;
+  if (g >= n_seq * nkv * n_splits) return;
+  const int sp = g % n_splits, kvh = (g / n_splits) % nkv, b = g / (n_splits * nkv);
+  const int h0 = kvh * rep + hg * REP;
+  const int P = pos[b], T = P + 1, qd = nq * HD, kvd = nkv * HD, ld = qd + 2 * kvd;
+  const int chunk = (T + n_splits - 1) / n_splits, p0 = sp * chunk, p1 = min(T, p0 + chunk);
+  const bool owner = P >= p0 && P < p1;                        // this split holds the current position
+  const float *row_in = qkv + (size_t)b * ld;
+  const size_t base = (size_t)b * seq_stride + (size_t)l * max_seq * kvd + (size_t)kvh * HD;
+  // ---- prologue: RoPE, rounding, KV write
+  {
+    const float qscale = 1.4426950408889634f / sqrtf((float)HD);
+    for (int t = tid; t < REP * HALF; t += 256) {
+      const int r = t / HALF, e = t % HALF;
+      const float2 cs = rope[(size_t)P * HALF + e];
+      const float *src = row_in + (h0 + r) * HD;
+      const float a = src[e], c = src[e + HALF];
+      qs[r * HD + e] = (a * cs.x - c * cs.y) * qscale;
+      qs[r * HD + e + HALF] = (a * cs.y + c * cs.x) * qscale;
+    }
+    if (owner) {
+      auto rnd = [](float v) { return KV_F16 ? (float)(_Float16)v : Store<1>::rnd(v); };
+      const bool writer = hg == 0;
+      const size_t slot = base + (size_t)P * kvd;
+      if (tid < HALF) {
+        const int e = tid;
+        const float2 cs = rope[(size_t)P * HALF + e];
+        const float *src = row_in + qd + kvh * HD;
+        const float a = src[e], c = src[e + HALF];
+        const float lo = a * cs.x - c * cs.y, hi = a * cs.y + c * cs.x;
+        kc[e] = rnd(lo); kc[e + HALF] = rnd(hi);
+        if (writer) { cache_store(kcache, slot + e, lo, KV_F16); cache_store(kcache, slot + e + HALF, hi, KV_F16); }
+      } else if (tid >= 128 && tid < 128 + HD) {
+        const int e = tid - 128;
+        const float v = row_in[qd + kvd + kvh * HD + e];
+        vc[e] = rnd(v);
+        if (writer) cache_store(vcache, slot + e, v, KV_F16);
+      }
     }
   }
-  for (int i = threadIdx.x; i < kvd; i += blockDim.x) cache_store(vcache, slot + i, row[qd + kvd + i], kv_f16);
-}
-
-// Single-query attention, one workgroup per (sequence, query head), over the sequence's cache
-// positions 0 .. pos[b].  Sixteen lanes share a cached row (HD/16 elements each, one 16- or
-// 8-byte load), so a wavefront load covers four positions with whole rows; the workgroup's 16
-// lane groups stride over the positions.  Pass 1: scores (DPP row sums) to LDS and the block
-// maximum; pass 2: probabilities and their sum; pass 3: each lane group accumulates its
-// positions' value rows, the 16 partial vectors are summed in group order.
-// Dynamic LDS: attn_lds_bytes(max_seq).
-__host__ __device__ inline size_t attn_lds_bytes(int max_seq) { return ((size_t)max_seq + 32 + 16 * 128 + 32) * 4; }
-template <int HD, bool KV_F16>
-__global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, const void *kcache, const void *vcache,
-                                                 int nq, int nkv, int n_seq, int l, int max_seq,
-                                                 size_t seq_stride, const int *__restrict__ pos, _Float16 *o16) {
-  constexpr int EL = HD / 16;                                  // elements per lane of a cached row
-  extern __shared__ float sm[];
-  float *red = sm, *part = sm + 32, *sc = sm + 32 + 16 * 128;
-  // Workgroup index -> (sequence, kv head, query head of its group) such that the query heads
-  // that share a kv head run on the same XCD (consecutive workgroup ids go round the 8 XCDs) and
-  // their reads of the same K/V rows meet in that XCD's L2.
-  const int rep = nq / nkv, tid = threadIdx.x;
-  const int i = blockIdx.x, g = (i / (8 * rep)) * 8 + (i & 7), r = (i % (8 * rep)) >> 3;
-  if (g >= n_seq * nkv) return;
-  const int b = g / nkv, kvh = g % nkv, h = kvh * rep + r;
-  const int grp = tid >> 4, dl = tid & 15;
-  const int T = pos[b] + 1, qd = nq * HD, kvd = nkv * HD;
-  const size_t base = (size_t)b * seq_stride + (size_t)l * max_seq * kvd + (size_t)kvh * HD + dl * EL;
-  float q[EL];
+  __syncthreads();
+  float q[REP][EL];
 #pragma unroll
-  for (int e = 0; e < EL; ++e) q[e] = qf[(size_t)b * qd + h * HD + dl * EL + e];
+  for (int r = 0; r < REP; ++r)
+#pragma unroll
+    for (int e = 0; e < EL; ++e) q[r][e] = qs[r * HD + dl * EL + e];
+  // one cached row slice
   auto row = [&](const void *cache, int j, float (&f)[EL]) {
-    const char *p = (const char *)cache + (base + (size_t)j * kvd) * 2;
+    const char *p = (const char *)cache + (base + (size_t)j * kvd + dl * EL) * 2;
     if constexpr (EL == 8) {
       const uint4 w = *(const uint4 *)p;
       f[0] = cache_lo(w.x, KV_F16); f[1] = cache_hi(w.x, KV_F16); f[2] = cache_lo(w.y, KV_F16);
@@ -817,61 +848,156 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qf, c
       f[3] = cache_hi(w.y, KV_F16);
     }
   };
-  // eight rows of the lane group in flight at a time (positions beyond T read row T - 1 again)
-  float mx = -1.0e30f;
-  for (int j0 = grp; j0 < T; j0 += 16 * 8) {
+  // The current position (the last one, held by the owner split) is not read from the cache: the
+  // loops run over the cached rows p0 .. pc - 1 and the first lane group adds it from LDS.
+  const int pc = owner ? P : p1;
+  // ---- pass 1: scores and maxima (rows beyond the last cached one read it again)
+  float mx[REP];
+#pragma unroll
+  for (int r = 0; r < REP; ++r) mx[r] = -1.0e30f;
+  for (int j0 = p0 + grp; j0 < pc; j0 += 16 * 8) {
     float kf[8][EL];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) row(kcache, min(j0 + 16 * u, T - 1), kf[u]);
+    for (int u = 0; u < 8; ++u) row(kcache, min(j0 + 16 * u, pc - 1), kf[u]);
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int j = j0 + 16 * u;
-      float dot = 0.f;
 #pragma unroll
-      for (int e = 0; e < EL; ++e) dot = fmaf(kf[u][e], q[e], dot);
-      dot = row16_sum(dot);
-      if (j < T) {
-        if (dl == 0) sc[j] = dot;
-        mx = fmaxf(mx, dot);
+      for (int r = 0; r < REP; ++r) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < EL; ++e) dot = fmaf(kf[u][e], q[r][e], dot);
+        dot = row16_sum(dot);
+        if (j < pc) {
+          if (dl == 0) sc[r * cap + (j - p0)] = dot;
+          mx[r] = fmaxf(mx[r], dot);
+        }
       }
     }
   }
+  if (owner && grp == 0) {
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-  __syncthreads();
-  if ((tid & 63) == 0) red[tid >> 6] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  float ls = 0.f;
-  for (int j = tid; j < T; j += 256) {
-    const float p = __builtin_amdgcn_exp2f(sc[j] - mx);
-    sc[j] = p;
-    ls += p;
-  }
-  const float lsum = block_sum(ls, red + 8);                 // (its barriers also publish sc)
-  float acc[EL];
+    for (int r = 0; r < REP; ++r) {
+      float dot = 0.f;
 #pragma unroll
-  for (int e = 0; e < EL; ++e) acc[e] = 0.f;
-  for (int j0 = grp; j0 < T; j0 += 16 * 8) {
-    float vf[8][EL];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) row(vcache, min(j0 + 16 * u, T - 1), vf[u]);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int j = j0 + 16 * u;
-      const float p = j < T ? sc[j] : 0.f;
-#pragma unroll
-      for (int e = 0; e < EL; ++e) acc[e] = fmaf(p, vf[u][e], acc[e]);
+      for (int e = 0; e < EL; ++e) dot = fmaf(kc[dl * EL + e], q[r][e], dot);
+      dot = row16_sum(dot);
+      if (dl == 0) sc[r * cap + (P - p0)] = dot;
+      mx[r] = fmaxf(mx[r], dot);
     }
   }
 #pragma unroll
-  for (int e = 0; e < EL; ++e) part[grp * HD + dl * EL + e] = acc[e];
-  __syncthreads();
-  if (tid < HD) {
-    float o = part[tid];
+  for (int r = 0; r < REP; ++r) {
 #pragma unroll
-    for (int k = 1; k < 16; ++k) o += part[k * HD + tid];
-    frag_store(o16, qd, b, h * HD + tid, (_Float16)(o / lsum));
+    for (int o = 32; o > 0; o >>= 1) mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], o));
+  }
+  __syncthreads();
+  if ((tid & 63) == 0) {
+#pragma unroll
+    for (int r = 0; r < REP; ++r) red[r * 4 + wv] = mx[r];
+  }
+  __syncthreads();
+  float ls[REP];
+#pragma unroll
+  for (int r = 0; r < REP; ++r) {
+    mx[r] = fmaxf(fmaxf(red[r * 4], red[r * 4 + 1]), fmaxf(red[r * 4 + 2], red[r * 4 + 3]));
+    ls[r] = 0.f;
+  }
+  // ---- pass 2: probabilities and their sums
+  for (int j = tid; j < p1 - p0; j += 256) {
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+      const float p = __builtin_amdgcn_exp2f(sc[r * cap + j] - mx[r]);
+      sc[r * cap + j] = p;
+      ls[r] += p;
+    }
+  }
+  block_sum_k<REP>(ls, red + 32);                              // (its barriers also publish sc)
+  // ---- pass 3: weighted value rows
+  float acc[REP][EL];
+#pragma unroll
+  for (int r = 0; r < REP; ++r)
+#pragma unroll
+    for (int e = 0; e < EL; ++e) acc[r][e] = 0.f;
+  for (int j0 = p0 + grp; j0 < pc; j0 += 16 * 8) {
+    float vf[8][EL];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) row(vcache, min(j0 + 16 * u, pc - 1), vf[u]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + 16 * u;
+#pragma unroll
+      for (int r = 0; r < REP; ++r) {
+        const float p = j < pc ? sc[r * cap + (j - p0)] : 0.f;
+#pragma unroll
+        for (int e = 0; e < EL; ++e) acc[r][e] = fmaf(p, vf[u][e], acc[r][e]);
+      }
+    }
+  }
+  if (owner && grp == 0) {
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+      const float p = sc[r * cap + (P - p0)];
+#pragma unroll
+      for (int e = 0; e < EL; ++e) acc[r][e] = fmaf(p, vc[dl * EL + e], acc[r][e]);
+    }
+  }
+  // the four lane groups of a wavefront (lanes 16 and 32 apart hold the same elements), then the
+  // four wavefronts through LDS
+#pragma unroll
+  for (int r = 0; r < REP; ++r)
+#pragma unroll
+    for (int e = 0; e < EL; ++e) {
+      float v = acc[r][e];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      acc[r][e] = v;
+    }
+  if ((tid & 63) < 16) {
+#pragma unroll
+    for (int r = 0; r < REP; ++r)
+#pragma unroll
+      for (int e = 0; e < EL; ++e) part[(wv * REP + r) * HD + dl * EL + e] = acc[r][e];
+  }
+  float *ml = red;                                             // [REP][2] (max, sum) of this split, for all threads
+  if (tid == 0) {
+#pragma unroll
+    for (int r = 0; r < REP; ++r) { ml[2 * r] = mx[r]; ml[2 * r + 1] = ls[r]; }
+  }
+  __syncthreads();
+  if (n_splits == 1) {
+    for (int t = tid; t < REP * HD; t += 256) {
+      const int r = t / HD, e = t % HD;
+      const float o = ((part[t] + part[REP * HD + t]) + part[2 * REP * HD + t]) + part[3 * REP * HD + t];
+      frag_store(o16, qd, b, (h0 + r) * HD + e, (_Float16)(o / ml[2 * r + 1]));
+    }
+    return;
+  }
+  // ---- several splits: publish the partial result, the last workgroup of the group merges
+  for (int t = tid; t < REP * HD; t += 256) {
+    const int r = t / HD, e = t % HD;
+    const float o = ((part[t] + part[REP * HD + t]) + part[2 * REP * HD + t]) + part[3 * REP * HD + t];
+    const size_t pi = ((size_t)b * nq + h0 + r) * kBdAttnMaxSplits + sp;
+    pub(part_o + pi * HD + e, o);
+  }
+  if (tid < REP) {
+    const size_t pi = ((size_t)b * nq + h0 + tid) * kBdAttnMaxSplits + sp;
+    pub(part_ml + pi * 2, ml[2 * tid]);
+    pub(part_ml + pi * 2 + 1, ml[2 * tid + 1]);
+  }
+  if (!last_arriver(tickets + ((size_t)b * nkv + kvh) * hgs + hg, (unsigned)n_splits, (int *)(red + 60))) return;
+  for (int t = tid; t < REP * HD; t += 256) {
+    const int r = t / HD, e = t % HD;
+    const size_t pb = ((size_t)b * nq + h0 + r) * kBdAttnMaxSplits;
+    float M = -1.0e30f;
+    for (int j = 0; j < n_splits; ++j) M = fmaxf(M, sub(part_ml + (pb + j) * 2));
+    float Ls = 0.f, O = 0.f;
+    for (int j = 0; j < n_splits; ++j) {
+      const float cj = __builtin_amdgcn_exp2f(sub(part_ml + (pb + j) * 2) - M);   // an empty split has sum 0
+      Ls = fmaf(sub(part_ml + (pb + j) * 2 + 1), cj, Ls);
+      O = fmaf(sub(part_o + (pb + j) * HD + e), cj, O);
+    }
+    frag_store(o16, qd, b, (h0 + r) * HD + e, (_Float16)(O / Ls));
   }
 }
 

@@ -275,3 +275,28 @@ def test_batch_wide_matrices_several_row_blocks_per_workgroup(n_seq):
         B.toks = [r[0] for r in res]
     B.compare_caches()
     B.close()
+
+
+REP2B = configs.ModelConfig("rep2-batch-bf16", 2, 512, 8, 4, 64, 1024, 1002, 10000.0, 1e-5,
+                            configs.DTYPE_BF16, 1040, 0, 2.0)
+
+
+@pytest.mark.parametrize("cfg", [HD64B.with_(n_layers=2, max_seq=1040), REP2B], ids=lambda c: c.name)
+def test_batch_long_contexts_attention_splits(cfg):
+    """Contexts up to 1030 positions: the batched attention runs with up to eight splits of the
+    positions (merged by the last workgroup to arrive), some of them empty for the short
+    sequences; two query heads per kv head take the one-head-per-workgroup variant."""
+    say(f"batched decode, long contexts, {cfg.name}")
+    lens = [1020, 3, 300, 517, 129]
+    B = Batch(cfg, len(lens), lens, 251)
+    rng = np.random.default_rng(13)
+    for step in range(3):
+        forced = [int(rng.integers(cfg.min_exit_layer, cfg.n_layers + 1)) for _ in lens]
+        got = B.g.decode_batch(len(lens), B.toks, forced)
+        res = [o.decode_step(t, f) for o, t, f in zip(B.os, B.toks, forced)]
+        hid = np.array([o.hidden() for o in B.os]).transpose(1, 0, 2)
+        B.compare([r[0] for r in res], [r[1] for r in res], [r[2] for r in res], hid,
+                  [o.logits() for o in B.os], got, f"{cfg.name} step {step}")
+        B.toks = [r[0] for r in res]
+    B.compare_caches()
+    B.close()
