@@ -1139,7 +1139,8 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   const int qkv_ld = qd + 2 * c.n_kv_heads * c.head_dim;
   for (int l = 0; l < L; ++l) {
     const DevLayer &W = x->layers_h[l];
-    bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
+    // the norm in front of the QKV GEMM: block 1's here, the others' by the previous block's last kernel
+    if (l == 0) bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
     launch_bd_gemm(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, n);
     {
       const dim3 ga((n * c.n_kv_heads * n_splits + 7) / 8 * 8 * hgs);
@@ -1156,13 +1157,17 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
     // gate and up rows interleaved, SwiGLU in the epilogue: the down projection's input as fp16
     launch_bd_gemm(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, n);
     launch_bd_gemm(x, l, m_d, 1, 0, a16, ffn, h, d, bd::EPI_ADD, n);
-    bd::k_bd_sim<<<dim3(n), dim3(256), 0, s>>>(hprev, h, d, l + 1, L, st, s_of, rec_sims,
-                                               hist + (size_t)(l + 1) * B * d);
-    if (l + 1 >= c.min_exit_layer && l + 1 < L)
+    // similarity, the sequences' own exit decisions, and the norm in front of the next GEMM
+    const bool may_exit = l + 1 >= c.min_exit_layer && l + 1 < L;
+    const bool batch_rule = c.batch_exit_rule == 1;
+    bd::k_bd_block_end<<<dim3(n), dim3(256), 0, s>>>(hprev, h, d, l + 1, L, st, s_of, rec_sims,
+                                                     hist + (size_t)(l + 1) * B * d, may_exit && !batch_rule, c.tau,
+                                                     l + 1 < L ? x->layers_h[l + 1].attn_norm : D.final_norm,
+                                                     c.rms_eps, x16);
+    if (may_exit && batch_rule)
       bd::k_bd_decide<<<dim3(1), dim3(64), 0, s>>>(n, l + 1, L, c.min_exit_layer, c.tau, c.batch_exit_rule, st, s_of);
   }
-  // the original final norm + LM head, greedy token per sequence
-  bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, D.final_norm, d, c.rms_eps, x16);
+  // the original LM head (its input is already normalised), greedy token per sequence
   {
     pf::GemmB Bh{};
     Bh.w[0] = Bh.w[1] = Bh.w[2] = D.lm_head;

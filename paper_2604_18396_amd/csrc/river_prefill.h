@@ -1002,32 +1002,53 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
 }
 
 // After block l1 (1-based), one workgroup per sequence b: s_b = cos(h_prev[b], h[b]) if the row
-// is still in the backbone (recorded, and kept in s_of for the decision); h(l1) of the row is
-// kept (hist, the debug view) and becomes the next block's h_prev.
-__global__ __launch_bounds__(256) void k_bd_sim(float *h_prev, const float *__restrict__ h, int d, int l1, int L,
-                                                SeqState st, float *s_of, float *sims /* [n][L] of this step */,
-                                                float *hist /* [n][d] */) {
+// is still in the backbone (recorded, and kept in s_of for k_bd_decide); h(l1) of the row is
+// kept (hist, the debug view) and becomes the next block's h_prev; with decide != 0 the row's own
+// exit decision (forced position, else s_b > tau; first hit at or above L_s, never at L -- the
+// caller passes decide = 0 outside that range and when Eq. 1's batch rule decides); then the
+// RMSNorm in front of the next GEMM (the next block's attention norm, or the final norm) into
+// xf in fragment order -- its sum of squares is the similarity's <h, h>.
+__global__ __launch_bounds__(256) void k_bd_block_end(float *h_prev, const float *__restrict__ h, int d, int l1, int L,
+                                                      SeqState st, float *s_of, float *sims /* [n][L] of this step */,
+                                                      float *hist /* [n][d] */, int decide, float tau,
+                                                      const void *next_gain, float eps, _Float16 *xf) {
   __shared__ float red[32];
   const int b = blockIdx.x;
   const bool live = st.river[b] == 0;
+  const float *row = h + (size_t)b * d;
   float p3[3] = {0.f, 0.f, 0.f};
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    const float a = h_prev[(size_t)b * d + i], c = h[(size_t)b * d + i];
-    p3[0] = fmaf(a, c, p3[0]); p3[1] = fmaf(a, a, p3[1]); p3[2] = fmaf(c, c, p3[2]);
-    h_prev[(size_t)b * d + i] = c;
-    hist[(size_t)b * d + i] = c;
+  for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {
+    const float4 a = *(const float4 *)(h_prev + (size_t)b * d + i), c = *(const float4 *)(row + i);
+    p3[0] += (a.x * c.x + a.y * c.y) + (a.z * c.z + a.w * c.w);
+    p3[1] += (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
+    p3[2] += (c.x * c.x + c.y * c.y) + (c.z * c.z + c.w * c.w);
+    *(float4 *)(h_prev + (size_t)b * d + i) = c;
+    *(float4 *)(hist + (size_t)b * d + i) = c;
   }
-  if (!live) return;                                          // uniform per workgroup
   block_sum_k<3>(p3, red);
-  float s = 0.f;
-  if (p3[1] > 0.f && p3[2] > 0.f) s = fminf(1.0f, fmaxf(-1.0f, p3[0] / (sqrtf(p3[1]) * sqrtf(p3[2]))));
-  if (threadIdx.x == 0) {
+  if (live && threadIdx.x == 0) {
+    float s = 0.f;
+    if (p3[1] > 0.f && p3[2] > 0.f) s = fminf(1.0f, fmaxf(-1.0f, p3[0] / (sqrtf(p3[1]) * sqrtf(p3[2]))));
     s_of[b] = s;
     sims[(size_t)b * L + (l1 - 1)] = s;
+    if (decide) {
+      const int f = st.forced[b];
+      if (f >= 0 ? f == l1 : s > tau) { st.river[b] = 1; st.exit_pos[b] = l1; }
+    }
+  }
+  const float r = 1.0f / sqrtf(p3[2] / (float)d + eps);
+  for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
+    const float4 a = *(const float4 *)(row + k), c = *(const float4 *)(row + k + 4);
+    const float v[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+    half8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (_Float16)(v[j] * r * Store<1>::ld(next_gain, k + j));
+    frag_store8(xf, d, b, k, o);
   }
 }
 
-// The exit decision after backbone block l1 from the similarities k_bd_sim left.  rule 0: every
+// The exit decision after backbone block l1 from the similarities k_bd_block_end left (launched
+// when Eq. 1's batch rule is in force).  rule 0: every
 // sequence for itself (s_b > tau); rule 1: Eq. 1 as printed, the whole batch leaves together
 // once min_b s_b > tau.  A forced exit position overrides the threshold for its sequence.
 // First hit at or above L_s, never at L, strict '>'.  One wavefront.
