@@ -204,6 +204,19 @@ __global__ void k_pack_sz(const void *scale, const void *zero, void *out, long l
     ((typename Store<DT>::SZ *)out)[i] = Store<DT>::pack(Store<DT>::ld(scale, i), Store<DT>::ld(zero, i));
 }
 
+// The same pairs in the order the batched 4-bit GEMM fetches them (bf16 models): per K tile of
+// 128 columns and row, the pairs of the tile's two 64-column halves -- [tile][row][2] -- so that
+// the 16 rows of an MFMA block find theirs in one 128-byte line.
+__global__ void k_pack_sz_tiles(const void *scale, const void *zero, uint32_t *out, int rows, int cols, int group) {
+  const int gpr = (cols + group - 1) / group, tiles = (cols + 127) / 128;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long long)tiles * rows * 2) return;
+  const int j = (int)(i & 1), r = (int)((i >> 1) % rows), kt = (int)((i >> 1) / rows);
+  const int k = kt * 128 + j * 64;
+  const size_t src = (size_t)r * gpr + min(k / group, gpr - 1);
+  out[i] = Store<1>::pack(Store<1>::ld(scale, src), Store<1>::ld(zero, src));
+}
+
 // River construction: one thread per quantisation group.
 template <int DT>
 __global__ void k_quantize_w4(const void *w, long long rows, int cols, int group, uint8_t *codes,
@@ -250,6 +263,7 @@ struct Layout {
   size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part,
       amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
+  size_t bd_qszt, bd_qszt_bytes;         // batched contexts: the pairs in K-tile order (k_pack_sz_tiles)
   // activation buffers of the GEMM prefill (pf_rows rows each; 0 rows: that path is not offered)
   size_t pf_tok, pf_h, pf_x16, pf_q16, pf_a16, pf_big;
   int pf_rows;
@@ -346,6 +360,7 @@ struct river_ctx {
   bool broken;
   std::string err;
   std::vector<DevLayer> layers_h;   // host copy of the per-block pointer table (GEMM prefill launches)
+  std::vector<const void *> qszt_h; // [L][7] the (scale, zero) pairs in K-tile order (batched contexts)
   std::vector<int> pos_b;           // batched contexts: positions in the cache, per sequence
   long long steps_b = 0;            // batched decode steps recorded so far
   int last_n = 0;                   // sequences of the last batched step
@@ -421,6 +436,12 @@ static size_t qsz_matrix_bytes(const river_config *c, int m) {
   return (size_t)(rows * gpr) * (c->dtype == RIVER_BF16 ? 4 : 8);
 }
 
+static size_t qszt_matrix_bytes(const river_config *c, int m) {
+  long long rows, cols;
+  matrix_shape(c, m, &rows, &cols);
+  return (size_t)((cols + 127) / 128) * rows * 2 * 4;
+}
+
 static Layout make_layout(const river_config *c) {
   Layout y{};
   const size_t es = c->dtype == RIVER_BF16 ? 2 : 4;
@@ -479,6 +500,10 @@ static Layout make_layout(const river_config *c) {
     y.bd_rec_token = take((size_t)bd::kRecordsB * B * 4);
     y.bd_rec_exit = take((size_t)bd::kRecordsB * B * 4);
     y.bd_rec_sims = take((size_t)bd::kRecordsB * B * c->n_layers * 4);
+    y.bd_qszt_bytes = 0;
+    for (int m = 0; m < 7; ++m) y.bd_qszt_bytes += align_up(qszt_matrix_bytes(c, m), 256);
+    y.bd_qszt_bytes *= (size_t)c->n_layers;
+    y.bd_qszt = take(y.bd_qszt_bytes);
   }
   y.total = off;
   return y;
@@ -725,6 +750,25 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
         off += align_up(bytes, 256);
       }
     if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) packing", e);
+  }
+  x->qszt_h.assign((size_t)L * 7, nullptr);
+  if (cfg->max_batch > 1) {
+    size_t off = lay.bd_qszt;
+    for (int l = 0; l < L; ++l)
+      for (int m = 0; m < 7; ++m) {
+        const size_t bytes = qszt_matrix_bytes(cfg, m);
+        if (hl[l].qc[m] && hqs[(size_t)l * 7 + m] && hqz[(size_t)l * 7 + m]) {
+          long long rows, cols;
+          matrix_shape(cfg, m, &rows, &cols);
+          const long long n = (long long)(bytes / 4);
+          k_pack_sz_tiles<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, x->stream>>>(
+              hqs[(size_t)l * 7 + m], hqz[(size_t)l * 7 + m], (uint32_t *)(ws + off), (int)rows, (int)cols,
+              cfg->river_group);
+          x->qszt_h[(size_t)l * 7 + m] = ws + off;
+        }
+        off += align_up(bytes, 256);
+      }
+    if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) tile packing", e);
   }
   x->layers_h = hl;
   x->pos_b.assign(cfg->max_batch, 0);
@@ -1048,9 +1092,11 @@ static void launch_bd_gemm_b(river_ctx *x, const pf::GemmB &Bd, const pf::GemmB 
 #define RIVER_BD_LAUNCH(MB, RBW)                                                                                      \
   bd::k_bd_gemm<MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, Bd, Bq, interleaved, N, K, g, C, ldc, epi, \
                                                                           rv, by_flag, n, rows_per_wg)
+  // passes of eight row blocks address the rows by a stride: one matrix, or the interleaved pair
+  const bool strided_ok = interleaved || (Bd.rows[1] == 0 && Bd.rows[2] == 0);
   if (n <= 16) {
     if (blocks <= 1) RIVER_BD_LAUNCH(1, 1);
-    else if (blocks <= 2) RIVER_BD_LAUNCH(1, 2);
+    else if (blocks <= 2 || !strided_ok) RIVER_BD_LAUNCH(1, 2);
     else RIVER_BD_LAUNCH(1, 8);
   } else {
     if (blocks <= 1) RIVER_BD_LAUNCH(2, 1);
@@ -1067,7 +1113,7 @@ static void launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, int inter
     matrix_shape(&x->cfg, ms[i], &r, &c);
     Bd.w[i] = x->layers_h[l].w[ms[i]];
     Bq.w[i] = x->layers_h[l].qc[ms[i]];
-    Bq.sz[i] = x->layers_h[l].qsz[ms[i]];
+    Bq.sz[i] = x->qszt_h[(size_t)l * 7 + ms[i]];
     Bd.rows[i] = Bq.rows[i] = (int)r;
     N += (int)r;
   }

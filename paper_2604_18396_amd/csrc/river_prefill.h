@@ -561,8 +561,8 @@ __global__ __launch_bounds__(256) void k_bd_rmsnorm(const float *__restrict__ h,
 enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
 constexpr int kBdWaves = 8;
 template <int RBW, int MB> struct BdDepth {                 // K tiles in flight per wavefront (register budget)
-  static constexpr int dense = MB == 1 ? (RBW == 1 ? 8 : RBW == 2 ? 5 : 2) : (RBW == 1 ? 5 : 3);
-  static constexpr int w4 = MB == 1 ? (RBW == 1 ? 6 : RBW == 2 ? 4 : 2) : (RBW == 1 ? 4 : 3);
+  static constexpr int dense = MB == 1 ? (RBW == 1 ? 8 : RBW == 2 ? 5 : 2) : (RBW == 1 ? 4 : 3);
+  static constexpr int w4 = MB == 1 ? (RBW == 1 ? 6 : RBW == 2 ? 4 : 2) : (RBW == 1 ? 3 : 3);
 };
 __host__ __device__ inline size_t bd_gemm_lds_bytes(int rbw, int mb) { return (size_t)kBdWaves * rbw * mb * 256 * 4; }
 
@@ -582,23 +582,38 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
   const int kl = W4 ? kg * 32 : kg * 8;
   struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint32_t sz[W4 ? RBW : 1]; };
   for (int p0 = wg_r0; p0 < wg_r1; p0 += RBW * 16) {
-    const char *bp[RBW], *szp[RBW];
-    bool ok[RBW];
+    // Row pointers of this lane's RBW rows (n = p0 + 16 rb + lane % 16).  Passes of more than two
+    // blocks are only launched on a single matrix or an interleaved pair, where the rows of
+    // consecutive blocks are a fixed distance apart: one pointer and a stride instead of RBW.
+    constexpr bool STRIDED = RBW > 2;
+    constexpr int NP = STRIDED ? 1 : RBW;
+    const char *bp[NP], *szp[NP];
+    unsigned szs[NP];                                         // bytes of one K tile of the pair table
+    size_t bstride = 0;
+    unsigned sstride = 0;
 #pragma unroll
-    for (int rb = 0; rb < RBW; ++rb) {
+    for (int rb = 0; rb < NP; ++rb) {
       const int n = p0 + rb * 16 + r16;
-      ok[rb] = n < wg_r1;
       int mat, r;
-      if (interleaved) { mat = min(n, N - 1) & 1; r = min(n, N - 1) >> 1; }
+      if (interleaved) { mat = n & 1; r = n >> 1; }
+      else if (STRIDED) { mat = 0; r = n; }
       else gemm_b_row(B, n, N, mat, r);
+      const size_t row_bytes = W4 ? (size_t)(K >> 1) : (size_t)K * 2;
+      bp[rb] = (const char *)B.w[mat] + (size_t)r * row_bytes + (W4 ? (kl >> 1) : kl * 2);
+      bstride = (interleaved ? 8 : 16) * row_bytes;
       if constexpr (W4) {
-        bp[rb] = (const char *)B.w[mat] + (size_t)r * (K >> 1) + (kl >> 1);
-        szp[rb] = (const char *)B.sz[mat] + (size_t)r * (K / group) * 4;
+        szp[rb] = (const char *)B.sz[mat] + ((size_t)r * 2 + (kg >> 1)) * 4;    // [K tile][row][half], see k_pack_sz_tiles
+        szs[rb] = (unsigned)B.rows[mat] * 8u;
+        sstride = (interleaved ? 8 : 16) * 8;
       } else {
-        bp[rb] = (const char *)B.w[mat] + ((size_t)r * K + kl) * 2;
         szp[rb] = nullptr;
+        szs[rb] = 0;
       }
     }
+    auto row_ok = [&](int rb) { return p0 + rb * 16 + r16 < wg_r1; };
+    auto b_ptr = [&](int rb) { return STRIDED ? bp[0] + (size_t)rb * bstride : bp[rb < NP ? rb : 0]; };
+    auto sz_ptr = [&](int rb) { return STRIDED ? szp[0] + (unsigned)rb * sstride : szp[rb < NP ? rb : 0]; };
+    auto sz_tile = [&](int rb) { return szs[STRIDED ? 0 : (rb < NP ? rb : 0)]; };
     auto load = [&](int kt, Stage &t) {
       const int k0 = kt * TILE;
       const bool kok = k0 + kl + (W4 ? 32 : 8) <= K;          // dense: also the second step's columns, K % 64 == 0
@@ -610,13 +625,13 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb) {
         if constexpr (W4) {
-          const bool v = ok[rb] && kok;
-          t.b[rb] = v ? ld_stream16(bp[rb] + (k0 >> 1)) : make_uint4(0, 0, 0, 0);
-          t.sz[rb] = v ? *RIVER_GLOBAL(uint32_t, szp[rb] + (size_t)((k0 + kl) / group) * 4) : 0u;
+          const bool v = row_ok(rb) && kok;
+          t.b[rb] = v ? ld_stream16(b_ptr(rb) + (k0 >> 1)) : make_uint4(0, 0, 0, 0);
+          t.sz[rb] = v ? *RIVER_GLOBAL(uint32_t, sz_ptr(rb) + (unsigned)kt * sz_tile(rb)) : 0u;
         } else {
 #pragma unroll
           for (int s = 0; s < 2; ++s)
-            t.b[rb * 2 + s] = ok[rb] && kok ? ld_stream16(bp[rb] + (size_t)(k0 + s * 32) * 2) : make_uint4(0, 0, 0, 0);
+            t.b[rb * 2 + s] = row_ok(rb) && kok ? ld_stream16(b_ptr(rb) + (size_t)(k0 + s * 32) * 2) : make_uint4(0, 0, 0, 0);
         }
       }
     };
