@@ -263,6 +263,7 @@ struct Layout {
   size_t kcache, vcache, rope, hidden, qbuf, obuf, kvcur, h1, abuf, logits, part_o, part_ml, cos_part,
       amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
+  size_t bd_partial;                     // [kBdKSplit][32][d_model] partial sums of the K-sliced GEMMs
   size_t bd_qszt, bd_qszt_bytes;         // batched contexts: the pairs in K-tile order (k_pack_sz_tiles)
   // activation buffers of the GEMM prefill (pf_rows rows each; 0 rows: that path is not offered)
   size_t pf_tok, pf_h, pf_x16, pf_q16, pf_a16, pf_big;
@@ -500,6 +501,7 @@ static Layout make_layout(const river_config *c) {
     y.bd_rec_token = take((size_t)bd::kRecordsB * B * 4);
     y.bd_rec_exit = take((size_t)bd::kRecordsB * B * 4);
     y.bd_rec_sims = take((size_t)bd::kRecordsB * B * c->n_layers * 4);
+    y.bd_partial = take((size_t)bd::kBdKSplit * bd::kRows * c->d_model * 4);
     y.bd_qszt_bytes = 0;
     for (int m = 0; m < 7; ++m) y.bd_qszt_bytes += align_up(qszt_matrix_bytes(c, m), 256);
     y.bd_qszt_bytes *= (size_t)c->n_layers;
@@ -1080,32 +1082,42 @@ extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const in
 // interleaved row by row for the gate/up pair): bf16 matrices for the rows in the backbone,
 // 4-bit twins for the others (see bd::k_bd_gemm).  The rows of B are dealt out to one
 // workgroup per CU, eight at a time.
-static void launch_bd_gemm_b(river_ctx *x, const pf::GemmB &Bd, const pf::GemmB &Bq, int interleaved, int N,
-                             const _Float16 *Af, int K, void *C, int ldc, int epi, int by_flag, int n) {
-  const int per_cu = (N + x->grid_persist - 1) / x->grid_persist;
+static int launch_bd_gemm_b(river_ctx *x, const pf::GemmB &Bd, const pf::GemmB &Bq, int interleaved, int N,
+                            const _Float16 *Af, int K, void *C, int ldc, int epi, int by_flag, int n) {
+  // A matrix with at most 16 rows per CU (output and down projection) would have every workgroup
+  // read the whole activation tile for a single row block; it is dealt out as K slices of four
+  // times the rows instead, and the kernel that consumes the sum adds the partial sums up.
+  const bool single = Bd.rows[1] == 0 && Bd.rows[2] == 0;
+  int k_split = 1;
+  if (epi == bd::EPI_ADD && single && N <= 16 * x->grid_persist && K >= 4096 && ldc == x->cfg.d_model)
+    k_split = bd::kBdKSplit;
+  const int per_cu = (N * k_split + x->grid_persist - 1) / x->grid_persist;
   const int rows_per_wg = std::max(8, (per_cu + 7) / 8 * 8);
   const int blocks = (rows_per_wg + 15) / 16;
-  const dim3 grid((N + rows_per_wg - 1) / rows_per_wg), blk(512);
+  const dim3 grid((N + rows_per_wg - 1) / rows_per_wg * k_split), blk(512);
   hipStream_t s = x->stream;
   const int g = x->cfg.river_group;
   const int *rv = x->st_b.river;
+  if (k_split > 1) { C = x->ws + x->lay.bd_partial; epi = bd::EPI_STORE; }
 #define RIVER_BD_LAUNCH(MB, RBW)                                                                                      \
   bd::k_bd_gemm<MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, Bd, Bq, interleaved, N, K, g, C, ldc, epi, \
-                                                                          rv, by_flag, n, rows_per_wg)
+                                                                          rv, by_flag, n, rows_per_wg, k_split)
   // passes of eight row blocks address the rows by a stride: one matrix, or the interleaved pair
-  const bool strided_ok = interleaved || (Bd.rows[1] == 0 && Bd.rows[2] == 0);
+  const bool strided_ok = interleaved || single;
   if (n <= 16) {
     if (blocks <= 1) RIVER_BD_LAUNCH(1, 1);
     else if (blocks <= 2 || !strided_ok) RIVER_BD_LAUNCH(1, 2);
+    else if (blocks <= 4) RIVER_BD_LAUNCH(1, 4);
     else RIVER_BD_LAUNCH(1, 8);
   } else {
     if (blocks <= 1) RIVER_BD_LAUNCH(2, 1);
     else RIVER_BD_LAUNCH(2, 2);
   }
 #undef RIVER_BD_LAUNCH
+  return k_split > 1 ? k_split : 0;          // partial sums the consumer has to add
 }
-static void launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, int interleaved, const _Float16 *Af, int K,
-                           void *C, int ldc, int epi, int n) {
+static int launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, int interleaved, const _Float16 *Af, int K,
+                          void *C, int ldc, int epi, int n) {
   pf::GemmB Bd{}, Bq{};
   int N = 0;
   for (int i = 0; i < nm; ++i) {
@@ -1118,7 +1130,7 @@ static void launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, int inter
     N += (int)r;
   }
   for (int i = nm; i < 3; ++i) { Bd.w[i] = Bd.w[0]; Bq.w[i] = Bq.w[0]; Bq.sz[i] = Bq.sz[0]; }
-  launch_bd_gemm_b(x, Bd, Bq, interleaved, N, Af, K, C, ldc, epi, 1, n);
+  return launch_bd_gemm_b(x, Bd, Bq, interleaved, N, Af, K, C, ldc, epi, 1, n);
 }
 
 extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in_tokens, const int32_t *forced_exit,
@@ -1155,6 +1167,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   float *hprev = (float *)(x->ws + y.bd_hprev);
   float *part_o = (float *)(x->ws + y.bd_part_o), *part_ml = (float *)(x->ws + y.bd_part_ml);
   unsigned int *tickets = (unsigned int *)(x->ws + y.bd_tickets);
+  const float *partial = (const float *)(x->ws + y.bd_partial);
   float *logits = (float *)(x->ws + y.bd_logits), *hist = (float *)(x->ws + y.bd_hist);
   _Float16 *x16 = (_Float16 *)(x->ws + y.pf_x16), *o16 = (_Float16 *)(x->ws + y.pf_q16);
   _Float16 *a16 = (_Float16 *)(x->ws + y.pf_a16);
@@ -1186,7 +1199,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   for (int l = 0; l < L; ++l) {
     const DevLayer &W = x->layers_h[l];
     // the norm in front of the QKV GEMM: block 1's here, the others' by the previous block's last kernel
-    if (l == 0) bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16);
+    if (l == 0) bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16, nullptr, 0);
     launch_bd_gemm(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, n);
     {
       const dim3 ga((n * c.n_kv_heads * n_splits + 7) / 8 * 8 * hgs);
@@ -1198,18 +1211,18 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
       attn<<<ga, dim3(256), attn_lds, s>>>(big, D.rope, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq,
                                            seq_stride, st.pos, n_splits, attn_cap, part_o, part_ml, tickets, o16);
     }
-    launch_bd_gemm(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, n);
-    bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16);
+    const int po = launch_bd_gemm(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, n);
+    bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16, partial, po);
     // gate and up rows interleaved, SwiGLU in the epilogue: the down projection's input as fp16
     launch_bd_gemm(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, n);
-    launch_bd_gemm(x, l, m_d, 1, 0, a16, ffn, h, d, bd::EPI_ADD, n);
+    const int pd = launch_bd_gemm(x, l, m_d, 1, 0, a16, ffn, h, d, bd::EPI_ADD, n);
     // similarity, the sequences' own exit decisions, and the norm in front of the next GEMM
     const bool may_exit = l + 1 >= c.min_exit_layer && l + 1 < L;
     const bool batch_rule = c.batch_exit_rule == 1;
     bd::k_bd_block_end<<<dim3(n), dim3(256), 0, s>>>(hprev, h, d, l + 1, L, st, s_of, rec_sims,
                                                      hist + (size_t)(l + 1) * B * d, may_exit && !batch_rule, c.tau,
                                                      l + 1 < L ? x->layers_h[l + 1].attn_norm : D.final_norm,
-                                                     c.rms_eps, x16);
+                                                     c.rms_eps, x16, partial, pd);
     if (may_exit && batch_rule)
       bd::k_bd_decide<<<dim3(1), dim3(64), 0, s>>>(n, l + 1, L, c.min_exit_layer, c.tau, c.batch_exit_rule, st, s_of);
   }

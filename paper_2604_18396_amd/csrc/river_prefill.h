@@ -517,26 +517,65 @@ __device__ __forceinline__ void frag_store8(_Float16 *xf, int K, int m, int k, h
 
 // xf[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain) in fragment order (both);
 // one workgroup (256) per sequence row; d % 8 == 0
-__global__ __launch_bounds__(256) void k_bd_rmsnorm(const float *__restrict__ h, const void *gain, int d, float eps,
-                                                    _Float16 *xf) {
+// The row-wise kernels of a batched step (one workgroup of 256 per sequence row) read their row
+// once: thread t owns columns 8 t + 2048 i .. + 7 and keeps up to kRowKeep such runs in registers
+// between the reduction and the second use (rows longer than 2048 kRowKeep columns are read
+// again).  n_part > 0: the partial sums [n_part][32][d] of the K-sliced GEMM that adds into h are
+// added first, in order, and h is updated.
+constexpr int kRowKeep = 4;
+struct Run8 { float v[8]; };
+__device__ __forceinline__ Run8 load_run8(float *row, const float *part, int n_part, int t, int d, int k) {
+  float4 a = *(const float4 *)(row + k), b = *(const float4 *)(row + k + 4);
+  if (n_part > 0) {
+    for (int j = 0; j < n_part; ++j) {
+      const float *p = part + ((size_t)j * kRows + t) * d + k;
+      const float4 pa = *(const float4 *)p, pb = *(const float4 *)(p + 4);
+      a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
+      b.x += pb.x; b.y += pb.y; b.z += pb.z; b.w += pb.w;
+    }
+    *(float4 *)(row + k) = a;
+    *(float4 *)(row + k + 4) = b;
+  }
+  return Run8{{a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w}};
+}
+__device__ __forceinline__ void norm_store_run8(const Run8 &x, float r, const void *gain, _Float16 *xf, int d, int t, int k) {
+  half8 o;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = (_Float16)(x.v[j] * r * Store<1>::ld(gain, k + j));
+  frag_store8(xf, d, t, k, o);
+}
+
+// xf[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain) in fragment order (both); d % 8 == 0
+__global__ __launch_bounds__(256) void k_bd_rmsnorm(float *__restrict__ h, const void *gain, int d, float eps,
+                                                    _Float16 *xf, const float *__restrict__ part, int n_part) {
   __shared__ float red[16];
   const int t = blockIdx.x;
-  const float *row = h + (size_t)t * d;
+  float *row = h + (size_t)t * d;
+  Run8 keep[kRowKeep];
   float ss = 0.f;
-  for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {
-    const float4 v = *(const float4 *)(row + i);
-    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+#pragma unroll
+  for (int i = 0; i < kRowKeep; ++i) {
+    const int k = threadIdx.x * 8 + i * 2048;
+    if (k < d) {
+      keep[i] = load_run8(row, part, n_part, t, d, k);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) ss = fmaf(keep[i].v[j], keep[i].v[j], ss);
+    }
+  }
+  for (int k = threadIdx.x * 8 + kRowKeep * 2048; k < d; k += 2048) {
+    const Run8 x = load_run8(row, part, n_part, t, d, k);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ss = fmaf(x.v[j], x.v[j], ss);
   }
   const float tot = block_sum(ss, red);
   const float r = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
-    const float4 a = *(const float4 *)(row + k), b = *(const float4 *)(row + k + 4);
-    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    half8 o;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = (_Float16)(v[j] * r * Store<1>::ld(gain, k + j));
-    frag_store8(xf, d, t, k, o);
+  for (int i = 0; i < kRowKeep; ++i) {
+    const int k = threadIdx.x * 8 + i * 2048;
+    if (k < d) norm_store_run8(keep[i], r, gain, xf, d, t, k);
   }
+  for (int k = threadIdx.x * 8 + kRowKeep * 2048; k < d; k += 2048)    // updated by this thread itself above
+    norm_store_run8(load_run8(row, nullptr, 0, t, d, k), r, gain, xf, d, t, k);
 }
 
 // C[rows, N] (op)= A[rows, K] B^T for the rows r < n_rows with river[r] == want (want < 0: all
@@ -560,9 +599,10 @@ __global__ __launch_bounds__(256) void k_bd_rmsnorm(const float *__restrict__ h,
 // then its column count).
 enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
 constexpr int kBdWaves = 8;
+constexpr int kBdKSplit = 4;                                // K slices of the narrow GEMMs (see k_bd_gemm)
 template <int RBW, int MB> struct BdDepth {                 // K tiles in flight per wavefront (register budget)
-  static constexpr int dense = MB == 1 ? (RBW == 1 ? 8 : RBW == 2 ? 5 : 2) : (RBW == 1 ? 4 : 3);
-  static constexpr int w4 = MB == 1 ? (RBW == 1 ? 6 : RBW == 2 ? 4 : 2) : (RBW == 1 ? 3 : 3);
+  static constexpr int dense = MB == 1 ? (RBW == 1 ? 8 : RBW == 2 ? 5 : RBW == 4 ? 3 : 2) : (RBW == 1 ? 4 : 3);
+  static constexpr int w4 = MB == 1 ? (RBW == 1 ? 6 : RBW == 2 ? 4 : RBW == 4 ? 3 : 2) : (RBW == 1 ? 3 : 3);
 };
 __host__ __device__ inline size_t bd_gemm_lds_bytes(int rbw, int mb) { return (size_t)kBdWaves * rbw * mb * 256 * 4; }
 
@@ -570,14 +610,18 @@ template <bool W4, int MB, int RBW>
 __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, const GemmB &B, int interleaved, int N,
                                              int K, int group, void *C, int ldc, int epi,
                                              const int *__restrict__ river, int want, int n_rows, int rows_per_wg,
-                                             float *red /* [kBdWaves][RBW][MB][256] */) {
+                                             int k_split, float *red /* [kBdWaves][RBW][MB][256] */) {
   constexpr int P = W4 ? BdDepth<RBW, MB>::w4 : BdDepth<RBW, MB>::dense;
   constexpr int TILE = W4 ? 128 : 64;                         // columns per K tile
   constexpr int NA = W4 ? 4 : 2;                              // MFMA steps (16-byte A fragments) per tile
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
-  const int wg_r0 = blockIdx.x * rows_per_wg, wg_r1 = min(N, wg_r0 + rows_per_wg);
-  const int nkt = (K + TILE - 1) / TILE;
+  // workgroup -> (group of rows, slice of K): with k_split > 1 the output is a partial sum, stored
+  // as rows 32 ks .. of C for the consumer to add up (see k_bd_rmsnorm)
+  const int ks = blockIdx.x % k_split;
+  const int wg_r0 = (blockIdx.x / k_split) * rows_per_wg, wg_r1 = min(N, wg_r0 + rows_per_wg);
+  const int nkt_all = (K + TILE - 1) / TILE;
+  const int kt0 = (int)((long long)nkt_all * ks / k_split), nkt = (int)((long long)nkt_all * (ks + 1) / k_split);
   // this lane's column offset inside a K tile (elements)
   const int kl = W4 ? kg * 32 : kg * 8;
   struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint32_t sz[W4 ? RBW : 1]; };
@@ -669,8 +713,8 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
     Stage st[P];
 #pragma unroll
     for (int u = 0; u < P; ++u)
-      if (wv + kBdWaves * u < nkt) load(wv + kBdWaves * u, st[u]);
-    for (int kt = wv; kt < nkt; kt += kBdWaves * P) {
+      if (kt0 + wv + kBdWaves * u < nkt) load(kt0 + wv + kBdWaves * u, st[u]);
+    for (int kt = kt0 + wv; kt < nkt; kt += kBdWaves * P) {
 #pragma unroll
       for (int u = 0; u < P; ++u) {
         const int k = kt + kBdWaves * u;
@@ -706,7 +750,7 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
         const float g = total(e), u = total(e + 1);
         frag_store((_Float16 *)C, ldc, row, n >> 1, (_Float16)(g / (1.0f + expf(-g)) * u));
       } else {
-        float *p = (float *)C + (size_t)row * ldc + n;
+        float *p = (float *)C + (size_t)(k_split > 1 ? ks * kRows + row : row) * ldc + n;
         const float v = total(e);
         if (epi == EPI_ADD) *p += v;
         else *p = v;
@@ -718,12 +762,14 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
 // One launch per GEMM of a step: the bf16 matrices for the rows still in the backbone, then the
 // 4-bit twins for the rows that have left it (by_flag; otherwise the bf16 matrices for all
 // rows, as the LM head needs).  A side without rows is not read.  Af: both fragment orders of
-// the activations (see frag_halfs).
+// the activations (see frag_halfs).  k_split > 1: narrow matrices (16 rows per CU would leave every
+// workgroup reading all of A for one row block) are dealt out as k_split K slices of four times
+// the rows; C is then the partial-sum buffer [k_split][32][ldc].
 template <int MB, int RBW>
 __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af, GemmB Bd, GemmB Bq, int interleaved,
                                                  int N, int K, int group, void *C, int ldc, int epi,
                                                  const int *__restrict__ river, int by_flag, int n_rows,
-                                                 int rows_per_wg) {
+                                                 int rows_per_wg, int k_split) {
   extern __shared__ float red[];
   __shared__ int any[2];
   if (threadIdx.x < 2) any[threadIdx.x] = 0;
@@ -732,11 +778,11 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af
   __syncthreads();
   const bool dense = any[0] != 0, twin = any[1] != 0;
   if (dense) bd_gemm_pass<false, MB, RBW>(Af, Bd, interleaved, N, K, group, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
-                                          rows_per_wg, red);
+                                          rows_per_wg, k_split, red);
   if (twin) {
     __syncthreads();                                          // the partial tiles of the first pass have been read
     bd_gemm_pass<true, MB, RBW>(Af + frag_halfs(K), Bq, interleaved, N, K, group, C, ldc, epi, river, 1, n_rows,
-                                rows_per_wg, red);
+                                rows_per_wg, k_split, red);
   }
 }
 
@@ -1023,23 +1069,37 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
 // caller passes decide = 0 outside that range and when Eq. 1's batch rule decides); then the
 // RMSNorm in front of the next GEMM (the next block's attention norm, or the final norm) into
 // xf in fragment order -- its sum of squares is the similarity's <h, h>.
-__global__ __launch_bounds__(256) void k_bd_block_end(float *h_prev, const float *__restrict__ h, int d, int l1, int L,
+__global__ __launch_bounds__(256) void k_bd_block_end(float *h_prev, float *__restrict__ h, int d, int l1, int L,
                                                       SeqState st, float *s_of, float *sims /* [n][L] of this step */,
                                                       float *hist /* [n][d] */, int decide, float tau,
-                                                      const void *next_gain, float eps, _Float16 *xf) {
+                                                      const void *next_gain, float eps, _Float16 *xf,
+                                                      const float *__restrict__ part, int n_part) {
   __shared__ float red[32];
   const int b = blockIdx.x;
   const bool live = st.river[b] == 0;
-  const float *row = h + (size_t)b * d;
+  float *row = h + (size_t)b * d;
   float p3[3] = {0.f, 0.f, 0.f};
-  for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {
-    const float4 a = *(const float4 *)(h_prev + (size_t)b * d + i), c = *(const float4 *)(row + i);
-    p3[0] += (a.x * c.x + a.y * c.y) + (a.z * c.z + a.w * c.w);
-    p3[1] += (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
-    p3[2] += (c.x * c.x + c.y * c.y) + (c.z * c.z + c.w * c.w);
-    *(float4 *)(h_prev + (size_t)b * d + i) = c;
-    *(float4 *)(hist + (size_t)b * d + i) = c;
+  // one run: the sums of Eq. 1's similarity, h(l1) into h_prev and the debug view
+  auto take = [&](int k) {
+    const float4 a0 = *(const float4 *)(h_prev + (size_t)b * d + k), a1 = *(const float4 *)(h_prev + (size_t)b * d + k + 4);
+    const Run8 c = load_run8(row, part, n_part, b, d, k);      // (adds the down projection's partial sums)
+    const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      p3[0] = fmaf(a[j], c.v[j], p3[0]); p3[1] = fmaf(a[j], a[j], p3[1]); p3[2] = fmaf(c.v[j], c.v[j], p3[2]);
+    }
+    const float4 c0 = make_float4(c.v[0], c.v[1], c.v[2], c.v[3]), c1 = make_float4(c.v[4], c.v[5], c.v[6], c.v[7]);
+    *(float4 *)(h_prev + (size_t)b * d + k) = c0; *(float4 *)(h_prev + (size_t)b * d + k + 4) = c1;
+    *(float4 *)(hist + (size_t)b * d + k) = c0; *(float4 *)(hist + (size_t)b * d + k + 4) = c1;
+    return c;
+  };
+  Run8 keep[kRowKeep];
+#pragma unroll
+  for (int i = 0; i < kRowKeep; ++i) {
+    const int k = threadIdx.x * 8 + i * 2048;
+    if (k < d) keep[i] = take(k);
   }
+  for (int k = threadIdx.x * 8 + kRowKeep * 2048; k < d; k += 2048) (void)take(k);
   block_sum_k<3>(p3, red);
   if (live && threadIdx.x == 0) {
     float s = 0.f;
@@ -1052,14 +1112,13 @@ __global__ __launch_bounds__(256) void k_bd_block_end(float *h_prev, const float
     }
   }
   const float r = 1.0f / sqrtf(p3[2] / (float)d + eps);
-  for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
-    const float4 a = *(const float4 *)(row + k), c = *(const float4 *)(row + k + 4);
-    const float v[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
-    half8 o;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = (_Float16)(v[j] * r * Store<1>::ld(next_gain, k + j));
-    frag_store8(xf, d, b, k, o);
+  for (int i = 0; i < kRowKeep; ++i) {
+    const int k = threadIdx.x * 8 + i * 2048;
+    if (k < d) norm_store_run8(keep[i], r, next_gain, xf, d, b, k);
   }
+  for (int k = threadIdx.x * 8 + kRowKeep * 2048; k < d; k += 2048)    // updated by this thread itself above
+    norm_store_run8(load_run8(row, nullptr, 0, b, d, k), r, next_gain, xf, d, b, k);
 }
 
 // The exit decision after backbone block l1 from the similarities k_bd_block_end left (launched
