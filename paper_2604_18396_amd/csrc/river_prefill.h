@@ -1148,7 +1148,21 @@ __global__ __launch_bounds__(256) void k_bd_argmax(const float *__restrict__ log
   const int b = blockIdx.x;
   float best = -INFINITY;
   int besti = 0x7fffffff;
-  for (int i = threadIdx.x; i < vocab; i += blockDim.x) argmax_take(best, besti, logits[(size_t)b * vocab + i], i);
+  const float *row = logits + (size_t)b * vocab;
+  // eight loads in flight per thread (the scan is a chain of load latencies otherwise)
+  for (int i0 = threadIdx.x; i0 < vocab; i0 += 8 * blockDim.x) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * blockDim.x;
+      v[u] = i < vocab ? row[i] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * (int)blockDim.x;
+      argmax_take(best, besti, v[u], i < vocab ? i : 0x7fffffff);
+    }
+  }
   block_argmax(best, besti, red);
   if (threadIdx.x == 0) {
     st.token[b] = besti;
