@@ -407,7 +407,6 @@ static bool valid_cfg(const river_config *c, std::string *why) {
     if (!gemm_prefill_ok(c))
       return bad("max_batch > 1 needs RIVER_BF16 with d_model, d_ffn and river_group multiples of 64 and the GEMM "
                  "prefill enabled");
-    if (c->max_seq > bd::kBdAttnMaxSplits * bd::kBdAttnSplitCap) return bad("max_batch > 1 supports max_seq up to 16384");
   }
   return true;
 }
@@ -1185,16 +1184,14 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
   const size_t seq_stride = y.cache_bytes / 2;               // elements (bf16)
   // attention: one workgroup per (sequence, kv head, group of query heads, split of the positions);
-  // splits so that every CU has two workgroups (measured best) and no split exceeds its LDS score area
+  // splits so that every CU has two workgroups (measured best) of at least 128 positions
   const int rep = c.n_q_heads / c.n_kv_heads, arep = rep % 4 == 0 ? 4 : 1;
   int t_max = 1;
   for (int b = 0; b < n; ++b) t_max = std::max(t_max, x->pos_b[b] + 1);
   const int hgs = rep / arep, groups = n * c.n_kv_heads * hgs;
-  int n_splits = std::max((2 * x->grid_persist + groups - 1) / groups,
-                          (t_max + bd::kBdAttnSplitCap - 1) / bd::kBdAttnSplitCap);
+  int n_splits = (2 * x->grid_persist + groups - 1) / groups;
   n_splits = std::max(1, std::min({n_splits, bd::kBdAttnMaxSplits, (t_max + 127) / 128}));
-  const int attn_cap = (t_max + n_splits - 1) / n_splits;
-  const size_t attn_lds = bd::bd_attn_lds_bytes(arep, c.head_dim, attn_cap);
+  const size_t attn_lds = bd::bd_attn_lds_bytes(arep, c.head_dim);
   const int qkv_ld = qd + 2 * c.n_kv_heads * c.head_dim;
   for (int l = 0; l < L; ++l) {
     const DevLayer &W = x->layers_h[l];
@@ -1209,7 +1206,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
                       : (arep == 4 ? (D.kv_f16 ? bd::k_bd_attn<64, true, 4> : bd::k_bd_attn<64, false, 4>)
                                    : (D.kv_f16 ? bd::k_bd_attn<64, true, 1> : bd::k_bd_attn<64, false, 1>));
       attn<<<ga, dim3(256), attn_lds, s>>>(big, D.rope, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq,
-                                           seq_stride, st.pos, n_splits, attn_cap, part_o, part_ml, tickets, o16);
+                                           seq_stride, st.pos, n_splits, part_o, part_ml, tickets, o16);
     }
     const int po = launch_bd_gemm(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, n);
     bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16, partial, po);

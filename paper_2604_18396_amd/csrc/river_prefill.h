@@ -820,22 +820,22 @@ __global__ void k_bd_copy(const float *__restrict__ src, float *dst, size_t n) {
 // also writes them to slot (b, l, pos[b]) of the shared cache -- the same slot for backbone and
 // river rows -- and nobody reads that slot from the cache in this launch.
 // Sixteen lanes share a cached row (HD/16 elements each, one 16- or 8-byte load), the 16 lane
-// groups stride over the split's positions, eight rows in flight per group.  Pass 1: scores (DPP
-// row sums) to LDS and the maxima; pass 2: probabilities and their sums; pass 3: the weighted
-// value rows; lane groups and wavefronts are summed in a fixed order.  With several splits every
-// workgroup publishes (max, sum, unnormalised output) per head and the last one to arrive of
-// the group merges them in split order (device-coherent stores and loads, no fences).  The
-// result goes to o16 in fragment order (frag_store), the output projection's input.
+// groups stride over the split's positions in batches of four K rows and their V rows, the next
+// batch in flight while one is consumed.  Every lane group keeps a running softmax per head
+// (base 2, rescaled once per batch; DPP row sums for the scores); lane groups, wavefronts and --
+// with several splits -- workgroups are merged in a fixed order: every workgroup publishes (max,
+// sum, unnormalised output) per head and the last one to arrive of the group merges them in
+// split order (device-coherent stores and loads, no fences).  The result goes to o16 in fragment
+// order (frag_store), the output projection's input.
 constexpr int kBdAttnMaxSplits = 8;
-constexpr int kBdAttnSplitCap = 2048;                        // most positions per split
-__host__ __device__ inline size_t bd_attn_lds_bytes(int rep, int hd, int cap) {
-  return ((size_t)rep * hd + 2 * hd + 64 + 4 * rep * hd + (size_t)rep * cap) * 4;
+__host__ __device__ inline size_t bd_attn_lds_bytes(int rep, int hd) {
+  return ((size_t)rep * hd + 2 * hd + 64 + 4 * rep * hd) * 4;
 }
 template <int HD, bool KV_F16, int REP>
 __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, const float2 *__restrict__ rope,
                                                  void *kcache, void *vcache, int nq, int nkv, int n_seq, int l,
                                                  int max_seq, size_t seq_stride, const int *__restrict__ pos,
-                                                 int n_splits, int cap, float *part_o, float *part_ml,
+                                                 int n_splits, float *part_o, float *part_ml,
                                                  unsigned int *tickets, _Float16 *o16) {
   constexpr int EL = HD / 16, HALF = HD / 2;                   // EL: elements per lane of a cached row
   extern __shared__ float sm[];
@@ -843,7 +843,6 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
   float *kc = qs + REP * HD, *vc = kc + HD;                    // this token's k, v (cache-rounded values)
   float *red = vc + HD;                                        // [64]
   float *part = red + 64;                                      // [4 wavefronts][REP][HD]
-  float *sc = part + 4 * REP * HD;                             // [REP][cap]
   const int tid = threadIdx.x, grp = tid >> 4, dl = tid & 15, wv = tid >> 6;
   const int rep = nq / nkv, hgs = rep / REP;
   // Workgroup index -> (data group g = (sequence, kv head, split), head group hg) such that the head
@@ -895,46 +894,36 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
   for (int r = 0; r < REP; ++r)
 #pragma unroll
     for (int e = 0; e < EL; ++e) q[r][e] = qs[r * HD + dl * EL + e];
-  // one cached row slice
-  auto row = [&](const void *cache, int j, float (&f)[EL]) {
-    const char *p = (const char *)cache + (base + (size_t)j * kvd + dl * EL) * 2;
-    if constexpr (EL == 8) {
-      const uint4 w = *(const uint4 *)p;
-      f[0] = cache_lo(w.x, KV_F16); f[1] = cache_hi(w.x, KV_F16); f[2] = cache_lo(w.y, KV_F16);
-      f[3] = cache_hi(w.y, KV_F16); f[4] = cache_lo(w.z, KV_F16); f[5] = cache_hi(w.z, KV_F16);
-      f[6] = cache_lo(w.w, KV_F16); f[7] = cache_hi(w.w, KV_F16);
-    } else {
-      const uint2 w = *(const uint2 *)p;
-      f[0] = cache_lo(w.x, KV_F16); f[1] = cache_hi(w.x, KV_F16); f[2] = cache_lo(w.y, KV_F16);
-      f[3] = cache_hi(w.y, KV_F16);
-    }
-  };
-  // The current position (the last one, held by the owner split) is not read from the cache: the
-  // loops run over the cached rows p0 .. pc - 1 and the first lane group adds it from LDS.
+  // The cached rows p0 .. pc - 1 (the current position, the last one, is not read from the cache:
+  // it seeds the first lane group's state from LDS).  Lane group grp takes rows p0 + grp + 16 t in
+  // batches of RB, K and V rows together, the next batch in flight while one is consumed.
   const int pc = owner ? P : p1;
-  // ---- pass 1: scores and maxima (rows beyond the last cached one read it again)
-  float mx[REP];
+  constexpr int RB = 4;
+  constexpr int NW = EL / 2;                                   // 32-bit words of a lane's row slice
+  struct Batch { uint32_t k[RB][NW], v[RB][NW]; };
+  auto load = [&](int j0, Batch &t) {
 #pragma unroll
-  for (int r = 0; r < REP; ++r) mx[r] = -1.0e30f;
-  for (int j0 = p0 + grp; j0 < pc; j0 += 16 * 8) {
-    float kf[8][EL];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) row(kcache, min(j0 + 16 * u, pc - 1), kf[u]);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int j = j0 + 16 * u;
-#pragma unroll
-      for (int r = 0; r < REP; ++r) {
-        float dot = 0.f;
-#pragma unroll
-        for (int e = 0; e < EL; ++e) dot = fmaf(kf[u][e], q[r][e], dot);
-        dot = row16_sum(dot);
-        if (j < pc) {
-          if (dl == 0) sc[r * cap + (j - p0)] = dot;
-          mx[r] = fmaxf(mx[r], dot);
-        }
+    for (int u = 0; u < RB; ++u) {
+      const int j = min(j0 + 16 * u, pc - 1);                  // rows beyond the last read it again (masked below)
+      const size_t off = (base + (size_t)j * kvd + dl * EL) * 2;
+      if constexpr (NW == 4) {
+        const uint4 a = *(const uint4 *)((const char *)kcache + off), c = *(const uint4 *)((const char *)vcache + off);
+        t.k[u][0] = a.x; t.k[u][1] = a.y; t.k[u][2] = a.z; t.k[u][3] = a.w;
+        t.v[u][0] = c.x; t.v[u][1] = c.y; t.v[u][2] = c.z; t.v[u][3] = c.w;
+      } else {
+        const uint2 a = *(const uint2 *)((const char *)kcache + off), c = *(const uint2 *)((const char *)vcache + off);
+        t.k[u][0] = a.x; t.k[u][1] = a.y;
+        t.v[u][0] = c.x; t.v[u][1] = c.y;
       }
     }
+  };
+  // running softmax per head (base 2: the scores carry log2 e): maximum, sum, weighted values
+  float m[REP], ls[REP], o[REP][EL];
+#pragma unroll
+  for (int r = 0; r < REP; ++r) {
+    m[r] = -1.0e30f; ls[r] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EL; ++e) o[r][e] = 0.f;
   }
   if (owner && grp == 0) {
 #pragma unroll
@@ -942,123 +931,131 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
       float dot = 0.f;
 #pragma unroll
       for (int e = 0; e < EL; ++e) dot = fmaf(kc[dl * EL + e], q[r][e], dot);
-      dot = row16_sum(dot);
-      if (dl == 0) sc[r * cap + (P - p0)] = dot;
-      mx[r] = fmaxf(mx[r], dot);
+      m[r] = row16_sum(dot);
+      ls[r] = 1.f;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) o[r][e] = vc[dl * EL + e];
     }
   }
+  auto consume = [&](int j0, const Batch &t) {
+    float sc[RB][REP];
 #pragma unroll
-  for (int r = 0; r < REP; ++r) {
+    for (int u = 0; u < RB; ++u) {
+      float kf[EL];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], o));
-  }
-  __syncthreads();
-  if ((tid & 63) == 0) {
-#pragma unroll
-    for (int r = 0; r < REP; ++r) red[r * 4 + wv] = mx[r];
-  }
-  __syncthreads();
-  float ls[REP];
-#pragma unroll
-  for (int r = 0; r < REP; ++r) {
-    mx[r] = fmaxf(fmaxf(red[r * 4], red[r * 4 + 1]), fmaxf(red[r * 4 + 2], red[r * 4 + 3]));
-    ls[r] = 0.f;
-  }
-  // ---- pass 2: probabilities and their sums
-  for (int j = tid; j < p1 - p0; j += 256) {
-#pragma unroll
-    for (int r = 0; r < REP; ++r) {
-      const float p = __builtin_amdgcn_exp2f(sc[r * cap + j] - mx[r]);
-      sc[r * cap + j] = p;
-      ls[r] += p;
-    }
-  }
-  block_sum_k<REP>(ls, red + 32);                              // (its barriers also publish sc)
-  // ---- pass 3: weighted value rows
-  float acc[REP][EL];
-#pragma unroll
-  for (int r = 0; r < REP; ++r)
-#pragma unroll
-    for (int e = 0; e < EL; ++e) acc[r][e] = 0.f;
-  for (int j0 = p0 + grp; j0 < pc; j0 += 16 * 8) {
-    float vf[8][EL];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) row(vcache, min(j0 + 16 * u, pc - 1), vf[u]);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int j = j0 + 16 * u;
+      for (int w = 0; w < NW; ++w) { kf[2 * w] = cache_lo(t.k[u][w], KV_F16); kf[2 * w + 1] = cache_hi(t.k[u][w], KV_F16); }
+      const bool ok = j0 + 16 * u < pc;
 #pragma unroll
       for (int r = 0; r < REP; ++r) {
-        const float p = j < pc ? sc[r * cap + (j - p0)] : 0.f;
+        float dot = 0.f;
 #pragma unroll
-        for (int e = 0; e < EL; ++e) acc[r][e] = fmaf(p, vf[u][e], acc[r][e]);
+        for (int e = 0; e < EL; ++e) dot = fmaf(kf[e], q[r][e], dot);
+        sc[u][r] = ok ? row16_sum(dot) : -1.0e30f;
       }
     }
-  }
-  if (owner && grp == 0) {
 #pragma unroll
     for (int r = 0; r < REP; ++r) {
-      const float p = sc[r * cap + (P - p0)];
+      float mn = m[r];
 #pragma unroll
-      for (int e = 0; e < EL; ++e) acc[r][e] = fmaf(p, vc[dl * EL + e], acc[r][e]);
+      for (int u = 0; u < RB; ++u) mn = fmaxf(mn, sc[u][r]);
+      const float cg = __builtin_amdgcn_exp2f(m[r] - mn);      // <= 1; 1 while nothing has been seen
+      m[r] = mn;
+      ls[r] *= cg;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) o[r][e] *= cg;
+#pragma unroll
+      for (int u = 0; u < RB; ++u) sc[u][r] = sc[u][r] > -0.5e30f ? __builtin_amdgcn_exp2f(sc[u][r] - mn) : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < RB; ++u) {
+      float vf[EL];
+#pragma unroll
+      for (int w = 0; w < NW; ++w) { vf[2 * w] = cache_lo(t.v[u][w], KV_F16); vf[2 * w + 1] = cache_hi(t.v[u][w], KV_F16); }
+#pragma unroll
+      for (int r = 0; r < REP; ++r) {
+        ls[r] += sc[u][r];
+#pragma unroll
+        for (int e = 0; e < EL; ++e) o[r][e] = fmaf(sc[u][r], vf[e], o[r][e]);
+      }
+    }
+  };
+  {
+    Batch ba, bb;
+    const int step = 16 * RB;
+    int j0 = p0 + grp;
+    if (j0 < pc) load(j0, ba);
+    for (; j0 < pc; j0 += 2 * step) {
+      if (j0 + step < pc) load(j0 + step, bb);
+      consume(j0, ba);
+      if (j0 + 2 * step < pc) load(j0 + 2 * step, ba);
+      if (j0 + step < pc) consume(j0 + step, bb);
     }
   }
-  // the four lane groups of a wavefront (lanes 16 and 32 apart hold the same elements), then the
-  // four wavefronts through LDS
+  // merge: the four lane groups of a wavefront by lane exchange (lanes 16 and 32 apart hold the
+  // same elements), then the four wavefronts through LDS, both in a fixed order
 #pragma unroll
-  for (int r = 0; r < REP; ++r)
+  for (int r = 0; r < REP; ++r) {
 #pragma unroll
-    for (int e = 0; e < EL; ++e) {
-      float v = acc[r][e];
-      v += __shfl_xor(v, 16);
-      v += __shfl_xor(v, 32);
-      acc[r][e] = v;
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float m2 = __shfl_xor(m[r], off), l2 = __shfl_xor(ls[r], off);
+      const float mn = fmaxf(m[r], m2);
+      const float c1 = __builtin_amdgcn_exp2f(m[r] - mn), c2 = __builtin_amdgcn_exp2f(m2 - mn);
+      ls[r] = ls[r] * c1 + l2 * c2;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) o[r][e] = o[r][e] * c1 + __shfl_xor(o[r][e], off) * c2;
+      m[r] = mn;
     }
+  }
+  float *wml = red;                                            // [4 wavefronts][REP][2]
   if ((tid & 63) < 16) {
 #pragma unroll
-    for (int r = 0; r < REP; ++r)
+    for (int r = 0; r < REP; ++r) {
 #pragma unroll
-      for (int e = 0; e < EL; ++e) part[(wv * REP + r) * HD + dl * EL + e] = acc[r][e];
-  }
-  float *ml = red;                                             // [REP][2] (max, sum) of this split, for all threads
-  if (tid == 0) {
-#pragma unroll
-    for (int r = 0; r < REP; ++r) { ml[2 * r] = mx[r]; ml[2 * r + 1] = ls[r]; }
+      for (int e = 0; e < EL; ++e) part[(wv * REP + r) * HD + dl * EL + e] = o[r][e];
+      if (dl == 0) { wml[(wv * REP + r) * 2] = m[r]; wml[(wv * REP + r) * 2 + 1] = ls[r]; }
+    }
   }
   __syncthreads();
+  // element e of head r over the four wavefronts -> (M, L, O) of this split
+  auto split_result = [&](int r, int e, float &M, float &Ls, float &O) {
+    M = -1.0e30f; Ls = 0.f; O = 0.f;
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, wml[(w * REP + r) * 2]);
+    for (int w = 0; w < 4; ++w) {
+      const float cw = __builtin_amdgcn_exp2f(wml[(w * REP + r) * 2] - M);   // a wavefront that saw nothing has sum 0
+      Ls = fmaf(wml[(w * REP + r) * 2 + 1], cw, Ls);
+      O = fmaf(part[(w * REP + r) * HD + e], cw, O);
+    }
+  };
   if (n_splits == 1) {
     for (int t = tid; t < REP * HD; t += 256) {
-      const int r = t / HD, e = t % HD;
-      const float o = ((part[t] + part[REP * HD + t]) + part[2 * REP * HD + t]) + part[3 * REP * HD + t];
-      frag_store(o16, qd, b, (h0 + r) * HD + e, (_Float16)(o / ml[2 * r + 1]));
+      float M, Ls, O;
+      split_result(t / HD, t % HD, M, Ls, O);
+      frag_store(o16, qd, b, (h0 + t / HD) * HD + t % HD, (_Float16)(O / Ls));
     }
     return;
   }
   // ---- several splits: publish the partial result, the last workgroup of the group merges
   for (int t = tid; t < REP * HD; t += 256) {
     const int r = t / HD, e = t % HD;
-    const float o = ((part[t] + part[REP * HD + t]) + part[2 * REP * HD + t]) + part[3 * REP * HD + t];
+    float M, Ls, O;
+    split_result(r, e, M, Ls, O);
     const size_t pi = ((size_t)b * nq + h0 + r) * kBdAttnMaxSplits + sp;
-    pub(part_o + pi * HD + e, o);
-  }
-  if (tid < REP) {
-    const size_t pi = ((size_t)b * nq + h0 + tid) * kBdAttnMaxSplits + sp;
-    pub(part_ml + pi * 2, ml[2 * tid]);
-    pub(part_ml + pi * 2 + 1, ml[2 * tid + 1]);
+    pub(part_o + pi * HD + e, O);
+    if (e == 0) { pub(part_ml + pi * 2, M); pub(part_ml + pi * 2 + 1, Ls); }
   }
   if (!last_arriver(tickets + ((size_t)b * nkv + kvh) * hgs + hg, (unsigned)n_splits, (int *)(red + 60))) return;
   for (int t = tid; t < REP * HD; t += 256) {
     const int r = t / HD, e = t % HD;
     const size_t pb = ((size_t)b * nq + h0 + r) * kBdAttnMaxSplits;
-    float M = -1.0e30f;
-    for (int j = 0; j < n_splits; ++j) M = fmaxf(M, sub(part_ml + (pb + j) * 2));
-    float Ls = 0.f, O = 0.f;
+    float Mg = -1.0e30f;
+    for (int j = 0; j < n_splits; ++j) Mg = fmaxf(Mg, sub(part_ml + (pb + j) * 2));
+    float Lg = 0.f, Og = 0.f;
     for (int j = 0; j < n_splits; ++j) {
-      const float cj = __builtin_amdgcn_exp2f(sub(part_ml + (pb + j) * 2) - M);   // an empty split has sum 0
-      Ls = fmaf(sub(part_ml + (pb + j) * 2 + 1), cj, Ls);
-      O = fmaf(sub(part_o + (pb + j) * HD + e), cj, O);
+      const float cj = __builtin_amdgcn_exp2f(sub(part_ml + (pb + j) * 2) - Mg);   // an empty split has sum 0
+      Lg = fmaf(sub(part_ml + (pb + j) * 2 + 1), cj, Lg);
+      Og = fmaf(sub(part_o + (pb + j) * HD + e), cj, Og);
     }
-    frag_store(o16, qd, b, (h0 + r) * HD + e, (_Float16)(O / Ls));
+    frag_store(o16, qd, b, (h0 + r) * HD + e, (_Float16)(Og / Lg));
   }
 }
 
