@@ -857,6 +857,34 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
   const bool owner = P >= p0 && P < p1;                        // this split holds the current position
   const float *row_in = qkv + (size_t)b * ld;
   const size_t base = (size_t)b * seq_stride + (size_t)l * max_seq * kvd + (size_t)kvh * HD;
+  // The cached rows p0 .. pc - 1 (the current position, the last one, is not read from the cache:
+  // it seeds the first lane group's state from LDS).  Lane group grp takes rows p0 + grp + 16 t in
+  // batches of RB, K and V rows together, the next batch in flight while one is consumed.
+  const int pc = owner ? P : p1;
+  constexpr int RB = 4;
+  constexpr int NW = EL / 2;                                   // 32-bit words of a lane's row slice
+  struct Batch { uint32_t k[RB][NW], v[RB][NW]; };
+  auto load = [&](int j0, Batch &t) {
+#pragma unroll
+    for (int u = 0; u < RB; ++u) {
+      const int j = min(j0 + 16 * u, pc - 1);                  // rows beyond the last read it again (masked below)
+      const size_t off = (base + (size_t)j * kvd + dl * EL) * 2;
+      if constexpr (NW == 4) {
+        const uint4 a = *(const uint4 *)((const char *)kcache + off), c = *(const uint4 *)((const char *)vcache + off);
+        t.k[u][0] = a.x; t.k[u][1] = a.y; t.k[u][2] = a.z; t.k[u][3] = a.w;
+        t.v[u][0] = c.x; t.v[u][1] = c.y; t.v[u][2] = c.z; t.v[u][3] = c.w;
+      } else {
+        const uint2 a = *(const uint2 *)((const char *)kcache + off), c = *(const uint2 *)((const char *)vcache + off);
+        t.k[u][0] = a.x; t.k[u][1] = a.y;
+        t.v[u][0] = c.x; t.v[u][1] = c.y;
+      }
+    }
+  };
+  // the first batch does not depend on this step's q, k, v: it is in flight during the prologue
+  Batch ba, bb;
+  const int step = 16 * RB;
+  int j0 = p0 + grp;
+  if (j0 < pc) load(j0, ba);
   // ---- prologue: RoPE, rounding, KV write
   {
     const float qscale = 1.4426950408889634f / sqrtf((float)HD);
@@ -894,29 +922,6 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
   for (int r = 0; r < REP; ++r)
 #pragma unroll
     for (int e = 0; e < EL; ++e) q[r][e] = qs[r * HD + dl * EL + e];
-  // The cached rows p0 .. pc - 1 (the current position, the last one, is not read from the cache:
-  // it seeds the first lane group's state from LDS).  Lane group grp takes rows p0 + grp + 16 t in
-  // batches of RB, K and V rows together, the next batch in flight while one is consumed.
-  const int pc = owner ? P : p1;
-  constexpr int RB = 4;
-  constexpr int NW = EL / 2;                                   // 32-bit words of a lane's row slice
-  struct Batch { uint32_t k[RB][NW], v[RB][NW]; };
-  auto load = [&](int j0, Batch &t) {
-#pragma unroll
-    for (int u = 0; u < RB; ++u) {
-      const int j = min(j0 + 16 * u, pc - 1);                  // rows beyond the last read it again (masked below)
-      const size_t off = (base + (size_t)j * kvd + dl * EL) * 2;
-      if constexpr (NW == 4) {
-        const uint4 a = *(const uint4 *)((const char *)kcache + off), c = *(const uint4 *)((const char *)vcache + off);
-        t.k[u][0] = a.x; t.k[u][1] = a.y; t.k[u][2] = a.z; t.k[u][3] = a.w;
-        t.v[u][0] = c.x; t.v[u][1] = c.y; t.v[u][2] = c.z; t.v[u][3] = c.w;
-      } else {
-        const uint2 a = *(const uint2 *)((const char *)kcache + off), c = *(const uint2 *)((const char *)vcache + off);
-        t.k[u][0] = a.x; t.k[u][1] = a.y;
-        t.v[u][0] = c.x; t.v[u][1] = c.y;
-      }
-    }
-  };
   // running softmax per head (base 2: the scores carry log2 e): maximum, sum, weighted values
   float m[REP], ls[REP], o[REP][EL];
 #pragma unroll
@@ -979,17 +984,11 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
       }
     }
   };
-  {
-    Batch ba, bb;
-    const int step = 16 * RB;
-    int j0 = p0 + grp;
-    if (j0 < pc) load(j0, ba);
-    for (; j0 < pc; j0 += 2 * step) {
-      if (j0 + step < pc) load(j0 + step, bb);
-      consume(j0, ba);
-      if (j0 + 2 * step < pc) load(j0 + 2 * step, ba);
-      if (j0 + step < pc) consume(j0 + step, bb);
-    }
+  for (; j0 < pc; j0 += 2 * step) {
+    if (j0 + step < pc) load(j0 + step, bb);
+    consume(j0, ba);
+    if (j0 + 2 * step < pc) load(j0 + 2 * step, ba);
+    if (j0 + step < pc) consume(j0 + step, bb);
   }
   // merge: the four lane groups of a wavefront by lane exchange (lanes 16 and 32 apart hold the
   // same elements), then the four wavefronts through LDS, both in a fixed order
