@@ -610,12 +610,17 @@ template <bool W4, int MB, int RBW>
 __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, const GemmB &B, int interleaved, int N,
                                              int K, int group, void *C, int ldc, int epi,
                                              const int *__restrict__ river, int want, int n_rows, int rows_per_wg,
-                                             int k_split, float *red /* [kBdWaves][RBW][MB][256] */) {
+                                             int k_split, int w0, int nw,
+                                             float *red /* [kBdWaves][RBW][MB][256] */) {
   constexpr int P = W4 ? BdDepth<RBW, MB>::w4 : BdDepth<RBW, MB>::dense;
   constexpr int TILE = W4 ? 128 : 64;                         // columns per K tile
   constexpr int NA = W4 ? 4 : 2;                              // MFMA steps (16-byte A fragments) per tile
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  // the pass is run by wavefronts w0 .. w0 + nw - 1 of the workgroup (all eight, or four when the
+  // other four run the other weight format beside it); every wavefront of the workgroup executes the
+  // same number of workgroup barriers in either case
+  const int tid = threadIdx.x - w0 * 64, lane = tid & 63, wv = tid >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
+  red += (size_t)w0 * RBW * MB * 256;
   // workgroup -> (group of rows, slice of K): with k_split > 1 the output is a partial sum, stored
   // as rows 32 ks .. of C for the consumer to add up (see k_bd_rmsnorm)
   const int ks = blockIdx.x % k_split;
@@ -713,18 +718,18 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
     Stage st[P];
 #pragma unroll
     for (int u = 0; u < P; ++u)
-      if (kt0 + wv + kBdWaves * u < nkt) load(kt0 + wv + kBdWaves * u, st[u]);
-    for (int kt = kt0 + wv; kt < nkt; kt += kBdWaves * P) {
+      if (kt0 + wv + nw * u < nkt) load(kt0 + wv + nw * u, st[u]);
+    for (int kt = kt0 + wv; kt < nkt; kt += nw * P) {
 #pragma unroll
       for (int u = 0; u < P; ++u) {
-        const int k = kt + kBdWaves * u;
+        const int k = kt + nw * u;
         if (k < nkt) {
           compute(st[u]);
-          if (k + kBdWaves * P < nkt) load(k + kBdWaves * P, st[u]);
+          if (k + nw * P < nkt) load(k + nw * P, st[u]);
         }
       }
     }
-    // the eight partial tiles -> one, in wavefront order; D: register r of lane l is sequence row
+    // the partial tiles of the nw wavefronts -> one, in wavefront order; D: register r of lane l is sequence row
     // (l / 16) * 4 + r, B row l % 16
     __syncthreads();                                          // the previous pass has been read
 #pragma unroll
@@ -736,13 +741,13 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
           red[((wv * RBW + rb) * MB + i) * 256 + (kg * 4 + r) * 16 + r16] = acc[rb][i][r];
     __syncthreads();
     constexpr int TILE_F = RBW * MB * 256;
-    for (int e = tid; e < TILE_F; e += 512) {
+    for (int e = tid; e < TILE_F; e += nw * 64) {
       const int rb = e / (MB * 256), i = (e / 256) % MB, row = i * 16 + ((e & 255) >> 4), n = p0 + rb * 16 + (e & 15);
       if (row >= n_rows || n >= wg_r1 || !(want < 0 || river[row] == want)) continue;
       auto total = [&](int idx) {
         float v = red[idx];
 #pragma unroll
-        for (int w = 1; w < kBdWaves; ++w) v += red[w * TILE_F + idx];
+        for (int w = 1; w < nw; ++w) v += red[w * TILE_F + idx];
         return v;
       };
       if (epi == EPI_SWIGLU) {
@@ -777,13 +782,16 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af
   if ((int)threadIdx.x < n_rows) any[by_flag && river[threadIdx.x] != 0] = 1;
   __syncthreads();
   const bool dense = any[0] != 0, twin = any[1] != 0;
-  if (dense) bd_gemm_pass<false, MB, RBW>(Af, Bd, interleaved, N, K, group, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
-                                          rows_per_wg, k_split, red);
-  if (twin) {
-    __syncthreads();                                          // the partial tiles of the first pass have been read
+  // Both sides: four wavefronts each, side by side -- the 4-bit side's dequantisation runs in the
+  // shadow of the bf16 side's memory waits, and there is one ramp-up and one tail instead of two.
+  constexpr int ND = kBdWaves / 2;                              // wavefronts of the bf16 side when both run (3 .. 4 measured best)
+  const bool second = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) >= ND;   // (a scalar branch)
+  if (dense && (!twin || !second))
+    bd_gemm_pass<false, MB, RBW>(Af, Bd, interleaved, N, K, group, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
+                                 rows_per_wg, k_split, 0, twin ? ND : kBdWaves, red);
+  if (twin && (!dense || second))
     bd_gemm_pass<true, MB, RBW>(Af + frag_halfs(K), Bq, interleaved, N, K, group, C, ldc, epi, river, 1, n_rows,
-                                rows_per_wg, k_split, red);
-  }
+                                rows_per_wg, k_split, dense ? ND : 0, dense ? kBdWaves - ND : kBdWaves, red);
 }
 
 // h[b, :] = E[token[b], :] (also h_prev and the debug view of h(0)); start-of-step state of
