@@ -202,6 +202,16 @@ def bench_batch(args, wl, torch, np, binding, byte_model, configs, inputs):
                 "algorithmic_bytes_per_step": by, "achieved_GBps": gbs, "frac": gbs / HBM_PEAK_GBS}
 
     r, dn, un = leg(ms_ragged, scheds), leg(ms_dense, np.full_like(scheds, L)), leg(ms_uniform, uniform)
+    # HBM bytes per step from the rocprofv3 counter runs recorded beside the package
+    traffic, traffic_detail = None, None
+    if os.path.exists(MEASURED):
+        traffic_detail = json.load(open(MEASURED)).get(f"{wl.name}:batched")
+        if traffic_detail:
+            traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]
+            traffic_detail = dict(traffic_detail,
+                                  source="NOT measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                         "runs summarised under profiles/ (see its note for the step count "
+                                         "and the algorithmic bytes of that run)")
     out = {
         "metric": "decode tokens/s @batch1 (8B shape) w/ early exit; HBM GB/s as % of peak",
         "value": r["value"], "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -212,8 +222,9 @@ def bench_batch(args, wl, torch, np, binding, byte_model, configs, inputs):
                    "mean_exit_position": float(np.mean(scheds[W:])), "exec_mode": "batched kernels",
                    "note": "aggregate over the batch; this workload is NOT the batch-1 headline metric"},
         "roofline": {"bound": "hbm", "achieved": r["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": r["frac"], "traffic": None, "kernel": "all kernels of a batched step "
-                     "(k_bd_gemm dominates)", "algorithmic_bytes_per_launch": r["algorithmic_bytes_per_step"]},
+                     "frac": r["frac"], "traffic": traffic, "kernel": "all kernels of a batched step "
+                     "(k_bd_gemm dominates)", "algorithmic_bytes_per_launch": r["algorithmic_bytes_per_step"],
+                     "traffic_detail": traffic_detail},
         "dense": dn, "uniform_exit": dict(un, note="every sequence of a step leaves at the same position "
                                                    "(one weight set per block), the effect of a whole-batch rule"),
     }
