@@ -437,14 +437,16 @@ __global__ __launch_bounds__(256) void k_pf_attn(const _Float16 *__restrict__ q1
 // Batched decode step (several sequences, each at its own position and exit depth)
 // =====================================================================================
 //
-// One decode step for n sequences: every block runs once for the rows (sequences) still in
-// the backbone and once for the rows that have left it, as two GEMMs over the same 32-row
-// activation tile -- bf16 backbone matrices and the 4-bit river twins -- each touching only
-// its own rows and returning at once when it has none (so a block whose rows all sit on one
-// side reads one weight set).  With depths drawn independently per sequence most blocks read
-// both sets: the reason Eq. 1 takes the minimum over the batch.  Which side a row is on is
-// decided on the device after every backbone block (k_bd_exit), per sequence or by Eq. 1's
-// batch rule; the host never waits inside a step.
+// One decode step for n sequences, seven launches per block: QKV GEMM, attention (with RoPE and
+// the KV write), O-proj GEMM, norm, gate/up GEMM (SwiGLU in its epilogue), down GEMM, block end
+// (similarity, exit decision, next norm).  Every GEMM runs the bf16 backbone matrices for the
+// rows (sequences) still in the backbone and the 4-bit river twins for the rows that have left
+// it, over the same activation tile, each side touching only its own rows and not read at all
+// when it has none (so a block whose rows all sit on one side reads one weight set).  With
+// depths drawn independently per sequence most blocks read both sets: the reason Eq. 1 takes the
+// minimum over the batch.  Which side a row is on is decided on the device after every backbone
+// block (k_bd_block_end per sequence, k_bd_decide for Eq. 1's batch rule); the host never waits
+// inside a step.
 namespace bd {
 
 using namespace pf;
@@ -592,8 +594,8 @@ __global__ __launch_bounds__(256) void k_bd_rmsnorm(float *__restrict__ h, const
 // k0 + 32 g .. + 31, one step per code word, which lie in one quantisation group), for A the
 // same columns of sequence row n (fp16, kept in fragment order: one contiguous 1 KiB per
 // wavefront and step, from the L2; every workgroup reads the whole tile once, shared by its RBW
-// row blocks).  P tiles are in flight per
-// wavefront in registers.  The eight partial tiles are summed in wavefront order through LDS.
+// row blocks).  P tiles are in flight per wavefront in registers.  The partial tiles of the
+// wavefronts are summed in wavefront order through LDS.
 // op (epi): store fp32, add into fp32, or -- with B's rows interleaved as (gate i, up i) --
 // silu(gate) * up stored as fp16 in fragment order (the activation of the down projection; ldc is
 // then its column count).
