@@ -281,7 +281,9 @@ REP2B = configs.ModelConfig("rep2-batch-bf16", 2, 512, 8, 4, 64, 1024, 1002, 100
                             configs.DTYPE_BF16, 1040, 0, 2.0)
 
 
-@pytest.mark.parametrize("cfg", [HD64B.with_(n_layers=2, max_seq=1040), REP2B], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [HD64B.with_(n_layers=2, max_seq=1040), REP2B,
+                                 HD64B.with_(name="hd64-batch-f16kv", n_layers=2, max_seq=1040, kv_dtype=configs.KV_F16)],
+                         ids=lambda c: c.name)
 def test_batch_long_contexts_attention_splits(cfg):
     """Contexts up to 1030 positions: the batched attention runs with up to eight splits of the
     positions (merged by the last workgroup to arrive), some of them empty for the short
