@@ -43,12 +43,14 @@ class Batch:
     """A batched HIP context and one oracle context per sequence on the same weights."""
 
     def __init__(self, cfg, n_seq, prompt_lens, seed, rule=binding.EXIT_PER_SEQUENCE, max_batch=None,
-                 prefill_depth=None):
+                 prefill_depth=None, make_river=None):
+        """make_river(cfg, weights): a river quantised outside the library, handed to both sides."""
         self.cfg, self.n = cfg, n_seq
         w = inputs.make_weights(cfg, seed, gain_std=0.05)
-        river = ro.quantize_river(cfg, w)
+        river = make_river(cfg, w) if make_river else ro.quantize_river(cfg, w)
         self.dw = binding.upload_weights(w)
-        self.dr = binding.quantize_river(cfg, self.dw)
+        self.dr = ([{m: tuple(t.cuda() for t in blk[m]) for m in blk} for blk in river] if make_river
+                   else binding.quantize_river(cfg, self.dw))
         self.g = binding.River(cfg, self.dw, self.dr, max_batch=max_batch or n_seq, batch_exit_rule=rule)
         self.os, self.toks = [], []
         for b in range(n_seq):
@@ -299,6 +301,25 @@ def test_batch_long_contexts_attention_splits(cfg):
         hid = np.array([o.hidden() for o in B.os]).transpose(1, 0, 2)
         B.compare([r[0] for r in res], [r[1] for r in res], [r[2] for r in res], hid,
                   [o.logits() for o in B.os], got, f"{cfg.name} step {step}")
+        B.toks = [r[0] for r in res]
+    B.compare_caches()
+    B.close()
+
+
+def test_batch_river_quantised_elsewhere():
+    """A river from another quantiser (integer zero points, group 128) through the batched step."""
+    from test_gpu_parity import foreign_river
+    cfg = HD64B.with_(name="hd64-batch-foreign-river", river_group=128, n_layers=3)
+    say("batched decode, river quantised elsewhere")
+    B = Batch(cfg, 5, [5, 40, 17, 33, 9], 261, make_river=lambda c, w: foreign_river(c, w, 128))
+    rng = np.random.default_rng(17)
+    for step in range(3):
+        forced = [int(rng.integers(cfg.min_exit_layer, cfg.n_layers + 1)) for _ in range(5)]
+        got = B.g.decode_batch(5, B.toks, forced)
+        res = [o.decode_step(t, f) for o, t, f in zip(B.os, B.toks, forced)]
+        hid = np.array([o.hidden() for o in B.os]).transpose(1, 0, 2)
+        B.compare([r[0] for r in res], [r[1] for r in res], [r[2] for r in res], hid,
+                  [o.logits() for o in B.os], got, f"foreign river step {step}")
         B.toks = [r[0] for r in res]
     B.compare_caches()
     B.close()

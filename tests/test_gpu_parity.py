@@ -66,11 +66,17 @@ def check_token(cfg, tg, to, lo, what):
 class Pair:
     """Oracle and HIP context on the same weights; each side quantises its own river."""
 
-    def __init__(self, cfg, weights, mode, with_river=True, oracle=None, prefill_gemm_min_tokens=0):
+    def __init__(self, cfg, weights, mode, with_river=True, oracle=None, prefill_gemm_min_tokens=0, river=None):
+        """river: a river quantised elsewhere, [{matrix: (codes, scale, zero)}] of CPU tensors,
+        handed to both sides as data."""
         self.cfg = cfg
-        self.o = oracle or ro.Oracle(cfg, weights, ro.quantize_river(cfg, weights) if with_river else None)
+        self.o = oracle or ro.Oracle(cfg, weights, river if river is not None else
+                                     (ro.quantize_river(cfg, weights) if with_river else None))
         self.dw = binding.upload_weights(weights)
-        self.dr = binding.quantize_river(cfg, self.dw) if with_river else None
+        if river is not None:
+            self.dr = [{m: tuple(t.cuda() for t in blk[m]) for m in blk} for blk in river]
+        else:
+            self.dr = binding.quantize_river(cfg, self.dw) if with_river else None
         self.g = binding.River(cfg, self.dw, self.dr, exec_mode=mode,
                                prefill_gemm_min_tokens=prefill_gemm_min_tokens)
 
@@ -689,4 +695,43 @@ def test_fp16_kv_cache(mode, cfg0):
         pair.compare_cache(n_prompt + 4)
         kg = pair.g.kcache()[:, :n_prompt + 4]
         assert np.array_equal(kg, kg.astype(np.float16).astype(np.float32))
+        pair.close()
+
+
+def foreign_river(cfg, weights, group):
+    """A river produced by another quantiser than the library's: integer zero points (as GPTQ- and
+    AWQ-style formats store them), scale = (max - min) / 15 of the group rounded to the weight
+    dtype, code = clamp(round(w / scale) + zero).  Input data for both sides."""
+    out = []
+    for blk in weights["layers"]:
+        q = {}
+        for m in ro.MATRICES:
+            w = blk[m].to(torch.float32).numpy()
+            rows, cols = w.shape
+            g = w.reshape(rows, cols // group, group)
+            mn, mx = g.min(-1), g.max(-1)
+            scale = torch.from_numpy(np.where(mx > mn, (mx - mn) / 15.0, 1.0).astype(np.float32)).to(blk[m].dtype)
+            sc = scale.to(torch.float32).numpy()
+            zero = np.clip(np.rint(-mn / sc), 0, 15)
+            codes = np.clip(np.rint(g / sc[..., None]) + zero[..., None], 0, 15).astype(np.uint8).reshape(rows, cols)
+            packed = torch.from_numpy((codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8))
+            q[m] = (packed.contiguous(), scale.contiguous(), torch.from_numpy(zero.astype(np.float32)).to(blk[m].dtype).contiguous())
+        out.append(q)
+    return out
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_river_quantised_elsewhere_integer_zero_points(mode):
+    """The river arrays are plain data: a river from another quantiser (integer zero points,
+    group 128) goes through prefill (MFMA GEMMs and per position) and decode on both sides."""
+    cfg = MID.with_(name="mid-foreign-river", river_group=128, max_seq=96)
+    weights = inputs.make_weights(cfg, 77, gain_std=0.1)
+    river = foreign_river(cfg, weights, 128)
+    for min_tokens in (0, -1):                          # MFMA prefill / per-position prefill
+        say(f"foreign river, mode {mode}, prefill_gemm_min_tokens {min_tokens}")
+        pair = Pair(cfg, weights, mode, prefill_gemm_min_tokens=min_tokens, river=river)
+        tok = pair.prefill(inputs.make_prompt(cfg.vocab, 40, 78), 2)
+        for step, forced in enumerate([1, 3, 2, 1]):
+            tok, _, _ = pair.step(tok, forced, f"foreign river step {step}")
+        pair.compare_cache(44)
         pair.close()
