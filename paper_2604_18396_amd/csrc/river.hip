@@ -204,19 +204,6 @@ __global__ void k_pack_sz(const void *scale, const void *zero, void *out, long l
     ((typename Store<DT>::SZ *)out)[i] = Store<DT>::pack(Store<DT>::ld(scale, i), Store<DT>::ld(zero, i));
 }
 
-// The same pairs in the order the batched 4-bit GEMM fetches them (bf16 models): per K tile of
-// 128 columns and row, the pairs of the tile's two 64-column halves -- [tile][row][2] -- so that
-// the 16 rows of an MFMA block find theirs in one 128-byte line.
-__global__ void k_pack_sz_tiles(const void *scale, const void *zero, uint32_t *out, int rows, int cols, int group) {
-  const int gpr = (cols + group - 1) / group, tiles = (cols + 127) / 128;
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (long long)tiles * rows * 2) return;
-  const int j = (int)(i & 1), r = (int)((i >> 1) % rows), kt = (int)((i >> 1) / rows);
-  const int k = kt * 128 + j * 64;
-  const size_t src = (size_t)r * gpr + min(k / group, gpr - 1);
-  out[i] = Store<1>::pack(Store<1>::ld(scale, src), Store<1>::ld(zero, src));
-}
-
 // River construction: one thread per quantisation group.
 template <int DT>
 __global__ void k_quantize_w4(const void *w, long long rows, int cols, int group, uint8_t *codes,
@@ -264,7 +251,7 @@ struct Layout {
       amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
   size_t bd_partial;                     // [kBdKSplit][32][d_model] partial sums of the K-sliced GEMMs
-  size_t bd_qszt, bd_qszt_bytes;         // batched contexts: the pairs in K-tile order (k_pack_sz_tiles)
+  size_t bd_stream, bd_stream_bytes;     // batched contexts: the GEMM weights a second time, in stream order (bd::BdB)
   // activation buffers of the GEMM prefill (pf_rows rows each; 0 rows: that path is not offered)
   size_t pf_tok, pf_h, pf_x16, pf_q16, pf_a16, pf_big;
   int pf_rows;
@@ -361,7 +348,8 @@ struct river_ctx {
   bool broken;
   std::string err;
   std::vector<DevLayer> layers_h;   // host copy of the per-block pointer table (GEMM prefill launches)
-  std::vector<const void *> qszt_h; // [L][7] the (scale, zero) pairs in K-tile order (batched contexts)
+  std::vector<bd::BdB> bd_dense_h, bd_twin_h;   // [L][4] stream-order weights of the QKV / O / gate-up / down GEMMs
+  bd::BdB bd_head;                  // (batched contexts; a twin that was not given: null)
   std::vector<int> pos_b;           // batched contexts: positions in the cache, per sequence
   long long steps_b = 0;            // batched decode steps recorded so far
   int last_n = 0;                   // sequences of the last batched step
@@ -436,10 +424,25 @@ static size_t qsz_matrix_bytes(const river_config *c, int m) {
   return (size_t)(rows * gpr) * (c->dtype == RIVER_BF16 ? 4 : 8);
 }
 
-static size_t qszt_matrix_bytes(const river_config *c, int m) {
-  long long rows, cols;
-  matrix_shape(c, m, &rows, &cols);
-  return (size_t)((cols + 127) / 128) * rows * 2 * 4;
+// The four GEMMs of a block in a batched step: matrices (stacked along N, or interleaved), N, K
+struct BdGemmShape { int ms[3], nm, interleaved, N, K; };
+static BdGemmShape bd_gemm_shape(const river_config *c, int g) {
+  const int q = c->n_q_heads * c->head_dim, kv = c->n_kv_heads * c->head_dim, d = c->d_model, f = c->d_ffn;
+  switch (g) {
+    case 0: return {{M_WQ, M_WK, M_WV}, 3, 0, q + 2 * kv, d};
+    case 1: return {{M_WO, M_WO, M_WO}, 1, 0, d, q};
+    case 2: return {{M_GATE, M_UP, M_UP}, 2, 1, 2 * f, d};
+    default: return {{M_DOWN, M_DOWN, M_DOWN}, 1, 0, d, f};
+  }
+}
+static size_t bd_stream_bytes_of(const river_config *c) {
+  size_t per_block = 0;
+  for (int g = 0; g < 4; ++g) {
+    const BdGemmShape sh = bd_gemm_shape(c, g);
+    per_block += align_up(bd::bd_dense_bytes(sh.N, sh.K), 256) + align_up(bd::bd_codes_bytes(sh.N, sh.K), 256) +
+                 align_up(bd::bd_pairs_bytes(sh.N, sh.K), 256);
+  }
+  return per_block * (size_t)c->n_layers + align_up(bd::bd_dense_bytes(c->vocab, c->d_model), 256);
 }
 
 static Layout make_layout(const river_config *c) {
@@ -501,10 +504,8 @@ static Layout make_layout(const river_config *c) {
     y.bd_rec_exit = take((size_t)bd::kRecordsB * B * 4);
     y.bd_rec_sims = take((size_t)bd::kRecordsB * B * c->n_layers * 4);
     y.bd_partial = take((size_t)bd::kBdKSplit * bd::kRows * c->d_model * 4);
-    y.bd_qszt_bytes = 0;
-    for (int m = 0; m < 7; ++m) y.bd_qszt_bytes += align_up(qszt_matrix_bytes(c, m), 256);
-    y.bd_qszt_bytes *= (size_t)c->n_layers;
-    y.bd_qszt = take(y.bd_qszt_bytes);
+    y.bd_stream_bytes = bd_stream_bytes_of(c);
+    y.bd_stream = take(y.bd_stream_bytes);
   }
   y.total = off;
   return y;
@@ -752,24 +753,54 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
       }
     if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) packing", e);
   }
-  x->qszt_h.assign((size_t)L * 7, nullptr);
+  // batched contexts: the GEMM weights a second time, in the order the batched GEMM streams them
+  x->bd_dense_h.assign((size_t)L * 4, bd::BdB{nullptr, nullptr});
+  x->bd_twin_h.assign((size_t)L * 4, bd::BdB{nullptr, nullptr});
+  x->bd_head = bd::BdB{nullptr, nullptr};
   if (cfg->max_batch > 1) {
-    size_t off = lay.bd_qszt;
-    for (int l = 0; l < L; ++l)
-      for (int m = 0; m < 7; ++m) {
-        const size_t bytes = qszt_matrix_bytes(cfg, m);
-        if (hl[l].qc[m] && hqs[(size_t)l * 7 + m] && hqz[(size_t)l * 7 + m]) {
-          long long rows, cols;
-          matrix_shape(cfg, m, &rows, &cols);
-          const long long n = (long long)(bytes / 4);
-          k_pack_sz_tiles<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, x->stream>>>(
-              hqs[(size_t)l * 7 + m], hqz[(size_t)l * 7 + m], (uint32_t *)(ws + off), (int)rows, (int)cols,
-              cfg->river_group);
-          x->qszt_h[(size_t)l * 7 + m] = ws + off;
+    size_t off = lay.bd_stream;
+    auto blocks_of = [](size_t pieces) { return dim3((unsigned)((pieces + 255) / 256)); };
+    for (int l = 0; l <= L; ++l)
+      for (int g = 0; g < (l < L ? 4 : 1); ++g) {
+        pf::GemmB Bw{}, Bc{}, Bs{};
+        BdGemmShape sh = bd_gemm_shape(cfg, g);
+        bool twin = l < L;
+        if (l == L) {                                         // the LM head
+          sh = BdGemmShape{{0, 0, 0}, 1, 0, cfg->vocab, cfg->d_model};
+          Bw.w[0] = Bw.w[1] = Bw.w[2] = w->lm_head;
+          Bw.rows[0] = cfg->vocab;
+        } else {
+          for (int i = 0; i < 3; ++i) {
+            const int m = sh.ms[i < sh.nm ? i : 0];
+            long long r, cc;
+            matrix_shape(cfg, m, &r, &cc);
+            Bw.w[i] = hl[l].w[m];
+            Bc.w[i] = hl[l].qc[m];
+            Bs.w[i] = hqs[(size_t)l * 7 + m];
+            Bs.sz[i] = hqz[(size_t)l * 7 + m];
+            Bw.rows[i] = Bc.rows[i] = Bs.rows[i] = i < sh.nm ? (int)r : 0;
+            twin = twin && Bc.w[i] && Bs.w[i] && Bs.sz[i];
+          }
         }
-        off += align_up(bytes, 256);
+        const size_t units = bd::bd_units(sh.N);
+        bd::k_bd_pack_dense<<<blocks_of(units * (sh.K / 64) * 64), dim3(256), 0, x->stream>>>(
+            Bw, sh.interleaved, sh.N, sh.K, (uint4 *)(ws + off));
+        bd::BdB dense{ws + off, nullptr};
+        off += align_up(bd::bd_dense_bytes(sh.N, sh.K), 256);
+        if (l == L) { x->bd_head = dense; break; }
+        x->bd_dense_h[(size_t)l * 4 + g] = dense;
+        const size_t cb = align_up(bd::bd_codes_bytes(sh.N, sh.K), 256), pb = align_up(bd::bd_pairs_bytes(sh.N, sh.K), 256);
+        if (twin) {
+          const size_t nkt = (size_t)(sh.K + 127) / 128;
+          bd::k_bd_pack_codes<<<blocks_of(units * nkt * 32), dim3(256), 0, x->stream>>>(
+              Bc, sh.interleaved, sh.N, sh.K, (uint4 *)(ws + off));
+          bd::k_bd_pack_pairs<<<blocks_of(units * nkt * 16), dim3(256), 0, x->stream>>>(
+              Bs, sh.interleaved, sh.N, sh.K, cfg->river_group, (uint32_t *)(ws + off + cb));
+          x->bd_twin_h[(size_t)l * 4 + g] = bd::BdB{ws + off, ws + off + cb};
+        }
+        off += cb + pb;
       }
-    if ((e = hipGetLastError()) != hipSuccess) return fail("river (scale, zero) tile packing", e);
+    if ((e = hipGetLastError()) != hipSuccess) return fail("stream-order weight packing", e);
   }
   x->layers_h = hl;
   x->pos_b.assign(cfg->max_batch, 0);
@@ -940,8 +971,8 @@ static int prefill_gemm(river_ctx *x, int seq, const int32_t *tokens, int n, int
   float *h = (float *)(x->ws + y.pf_h), *big = (float *)(x->ws + y.pf_big);
   _Float16 *x16 = (_Float16 *)(x->ws + y.pf_x16), *q16 = (_Float16 *)(x->ws + y.pf_q16);
   _Float16 *a16 = (_Float16 *)(x->ws + y.pf_a16);
-  const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
   char *kc = (char *)D.kcache + (size_t)seq * y.cache_bytes, *vc = (char *)D.vcache + (size_t)seq * y.cache_bytes;
+  const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
   for (int c0 = 0; c0 < n; c0 += y.pf_rows) {
     const int m = std::min(y.pf_rows, n - c0), rows = (m + 127) / 128 * 128;
     const bool last = c0 + m == n;
@@ -1077,35 +1108,29 @@ extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const in
   return check_device_error(x);
 }
 
-// GEMM of a batched decode step over the matrices ms[0..nm) of block l (stacked along N, or
-// interleaved row by row for the gate/up pair): bf16 matrices for the rows in the backbone,
-// 4-bit twins for the others (see bd::k_bd_gemm).  The rows of B are dealt out to one
-// workgroup per CU, eight at a time.
-static int launch_bd_gemm_b(river_ctx *x, const pf::GemmB &Bd, const pf::GemmB &Bq, int interleaved, int N,
-                            const _Float16 *Af, int K, void *C, int ldc, int epi, int by_flag, int n) {
+// GEMM g (QKV, O, gate/up, down) of block l of a batched decode step, or the LM head (Bq null,
+// by_flag 0): bf16 matrices for the rows in the backbone, 4-bit twins for the others (see
+// bd::k_bd_gemm).  The rows of B are dealt out to one workgroup per CU, eight at a time.
+static int launch_bd_gemm_b(river_ctx *x, const bd::BdB &Bd, const bd::BdB &Bq, int N, const _Float16 *Af, int K,
+                            void *C, int ldc, int epi, int by_flag, int n) {
   // A matrix with at most 16 rows per CU (output and down projection) would have every workgroup
   // read the whole activation tile for a single row block; it is dealt out as K slices of four
   // times the rows instead, and the kernel that consumes the sum adds the partial sums up.
-  const bool single = Bd.rows[1] == 0 && Bd.rows[2] == 0;
   int k_split = 1;
-  if (epi == bd::EPI_ADD && single && N <= 16 * x->grid_persist && K >= 4096 && ldc == x->cfg.d_model)
-    k_split = bd::kBdKSplit;
+  if (epi == bd::EPI_ADD && N <= 16 * x->grid_persist && K >= 4096 && ldc == x->cfg.d_model) k_split = bd::kBdKSplit;
   const int per_cu = (N * k_split + x->grid_persist - 1) / x->grid_persist;
   const int rows_per_wg = std::max(8, (per_cu + 7) / 8 * 8);
   const int blocks = (rows_per_wg + 15) / 16;
   const dim3 grid((N + rows_per_wg - 1) / rows_per_wg * k_split), blk(512);
   hipStream_t s = x->stream;
-  const int g = x->cfg.river_group;
   const int *rv = x->st_b.river;
   if (k_split > 1) { C = x->ws + x->lay.bd_partial; epi = bd::EPI_STORE; }
-#define RIVER_BD_LAUNCH(MB, RBW)                                                                                      \
-  bd::k_bd_gemm<MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, Bd, Bq, interleaved, N, K, g, C, ldc, epi, \
-                                                                          rv, by_flag, n, rows_per_wg, k_split)
-  // passes of eight row blocks address the rows by a stride: one matrix, or the interleaved pair
-  const bool strided_ok = interleaved || single;
+#define RIVER_BD_LAUNCH(MB, RBW)                                                                               \
+  bd::k_bd_gemm<MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, Bd, Bq, N, K, C, ldc, epi, rv, \
+                                                                          by_flag, n, rows_per_wg, k_split)
   if (n <= 16) {
     if (blocks <= 1) RIVER_BD_LAUNCH(1, 1);
-    else if (blocks <= 2 || !strided_ok) RIVER_BD_LAUNCH(1, 2);
+    else if (blocks <= 2) RIVER_BD_LAUNCH(1, 2);
     else if (blocks <= 4) RIVER_BD_LAUNCH(1, 4);
     else RIVER_BD_LAUNCH(1, 8);
   } else {
@@ -1115,21 +1140,10 @@ static int launch_bd_gemm_b(river_ctx *x, const pf::GemmB &Bd, const pf::GemmB &
 #undef RIVER_BD_LAUNCH
   return k_split > 1 ? k_split : 0;          // partial sums the consumer has to add
 }
-static int launch_bd_gemm(river_ctx *x, int l, const int *ms, int nm, int interleaved, const _Float16 *Af, int K,
-                          void *C, int ldc, int epi, int n) {
-  pf::GemmB Bd{}, Bq{};
-  int N = 0;
-  for (int i = 0; i < nm; ++i) {
-    long long r, c;
-    matrix_shape(&x->cfg, ms[i], &r, &c);
-    Bd.w[i] = x->layers_h[l].w[ms[i]];
-    Bq.w[i] = x->layers_h[l].qc[ms[i]];
-    Bq.sz[i] = x->qszt_h[(size_t)l * 7 + ms[i]];
-    Bd.rows[i] = Bq.rows[i] = (int)r;
-    N += (int)r;
-  }
-  for (int i = nm; i < 3; ++i) { Bd.w[i] = Bd.w[0]; Bq.w[i] = Bq.w[0]; Bq.sz[i] = Bq.sz[0]; }
-  return launch_bd_gemm_b(x, Bd, Bq, interleaved, N, Af, K, C, ldc, epi, 1, n);
+static int launch_bd_gemm(river_ctx *x, int l, int g, const _Float16 *Af, void *C, int ldc, int epi, int n) {
+  const BdGemmShape sh = bd_gemm_shape(&x->cfg, g);
+  return launch_bd_gemm_b(x, x->bd_dense_h[(size_t)l * 4 + g], x->bd_twin_h[(size_t)l * 4 + g], sh.N, Af, sh.K, C, ldc,
+                          epi, 1, n);
 }
 
 extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in_tokens, const int32_t *forced_exit,
@@ -1181,7 +1195,6 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   if (in_tokens) HIP_TRY(x, hipMemcpyAsync(st.token, in_tokens, (size_t)n * 4, hipMemcpyHostToDevice, s));
   bd::k_bd_fill_nan<<<dim3((n * L + 255) / 256), dim3(256), 0, s>>>(rec_sims, n * L);
   bd::k_bd_embed<<<dim3(n), dim3(256), 0, s>>>(st, D.tok_emb, d, c.vocab, L, h, hprev, hist);
-  const int m_qkv[3] = {M_WQ, M_WK, M_WV}, m_o[1] = {M_WO}, m_gu[2] = {M_GATE, M_UP}, m_d[1] = {M_DOWN};
   const size_t seq_stride = y.cache_bytes / 2;               // elements (bf16)
   // attention: one workgroup per (sequence, kv head, group of query heads, split of the positions);
   // splits so that every CU has two workgroups (measured best) of at least 128 positions
@@ -1197,7 +1210,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
     const DevLayer &W = x->layers_h[l];
     // the norm in front of the QKV GEMM: block 1's here, the others' by the previous block's last kernel
     if (l == 0) bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.attn_norm, d, c.rms_eps, x16, nullptr, 0);
-    launch_bd_gemm(x, l, m_qkv, 3, 0, x16, d, big, qkv_ld, bd::EPI_STORE, n);
+    launch_bd_gemm(x, l, 0, x16, big, qkv_ld, bd::EPI_STORE, n);
     {
       const dim3 ga((n * c.n_kv_heads * n_splits + 7) / 8 * 8 * hgs);
       auto attn = c.head_dim == 128
@@ -1208,11 +1221,11 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
       attn<<<ga, dim3(256), attn_lds, s>>>(big, D.rope, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq,
                                            seq_stride, st.pos, n_splits, part_o, part_ml, tickets, o16);
     }
-    const int po = launch_bd_gemm(x, l, m_o, 1, 0, o16, qd, h, d, bd::EPI_ADD, n);
+    const int po = launch_bd_gemm(x, l, 1, o16, h, d, bd::EPI_ADD, n);
     bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16, partial, po);
     // gate and up rows interleaved, SwiGLU in the epilogue: the down projection's input as fp16
-    launch_bd_gemm(x, l, m_gu, 2, 1, x16, d, a16, ffn, bd::EPI_SWIGLU, n);
-    const int pd = launch_bd_gemm(x, l, m_d, 1, 0, a16, ffn, h, d, bd::EPI_ADD, n);
+    launch_bd_gemm(x, l, 2, x16, a16, ffn, bd::EPI_SWIGLU, n);
+    const int pd = launch_bd_gemm(x, l, 3, a16, h, d, bd::EPI_ADD, n);
     // similarity, the sequences' own exit decisions, and the norm in front of the next GEMM
     const bool may_exit = l + 1 >= c.min_exit_layer && l + 1 < L;
     const bool batch_rule = c.batch_exit_rule == 1;
@@ -1224,12 +1237,7 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
       bd::k_bd_decide<<<dim3(1), dim3(64), 0, s>>>(n, l + 1, L, c.min_exit_layer, c.tau, c.batch_exit_rule, st, s_of);
   }
   // the original LM head (its input is already normalised), greedy token per sequence
-  {
-    pf::GemmB Bh{};
-    Bh.w[0] = Bh.w[1] = Bh.w[2] = D.lm_head;
-    Bh.rows[0] = c.vocab;
-    launch_bd_gemm_b(x, Bh, Bh, 0, c.vocab, x16, d, logits, c.vocab, bd::EPI_STORE, 0, n);
-  }
+  launch_bd_gemm_b(x, x->bd_head, x->bd_head, c.vocab, x16, d, logits, c.vocab, bd::EPI_STORE, 0, n);
   bd::k_bd_argmax<<<dim3(n), dim3(256), 0, s>>>(logits, c.vocab, st, rec_token, rec_exit);
   HIP_TRY(x, hipGetLastError());
   for (int b = 0; b < n; ++b) x->pos_b[b] += 1;

@@ -517,6 +517,76 @@ __device__ __forceinline__ void frag_store8(_Float16 *xf, int K, int m, int k, h
   *(half8 *)(xf + frag_halfs(K) + frag_index_w4(m, k)) = v;
 }
 
+// The weights of a batched GEMM are kept a second time in **stream order**: the rows of the GEMM
+// (matrices stacked along N, or the gate/up pair interleaved row by row) in units of 8 rows, and per
+// unit and K tile the 16-byte pieces in the order the lanes of a wavefront fetch them ([lane group
+// g][row % 8]).  A load instruction of a wavefront then reads two runs of 512 contiguous bytes (the
+// two 8-row halves of its MFMA block) instead of 64 bytes from each of 16 rows, and the K tiles of
+// a unit follow each other in memory.
+//   bf16:   [unit][K tile of 64][step s][g][row % 8][columns k0 + 32 s + 8 g .. + 7]
+//   codes:  [unit][K tile of 128][g][row % 8][16 bytes: columns k0 + 32 g .. + 31]
+//   pairs:  [unit][K tile of 128][row % 8][64-column half] -- (scale, zero) as one packed word
+// Rows beyond N and columns beyond K are zero (pairs: the row's last group).
+struct BdB { const void *w, *sz; };
+__host__ __device__ inline size_t bd_units(int N) { return (size_t)(N + 7) / 8; }
+__host__ __device__ inline size_t bd_dense_bytes(int N, int K) { return bd_units(N) * (size_t)((K + 63) / 64) * 1024; }
+__host__ __device__ inline size_t bd_codes_bytes(int N, int K) { return bd_units(N) * (size_t)((K + 127) / 128) * 512; }
+__host__ __device__ inline size_t bd_pairs_bytes(int N, int K) { return bd_units(N) * (size_t)((K + 127) / 128) * 64; }
+
+// row n of the GEMM -> (matrix, row) of the row-major source
+__device__ __forceinline__ void bd_src_row(const GemmB &B, int interleaved, int n, int N, int &mat, int &row) {
+  if (interleaved) { mat = n & 1; row = n >> 1; }
+  else gemm_b_row(B, n, N, mat, row);
+}
+// one thread per 16-byte piece; K % 64 == 0, rows 16-byte aligned
+__global__ void k_bd_pack_dense(GemmB B, int interleaved, int N, int K, uint4 *out) {
+  const int nkt = (K + 63) / 64;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= bd_units(N) * nkt * 64) return;
+  const int r8 = (int)(i & 7), g = (int)((i >> 3) & 3), st = (int)((i >> 5) & 1);
+  const size_t t = i >> 6;
+  const int kt = (int)(t % nkt), n = (int)(t / nkt) * 8 + r8, k = kt * 64 + st * 32 + g * 8;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (n < N && k + 8 <= K) {
+    int mat, row;
+    bd_src_row(B, interleaved, n, N, mat, row);
+    v = *(const uint4 *)((const char *)B.w[mat] + ((size_t)row * K + k) * 2);
+  }
+  out[i] = v;
+}
+__global__ void k_bd_pack_codes(GemmB B, int interleaved, int N, int K, uint4 *out) {
+  const int nkt = (K + 127) / 128;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= bd_units(N) * nkt * 32) return;
+  const int r8 = (int)(i & 7), g = (int)((i >> 3) & 3);
+  const size_t t = i >> 5;
+  const int kt = (int)(t % nkt), n = (int)(t / nkt) * 8 + r8, k = kt * 128 + g * 32;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (n < N && k + 32 <= K) {
+    int mat, row;
+    bd_src_row(B, interleaved, n, N, mat, row);
+    v = *(const uint4 *)((const char *)B.w[mat] + (size_t)row * (K >> 1) + (k >> 1));
+  }
+  out[i] = v;
+}
+// S.w[m] / S.sz[m]: the scales / zero points of matrix m, [rows][ceil(K / group)] bf16
+__global__ void k_bd_pack_pairs(GemmB S, int interleaved, int N, int K, int group, uint32_t *out) {
+  const int nkt = (K + 127) / 128, gpr = (K + group - 1) / group;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= bd_units(N) * nkt * 16) return;
+  const int j = (int)(i & 1), r8 = (int)((i >> 1) & 7);
+  const size_t t = i >> 4;
+  const int kt = (int)(t % nkt), n = (int)(t / nkt) * 8 + r8, k = kt * 128 + j * 64;
+  uint32_t v = 0;
+  if (n < N) {
+    int mat, row;
+    bd_src_row(S, interleaved, n, N, mat, row);
+    const size_t src = (size_t)row * gpr + min(k / group, gpr - 1);
+    v = Store<1>::pack(Store<1>::ld(S.w[mat], src), Store<1>::ld(S.sz[mat], src));
+  }
+  out[i] = v;
+}
+
 // xf[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain) in fragment order (both);
 // one workgroup (256) per sequence row; d % 8 == 0
 // The row-wise kernels of a batched step (one workgroup of 256 per sequence row) read their row
@@ -591,7 +661,8 @@ __global__ __launch_bounds__(256) void k_bd_rmsnorm(float *__restrict__ h, const
 // 4-bit codes).  A lane loads its MFMA operands directly in the layout the instruction wants --
 // no LDS on the way: for B, lane (n = lane % 16, g = lane / 16) fetches 16 bytes of row n (dense:
 // columns k0 + 32 s + 8 g .. + 7 for the tile's two steps s; codes: the 32 columns
-// k0 + 32 g .. + 31, one step per code word, which lie in one quantisation group), for A the
+// k0 + 32 g .. + 31, one step per code word, which lie in one quantisation group) from the
+// stream-order copy of the weights (see BdB), where they are the lane's piece of a contiguous run, for A the
 // same columns of sequence row n (fp16, kept in fragment order: one contiguous 1 KiB per
 // wavefront and step, from the L2; every workgroup reads the whole tile once, shared by its RBW
 // row blocks).  P tiles are in flight per wavefront in registers.  The partial tiles of the
@@ -609,8 +680,8 @@ template <int RBW, int MB> struct BdDepth {                 // K tiles in flight
 __host__ __device__ inline size_t bd_gemm_lds_bytes(int rbw, int mb) { return (size_t)kBdWaves * rbw * mb * 256 * 4; }
 
 template <bool W4, int MB, int RBW>
-__device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, const GemmB &B, int interleaved, int N,
-                                             int K, int group, void *C, int ldc, int epi,
+__device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, const BdB &B, int N,
+                                             int K, void *C, int ldc, int epi,
                                              const int *__restrict__ river, int want, int n_rows, int rows_per_wg,
                                              int k_split, int w0, int nw,
                                              float *red /* [kBdWaves][RBW][MB][256] */) {
@@ -633,41 +704,17 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
   const int kl = W4 ? kg * 32 : kg * 8;
   struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint32_t sz[W4 ? RBW : 1]; };
   for (int p0 = wg_r0; p0 < wg_r1; p0 += RBW * 16) {
-    // Row pointers of this lane's RBW rows (n = p0 + 16 rb + lane % 16).  Passes of more than two
-    // blocks are only launched on a single matrix or an interleaved pair, where the rows of
-    // consecutive blocks are a fixed distance apart: one pointer and a stride instead of RBW.
-    constexpr bool STRIDED = RBW > 2;
-    constexpr int NP = STRIDED ? 1 : RBW;
-    const char *bp[NP], *szp[NP];
-    unsigned szs[NP];                                         // bytes of one K tile of the pair table
-    size_t bstride = 0;
-    unsigned sstride = 0;
-#pragma unroll
-    for (int rb = 0; rb < NP; ++rb) {
-      const int n = p0 + rb * 16 + r16;
-      int mat, r;
-      if (interleaved) { mat = n & 1; r = n >> 1; }
-      else if (STRIDED) { mat = 0; r = n; }
-      else gemm_b_row(B, n, N, mat, r);
-      const size_t row_bytes = W4 ? (size_t)(K >> 1) : (size_t)K * 2;
-      bp[rb] = (const char *)B.w[mat] + (size_t)r * row_bytes + (W4 ? (kl >> 1) : kl * 2);
-      bstride = (interleaved ? 8 : 16) * row_bytes;
-      if constexpr (W4) {
-        szp[rb] = (const char *)B.sz[mat] + ((size_t)r * 2 + (kg >> 1)) * 4;    // [K tile][row][half], see k_pack_sz_tiles
-        szs[rb] = (unsigned)B.rows[mat] * 8u;
-        sstride = (interleaved ? 8 : 16) * 8;
-      } else {
-        szp[rb] = nullptr;
-        szs[rb] = 0;
-      }
-    }
+    // this lane's 16-byte piece of K tile 0 of row block 0 (stream order, see BdB): unit p0 / 8 or the
+    // next one, piece [g][row % 8]; a row block further is 2 units, a K tile further one tile
+    const size_t unit = (size_t)(p0 >> 3) + (r16 >> 3);
+    const char *bp = (const char *)B.w + unit * nkt_all * (W4 ? 512 : 1024) + (kg * 8 + (r16 & 7)) * 16;
+    const char *szp = W4 ? (const char *)B.sz + unit * nkt_all * 64 + ((r16 & 7) * 2 + (kg >> 1)) * 4 : nullptr;
+    const size_t bstride = (size_t)nkt_all * (W4 ? 1024 : 2048);
+    const unsigned sstride = (unsigned)nkt_all * 128u;
     auto row_ok = [&](int rb) { return p0 + rb * 16 + r16 < wg_r1; };
-    auto b_ptr = [&](int rb) { return STRIDED ? bp[0] + (size_t)rb * bstride : bp[rb < NP ? rb : 0]; };
-    auto sz_ptr = [&](int rb) { return STRIDED ? szp[0] + (unsigned)rb * sstride : szp[rb < NP ? rb : 0]; };
-    auto sz_tile = [&](int rb) { return szs[STRIDED ? 0 : (rb < NP ? rb : 0)]; };
     auto load = [&](int kt, Stage &t) {
       const int k0 = kt * TILE;
-      const bool kok = k0 + kl + (W4 ? 32 : 8) <= K;          // dense: also the second step's columns, K % 64 == 0
+      const bool kok = k0 + kl + (W4 ? 32 : 8) <= K;          // columns of A beyond K are not defined (B's are zero)
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -676,13 +723,13 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb) {
         if constexpr (W4) {
-          const bool v = row_ok(rb) && kok;
-          t.b[rb] = v ? ld_stream16(b_ptr(rb) + (k0 >> 1)) : make_uint4(0, 0, 0, 0);
-          t.sz[rb] = v ? *RIVER_GLOBAL(uint32_t, sz_ptr(rb) + (unsigned)kt * sz_tile(rb)) : 0u;
+          const bool v = row_ok(rb);
+          t.b[rb] = v ? ld_stream16(bp + rb * bstride + (size_t)kt * 512) : make_uint4(0, 0, 0, 0);
+          t.sz[rb] = v ? *RIVER_GLOBAL(uint32_t, szp + rb * sstride + (unsigned)kt * 64u) : 0u;
         } else {
 #pragma unroll
           for (int s = 0; s < 2; ++s)
-            t.b[rb * 2 + s] = row_ok(rb) && kok ? ld_stream16(b_ptr(rb) + (size_t)(k0 + s * 32) * 2) : make_uint4(0, 0, 0, 0);
+            t.b[rb * 2 + s] = row_ok(rb) ? ld_stream16(bp + rb * bstride + (size_t)kt * 1024 + s * 512) : make_uint4(0, 0, 0, 0);
         }
       }
     };
@@ -773,8 +820,8 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
 // workgroup reading all of A for one row block) are dealt out as k_split K slices of four times
 // the rows; C is then the partial-sum buffer [k_split][32][ldc].
 template <int MB, int RBW>
-__global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af, GemmB Bd, GemmB Bq, int interleaved,
-                                                 int N, int K, int group, void *C, int ldc, int epi,
+__global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af, BdB Bd, BdB Bq,
+                                                 int N, int K, void *C, int ldc, int epi,
                                                  const int *__restrict__ river, int by_flag, int n_rows,
                                                  int rows_per_wg, int k_split) {
   extern __shared__ float red[];
@@ -789,10 +836,10 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af
   constexpr int ND = kBdWaves / 2;                              // wavefronts of the bf16 side when both run (3 .. 4 measured best)
   const bool second = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) >= ND;   // (a scalar branch)
   if (dense && (!twin || !second))
-    bd_gemm_pass<false, MB, RBW>(Af, Bd, interleaved, N, K, group, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
+    bd_gemm_pass<false, MB, RBW>(Af, Bd, N, K, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
                                  rows_per_wg, k_split, 0, twin ? ND : kBdWaves, red);
   if (twin && (!dense || second))
-    bd_gemm_pass<true, MB, RBW>(Af + frag_halfs(K), Bq, interleaved, N, K, group, C, ldc, epi, river, 1, n_rows,
+    bd_gemm_pass<true, MB, RBW>(Af + frag_halfs(K), Bq, N, K, C, ldc, epi, river, 1, n_rows,
                                 rows_per_wg, k_split, dense ? ND : 0, dense ? kBdWaves - ND : kBdWaves, red);
 }
 
