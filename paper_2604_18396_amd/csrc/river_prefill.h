@@ -470,23 +470,17 @@ __device__ __forceinline__ f32x4v mfma16x16(half8 a, half8 b, f32x4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
-// Eight 4-bit codes of one 32-bit word (byte j = column 2j in the low nibble, 2j+1 in the high
-// nibble) -> eight fp16 weights (code - zero) * scale in column order.  A nibble n becomes the
-// half value 1024 + n by placing it in the mantissa of 1024.0; subtracting 1024 is exact, and
-// code * scale - zero * scale is one packed fma; -zero*scale is carried as a high and a low
-// half (nzh2, nzl2), so that its rounding does not add a common offset to a whole group.
-__device__ __forceinline__ half8 dequant8(uint32_t w, half2v sc2, half2v nzh2, half2v nzl2) {
-  const uint32_t lo4 = w & 0x0f0f0f0fu, hi4 = (w >> 4) & 0x0f0f0f0fu;
-  const half2v k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+// Eight 4-bit codes of one 32-bit word of the stream-order copy (see BdB: nibble j holds column 2j,
+// nibble 4 + j column 2j + 1) -> the eight fp16 values 16 + code in column order: a nibble placed
+// in bits 6..9 of the mantissa of 16.0 adds exactly its value, and pair j of the word needs one
+// shift and one and-or.  Scale and zero point are applied to the products of a whole quantisation
+// group (see bd_gemm_pass), not to the weights, so nothing is rounded here.
+__device__ __forceinline__ half8 raw8(uint32_t w) {
   half8 out;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    // bytes of the pair: [lo4.byte j, 0, hi4.byte j, 0] (v_perm_b32: selector 0x0c gives 0x00;
-    // bytes 0-3 index the second operand, 4-7 the first)
-    const uint32_t sel = 0x0c000c00u | (uint32_t)j | ((uint32_t)(4 + j) << 16);
-    const uint32_t pr = __builtin_amdgcn_perm(hi4, lo4, sel) | 0x64006400u;
-    half2v q = __builtin_bit_cast(half2v, pr) - k1024;
-    q = (q * sc2 + nzh2) + nzl2;
+    const uint32_t sh = j < 2 ? w << (6 - 4 * j) : w >> (4 * j - 6);
+    const half2v q = __builtin_bit_cast(half2v, (sh & 0x03c003c0u) | 0x4c004c00u);
     out[2 * j] = q[0];
     out[2 * j + 1] = q[1];
   }
@@ -495,27 +489,14 @@ __device__ __forceinline__ half8 dequant8(uint32_t w, half2v sc2, half2v nzh2, h
 
 // The activations of a batched step (up to 32 sequence rows x K) are kept in the order the
 // matrix-core operands are fetched in, so that a wavefront's A fragment of one MFMA step is one
-// contiguous 1 KiB load: [K tile][step][row block of 16][lane group g][row % 16][8 columns].
-// Two such orders, one per weight format: dense tiles are 64 columns (step s, group g: columns
-// k0 + 32 s + 8 g .. + 7), 4-bit tiles 128 columns (k0 + 32 g + 8 s .. + 7: a lane's four code
-// words are four steps).  A buffer holds both, the dense order first; K is padded to 128.
-__host__ __device__ inline size_t frag_halfs(int K) { return (size_t)32 * ((K + 127) / 128 * 128); }
-__host__ __device__ inline size_t frag_index_dense(int m, int k) {
-  return ((((size_t)(k >> 6) * 2 + ((k >> 5) & 1)) * 2 + (m >> 4)) * 64 + ((k >> 3) & 3) * 16 + (m & 15)) * 8 + (k & 7);
+// contiguous 1 KiB load: [step of 32 columns][row block of 16][lane group g][row % 16][8 columns
+// 32 step + 8 g .. + 7]; 32 x K halfs (K % 32 == 0).
+__host__ __device__ inline size_t frag_index(int m, int k) {
+  return ((((size_t)(k >> 5)) * 2 + (m >> 4)) * 64 + ((k >> 3) & 3) * 16 + (m & 15)) * 8 + (k & 7);
 }
-__host__ __device__ inline size_t frag_index_w4(int m, int k) {
-  return ((((size_t)(k >> 7) * 4 + ((k >> 3) & 3)) * 2 + (m >> 4)) * 64 + ((k >> 5) & 3) * 16 + (m & 15)) * 8 + (k & 7);
-}
-// element (m, k) into both orders of the buffer xf (K columns)
-__device__ __forceinline__ void frag_store(_Float16 *xf, int K, int m, int k, _Float16 v) {
-  xf[frag_index_dense(m, k)] = v;
-  xf[frag_halfs(K) + frag_index_w4(m, k)] = v;
-}
-// eight consecutive elements (m, k .. k+7), k % 8 == 0: one 16-byte store per order
-__device__ __forceinline__ void frag_store8(_Float16 *xf, int K, int m, int k, half8 v) {
-  *(half8 *)(xf + frag_index_dense(m, k)) = v;
-  *(half8 *)(xf + frag_halfs(K) + frag_index_w4(m, k)) = v;
-}
+__device__ __forceinline__ void frag_store(_Float16 *xf, int m, int k, _Float16 v) { xf[frag_index(m, k)] = v; }
+// eight consecutive elements (m, k .. k+7), k % 8 == 0: one 16-byte store
+__device__ __forceinline__ void frag_store8(_Float16 *xf, int m, int k, half8 v) { *(half8 *)(xf + frag_index(m, k)) = v; }
 
 // The weights of a batched GEMM are kept a second time in **stream order**: the rows of the GEMM
 // (matrices stacked along N, or the gate/up pair interleaved row by row) in units of 8 rows, and per
@@ -524,7 +505,8 @@ __device__ __forceinline__ void frag_store8(_Float16 *xf, int K, int m, int k, h
 // two 8-row halves of its MFMA block) instead of 64 bytes from each of 16 rows, and the K tiles of
 // a unit follow each other in memory.
 //   bf16:   [unit][K tile of 64][step s][g][row % 8][columns k0 + 32 s + 8 g .. + 7]
-//   codes:  [unit][K tile of 128][g][row % 8][16 bytes: columns k0 + 32 g .. + 31]
+//   codes:  [unit][K tile of 128][g][row % 8][4 words: word s = columns k0 + 32 s + 8 g .. + 7, column
+//           2j in nibble j and column 2j + 1 in nibble 4 + j] -- a word is the B operand of one MFMA step
 //   pairs:  [unit][K tile of 128][row % 8][64-column half] -- (scale, zero) as one packed word
 // Rows beyond N and columns beyond K are zero (pairs: the row's last group).
 struct BdB { const void *w, *sz; };
@@ -560,14 +542,24 @@ __global__ void k_bd_pack_codes(GemmB B, int interleaved, int N, int K, uint4 *o
   if (i >= bd_units(N) * nkt * 32) return;
   const int r8 = (int)(i & 7), g = (int)((i >> 3) & 3);
   const size_t t = i >> 5;
-  const int kt = (int)(t % nkt), n = (int)(t / nkt) * 8 + r8, k = kt * 128 + g * 32;
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (n < N && k + 32 <= K) {
+  const int kt = (int)(t % nkt), n = (int)(t / nkt) * 8 + r8;
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
+  if (n < N) {
     int mat, row;
     bd_src_row(B, interleaved, n, N, mat, row);
-    v = *(const uint4 *)((const char *)B.w[mat] + (size_t)row * (K >> 1) + (k >> 1));
+    const char *src = (const char *)B.w[mat] + (size_t)row * (K >> 1);
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      const int k = kt * 128 + st * 32 + g * 8;
+      if (k + 8 > K) continue;
+      // row-major: byte j = column k + 2j in the low nibble, k + 2j + 1 in the high nibble
+      const uint32_t v = *(const uint32_t *)(src + (k >> 1));
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        w[st] |= (((v >> (8 * j)) & 0xfu) << (4 * j)) | (((v >> (8 * j + 4)) & 0xfu) << (16 + 4 * j));
+    }
   }
-  out[i] = v;
+  out[i] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 // S.w[m] / S.sz[m]: the scales / zero points of matrix m, [rows][ceil(K / group)] bf16
 __global__ void k_bd_pack_pairs(GemmB S, int interleaved, int N, int K, int group, uint32_t *out) {
@@ -587,8 +579,6 @@ __global__ void k_bd_pack_pairs(GemmB S, int interleaved, int N, int K, int grou
   out[i] = v;
 }
 
-// xf[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain) in fragment order (both);
-// one workgroup (256) per sequence row; d % 8 == 0
 // The row-wise kernels of a batched step (one workgroup of 256 per sequence row) read their row
 // once: thread t owns columns 8 t + 2048 i .. + 7 and keeps up to kRowKeep such runs in registers
 // between the reduction and the second use (rows longer than 2048 kRowKeep columns are read
@@ -614,10 +604,10 @@ __device__ __forceinline__ void norm_store_run8(const Run8 &x, float r, const vo
   half8 o;
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = (_Float16)(x.v[j] * r * Store<1>::ld(gain, k + j));
-  frag_store8(xf, d, t, k, o);
+  frag_store8(xf, t, k, o);
 }
 
-// xf[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain) in fragment order (both); d % 8 == 0
+// xf[t, :] = fp16(h[t, :] * rsqrt(mean(h[t, :]^2) + eps) * gain) in fragment order; d % 8 == 0
 __global__ __launch_bounds__(256) void k_bd_rmsnorm(float *__restrict__ h, const void *gain, int d, float eps,
                                                     _Float16 *xf, const float *__restrict__ part, int n_part) {
   __shared__ float red[16];
@@ -691,7 +681,8 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
   // the pass is run by wavefronts w0 .. w0 + nw - 1 of the workgroup (all eight, or four when the
   // other four run the other weight format beside it); every wavefront of the workgroup executes the
   // same number of workgroup barriers in either case
-  const int tid = threadIdx.x - w0 * 64, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x - w0 * 64, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // (a scalar: K tiles are addressed by scalar offsets)
   const int r16 = lane & 15, kg = lane >> 4;
   red += (size_t)w0 * RBW * MB * 256;
   // workgroup -> (group of rows, slice of K): with k_split > 1 the output is a partial sum, stored
@@ -700,36 +691,53 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
   const int wg_r0 = (blockIdx.x / k_split) * rows_per_wg, wg_r1 = min(N, wg_r0 + rows_per_wg);
   const int nkt_all = (K + TILE - 1) / TILE;
   const int kt0 = (int)((long long)nkt_all * ks / k_split), nkt = (int)((long long)nkt_all * (ks + 1) / k_split);
-  // this lane's column offset inside a K tile (elements)
-  const int kl = W4 ? kg * 32 : kg * 8;
-  struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint32_t sz[W4 ? RBW : 1]; };
+  struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint2 sz[W4 ? RBW : 1]; };
   for (int p0 = wg_r0; p0 < wg_r1; p0 += RBW * 16) {
-    // this lane's 16-byte piece of K tile 0 of row block 0 (stream order, see BdB): unit p0 / 8 or the
-    // next one, piece [g][row % 8]; a row block further is 2 units, a K tile further one tile
-    const size_t unit = (size_t)(p0 >> 3) + (r16 >> 3);
-    const char *bp = (const char *)B.w + unit * nkt_all * (W4 ? 512 : 1024) + (kg * 8 + (r16 & 7)) * 16;
-    const char *szp = W4 ? (const char *)B.sz + unit * nkt_all * 64 + ((r16 & 7) * 2 + (kg >> 1)) * 4 : nullptr;
-    const size_t bstride = (size_t)nkt_all * (W4 ? 1024 : 2048);
-    const unsigned sstride = (unsigned)nkt_all * 128u;
+    // Stream order (see BdB): this lane's 16-byte piece of K tile 0 of row block 0 lies in unit p0 / 8
+    // or the next one, at [g][row % 8]; a row block further is 2 units, a K tile further one tile.
+    // Buffer loads: the pass's base in a descriptor, the lane's part of the address in one 32-bit
+    // register, everything that is the same for all lanes in the scalar offset.
+    constexpr unsigned UB = W4 ? 512u : 1024u;                // bytes of one unit's K tile
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const char *)B.w + (size_t)(p0 >> 3) * nkt_all * UB), 0, 0x7ffffff0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const char *)(W4 ? B.sz : B.w) + (W4 ? (size_t)(p0 >> 3) * nkt_all * 64 : 0)), 0, 0x7ffffff0, 0x00020000);
+    const unsigned vw = (unsigned)(r16 >> 3) * nkt_all * UB + (kg * 8 + (r16 & 7)) * 16;
+    const unsigned vz = (unsigned)(r16 >> 3) * nkt_all * 64u + (r16 & 7) * 8;      // both halves' pairs
+    const unsigned bstride = (unsigned)nkt_all * 2u * UB, sstride = (unsigned)nkt_all * 128u;
+    // Rows beyond the workgroup's range, columns beyond K (and K tiles beyond the slice, where such
+    // a load is issued at all) get an offset beyond the descriptor's range: a buffer load then
+    // returns zero without touching memory, and no load sits behind a branch.
+    constexpr unsigned kOut = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void *)Af, 0, 0x7ffffff0, 0x00020000);
     auto row_ok = [&](int rb) { return p0 + rb * 16 + r16 < wg_r1; };
+    auto ld16 = [&](const __amdgpu_buffer_rsrc_t &r, unsigned voff, unsigned soff, auto stream) {
+      constexpr int aux = decltype(stream)::value ? 2 : 0;    // 2: streaming (read once)
+      const u32x4 v = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, aux));
+      return make_uint4(v.x, v.y, v.z, v.w);
+    };
     auto load = [&](int kt, Stage &t) {
-      const int k0 = kt * TILE;
-      const bool kok = k0 + kl + (W4 ? 32 : 8) <= K;          // columns of A beyond K are not defined (B's are zero)
+      const bool tile = kt < nkt;                             // (the same for all lanes)
+      // step kt * NA + s of the activations; K % 64 == 0, so a 128-column tile may end after two steps
+      // (columns of A beyond K are not defined; B's are zero)
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int s = 0; s < NA; ++s)
-          t.a[i * NA + s] = kok ? *(const uint4 *)(Af + ((size_t)((kt * NA + s) * 2 + i) * 64 + lane) * 8) : make_uint4(0, 0, 0, 0);
+          t.a[i * NA + s] = ld16(ra, tile && (kt * NA + s) * 32 < K ? lane * 16u : kOut,
+                                 (unsigned)((kt * NA + s) * 2 + i) * 1024u, IC<0>{});
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb) {
+        const unsigned vo = tile && row_ok(rb) ? vw : kOut;
         if constexpr (W4) {
-          const bool v = row_ok(rb);
-          t.b[rb] = v ? ld_stream16(bp + rb * bstride + (size_t)kt * 512) : make_uint4(0, 0, 0, 0);
-          t.sz[rb] = v ? *RIVER_GLOBAL(uint32_t, szp + rb * sstride + (unsigned)kt * 64u) : 0u;
+          t.b[rb] = ld16(rw, vo, rb * bstride + (unsigned)kt * UB, IC<1>{});
+          const u32x2 q = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(
+                                                        rz, tile && row_ok(rb) ? vz : kOut,
+                                                        rb * sstride + (unsigned)kt * 64u, 0));
+          t.sz[rb] = make_uint2(q.x, q.y);
         } else {
 #pragma unroll
-          for (int s = 0; s < 2; ++s)
-            t.b[rb * 2 + s] = row_ok(rb) ? ld_stream16(bp + rb * bstride + (size_t)kt * 1024 + s * 512) : make_uint4(0, 0, 0, 0);
+          for (int s = 0; s < 2; ++s) t.b[rb * 2 + s] = ld16(rw, vo, rb * bstride + (unsigned)kt * UB + s * 512u, IC<1>{});
         }
       }
     };
@@ -739,21 +747,39 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
 #pragma unroll
       for (int i = 0; i < MB; ++i) acc[rb][i] = f32x4v{0.f, 0.f, 0.f, 0.f};
     auto compute = [&](const Stage &t) {
+      if constexpr (W4) {
+        // The codes go into the matrix cores as they are (16 + code, see raw8).  Per 64-column half of
+        // the tile, which lies in one quantisation group: (W x)[m][n] = scale_n * sum_k a_mk (16 +
+        // code_nk) - scale_n * (16 + zero_n) * sum_k a_mk; the last sum (rs) comes in the layout of
+        // the product tile from a product with a matrix of ones, shared by the row blocks.
+        const half8 ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f,
+                            (_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
 #pragma unroll
-      for (int rb = 0; rb < RBW; ++rb) {
-        if constexpr (W4) {
-          const float nz = -bf16_hi(t.sz[rb]) * bf16_lo(t.sz[rb]);
-          const _Float16 sc = (_Float16)bf16_lo(t.sz[rb]), nzh = (_Float16)nz, nzl = (_Float16)(nz - (float)nzh);
-          const half2v sc2 = {sc, sc}, nzh2 = {nzh, nzh}, nzl2 = {nzl, nzl};
-          const uint32_t w[4] = {t.b[rb].x, t.b[rb].y, t.b[rb].z, t.b[rb].w};
+        for (int hf = 0; hf < 2; ++hf) {
+          f32x4v rs[MB];
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const half8 b = dequant8(w[s], sc2, nzh2, nzl2);
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-              acc[rb][i] = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + s]), b, acc[rb][i]);
+          for (int i = 0; i < MB; ++i) {
+            rs[i] = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + 2 * hf]), ones, f32x4v{0.f, 0.f, 0.f, 0.f});
+            rs[i] = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + 2 * hf + 1]), ones, rs[i]);
           }
-        } else {
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) {
+            const uint32_t w0 = hf ? t.b[rb].z : t.b[rb].x, w1 = hf ? t.b[rb].w : t.b[rb].y;
+            const uint32_t pr = hf ? t.sz[rb].y : t.sz[rb].x;
+            const half8 b0 = raw8(w0), b1 = raw8(w1);
+            const float sc = bf16_lo(pr), nz = -sc * (16.0f + bf16_hi(pr));
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+              f32x4v tmp = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + 2 * hf]), b0, f32x4v{0.f, 0.f, 0.f, 0.f});
+              tmp = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + 2 * hf + 1]), b1, tmp);
+#pragma unroll
+              for (int r = 0; r < 4; ++r) acc[rb][i][r] += sc * tmp[r] + nz * rs[i][r];
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
           for (int s = 0; s < 2; ++s) {
             const half8 b = bf16x8_to_half8(t.b[rb * 2 + s]);
@@ -761,21 +787,23 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
             for (int i = 0; i < MB; ++i)
               acc[rb][i] = mfma16x16(__builtin_bit_cast(half8, t.a[i * NA + s]), b, acc[rb][i]);
           }
-        }
       }
     };
+    // P stages in flight per wavefront; a round consumes each stage and refills it with the tile P
+    // rounds of wavefronts further.  Refills beyond the slice are skipped -- except in the widest
+    // 4-bit pass, which issues them all the same (beyond the range: no memory access), because the
+    // compiler then needs fewer registers and that pass has none to spare.
+    constexpr bool kAlways = W4 && RBW >= 8;
     Stage st[P];
 #pragma unroll
     for (int u = 0; u < P; ++u)
-      if (kt0 + wv + nw * u < nkt) load(kt0 + wv + nw * u, st[u]);
+      if (kAlways || kt0 + wv + nw * u < nkt) load(kt0 + wv + nw * u, st[u]);
     for (int kt = kt0 + wv; kt < nkt; kt += nw * P) {
 #pragma unroll
       for (int u = 0; u < P; ++u) {
         const int k = kt + nw * u;
-        if (k < nkt) {
-          compute(st[u]);
-          if (k + nw * P < nkt) load(k + nw * P, st[u]);
-        }
+        if (k < nkt) compute(st[u]);
+        if (kAlways || k + nw * P < nkt) load(k + nw * P, st[u]);
       }
     }
     // the partial tiles of the nw wavefronts -> one, in wavefront order; D: register r of lane l is sequence row
@@ -802,7 +830,7 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
       if (epi == EPI_SWIGLU) {
         if (n & 1) continue;
         const float g = total(e), u = total(e + 1);
-        frag_store((_Float16 *)C, ldc, row, n >> 1, (_Float16)(g / (1.0f + expf(-g)) * u));
+        frag_store((_Float16 *)C, row, n >> 1, (_Float16)(g / (1.0f + expf(-g)) * u));
       } else {
         float *p = (float *)C + (size_t)(k_split > 1 ? ks * kRows + row : row) * ldc + n;
         const float v = total(e);
@@ -815,8 +843,8 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
 
 // One launch per GEMM of a step: the bf16 matrices for the rows still in the backbone, then the
 // 4-bit twins for the rows that have left it (by_flag; otherwise the bf16 matrices for all
-// rows, as the LM head needs).  A side without rows is not read.  Af: both fragment orders of
-// the activations (see frag_halfs).  k_split > 1: narrow matrices (16 rows per CU would leave every
+// rows, as the LM head needs).  A side without rows is not read.  Af: the activations in fragment
+// order (see frag_index).  k_split > 1: narrow matrices (16 rows per CU would leave every
 // workgroup reading all of A for one row block) are dealt out as k_split K slices of four times
 // the rows; C is then the partial-sum buffer [k_split][32][ldc].
 template <int MB, int RBW>
@@ -839,7 +867,7 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af
     bd_gemm_pass<false, MB, RBW>(Af, Bd, N, K, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
                                  rows_per_wg, k_split, 0, twin ? ND : kBdWaves, red);
   if (twin && (!dense || second))
-    bd_gemm_pass<true, MB, RBW>(Af + frag_halfs(K), Bq, N, K, C, ldc, epi, river, 1, n_rows,
+    bd_gemm_pass<true, MB, RBW>(Af, Bq, N, K, C, ldc, epi, river, 1, n_rows,
                                 rows_per_wg, k_split, dense ? ND : 0, dense ? kBdWaves - ND : kBdWaves, red);
 }
 
@@ -1086,7 +1114,7 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
     for (int t = tid; t < REP * HD; t += 256) {
       float M, Ls, O;
       split_result(t / HD, t % HD, M, Ls, O);
-      frag_store(o16, qd, b, (h0 + t / HD) * HD + t % HD, (_Float16)(O / Ls));
+      frag_store(o16, b, (h0 + t / HD) * HD + t % HD, (_Float16)(O / Ls));
     }
     return;
   }
@@ -1111,7 +1139,7 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
       Lg = fmaf(sub(part_ml + (pb + j) * 2 + 1), cj, Lg);
       Og = fmaf(sub(part_o + (pb + j) * HD + e), cj, Og);
     }
-    frag_store(o16, qd, b, (h0 + r) * HD + e, (_Float16)(Og / Lg));
+    frag_store(o16, b, (h0 + r) * HD + e, (_Float16)(Og / Lg));
   }
 }
 
