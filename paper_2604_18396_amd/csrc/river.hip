@@ -496,7 +496,7 @@ static Layout make_layout(const river_config *c) {
     y.bd_state = take(6 * B * 4);
     y.bd_hprev = take((size_t)bd::kRows * c->d_model * 4);
     y.bd_part_o = take((size_t)bd::kRows * qd * bd::kBdAttnMaxSplits * 4);      // attention split partials
-    y.bd_part_ml = take((size_t)bd::kRows * c->n_q_heads * bd::kBdAttnMaxSplits * 2 * 4);
+    y.bd_part_ml = take((size_t)bd::kRows * std::max(c->n_q_heads * bd::kBdAttnMaxSplits, bd::kBdArgmaxChunks) * 2 * 4);  // (also the argmax partials)
     y.bd_tickets = take((size_t)bd::kRows * c->n_q_heads * 4);
     y.bd_logits = take(B * c->vocab * 4);
     y.bd_hist = take((size_t)(c->n_layers + 1) * B * c->d_model * 4);
@@ -1238,7 +1238,8 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
   }
   // the original LM head (its input is already normalised), greedy token per sequence
   launch_bd_gemm_b(x, x->bd_head, x->bd_head, c.vocab, x16, d, logits, c.vocab, bd::EPI_STORE, 0, n);
-  bd::k_bd_argmax<<<dim3(n), dim3(256), 0, s>>>(logits, c.vocab, st, rec_token, rec_exit);
+  // (the attention kernels are done with their partial-result area and tickets)
+  bd::k_bd_argmax<<<dim3(n * bd::kBdArgmaxChunks), dim3(256), 0, s>>>(logits, c.vocab, st, rec_token, rec_exit, part_ml, tickets);
   HIP_TRY(x, hipGetLastError());
   for (int b = 0; b < n; ++b) x->pos_b[b] += 1;
   x->steps_b += 1;

@@ -1221,31 +1221,46 @@ __global__ void k_bd_decide(int n, int l1, int L, int min_exit, float tau, int r
   }
 }
 
-// Greedy token of every sequence (lowest index on ties), its record, and the step's end:
-// the sequence advances by one position.  One workgroup per sequence.
+// Greedy token of every sequence (lowest index on ties), its record, and the step's end: the
+// sequence advances by one position.  kBdArgmaxChunks workgroups per sequence scan a chunk of the
+// row each and publish (value, index); the last one to arrive takes the best of them in chunk
+// order (part: [n][chunks][2], tickets: [n], zero between launches).
+constexpr int kBdArgmaxChunks = 16;
 __global__ __launch_bounds__(256) void k_bd_argmax(const float *__restrict__ logits, int vocab, SeqState st,
-                                                   int *rec_token, int *rec_exit) {
+                                                   int *rec_token, int *rec_exit, float *part, unsigned int *tickets) {
   __shared__ float red[64];
-  const int b = blockIdx.x;
+  __shared__ int flag;
+  const int b = blockIdx.x / kBdArgmaxChunks, c = blockIdx.x % kBdArgmaxChunks;
+  const int per = ((vocab + kBdArgmaxChunks - 1) / kBdArgmaxChunks + 3) / 4 * 4;
+  const int i_begin = c * per, i_end = min(vocab, i_begin + per);
   float best = -INFINITY;
   int besti = 0x7fffffff;
   const float *row = logits + (size_t)b * vocab;
   // eight loads in flight per thread (the scan is a chain of load latencies otherwise)
-  for (int i0 = threadIdx.x; i0 < vocab; i0 += 8 * blockDim.x) {
+  for (int i0 = i_begin + threadIdx.x; i0 < i_end; i0 += 8 * blockDim.x) {
     float v[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int i = i0 + u * blockDim.x;
-      v[u] = i < vocab ? row[i] : -INFINITY;
+      v[u] = i < i_end ? row[i] : -INFINITY;
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int i = i0 + u * (int)blockDim.x;
-      argmax_take(best, besti, v[u], i < vocab ? i : 0x7fffffff);
+      argmax_take(best, besti, v[u], i < i_end ? i : 0x7fffffff);
     }
   }
   block_argmax(best, besti, red);
+  float *mine = part + ((size_t)b * kBdArgmaxChunks + c) * 2;
+  if (threadIdx.x == 0) { pub(mine, best); pub(mine + 1, __int_as_float(besti)); }
+  if (!last_arriver(tickets + b, kBdArgmaxChunks, &flag)) return;
   if (threadIdx.x == 0) {
+    best = -INFINITY;
+    besti = 0x7fffffff;
+    for (int j = 0; j < kBdArgmaxChunks; ++j) {
+      const float *pj = part + ((size_t)b * kBdArgmaxChunks + j) * 2;
+      argmax_take(best, besti, sub(pj), __float_as_int(sub(pj + 1)));
+    }
     st.token[b] = besti;
     st.pos[b] += 1;
     if (rec_token) { rec_token[b] = besti; rec_exit[b] = st.exit_pos[b]; }
