@@ -841,9 +841,11 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
       if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lb)) != hipSuccess)
         return fail("hipFuncSetAttribute(max dynamic LDS)", e);
     if (cfg->max_batch > 1) {
-      // the widest batched GEMM keeps 64 KiB of partial tiles beside its static LDS
+      // the widest batched GEMMs keep 64 KiB of partial tiles beside their static LDS
       if ((e = hipFuncSetAttribute((const void *)bd::k_bd_gemm<1, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)bd::bd_gemm_lds_bytes(8, 1))) != hipSuccess)
+                                   (int)bd::bd_gemm_lds_bytes(8, 1))) != hipSuccess ||
+          (e = hipFuncSetAttribute((const void *)bd::k_bd_gemm<2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)bd::bd_gemm_lds_bytes(4, 2))) != hipSuccess)
         return fail("hipFuncSetAttribute(batched GEMM LDS)", e);
     }
   }
@@ -1135,7 +1137,8 @@ static int launch_bd_gemm_b(river_ctx *x, const bd::BdB &Bd, const bd::BdB &Bq, 
     else RIVER_BD_LAUNCH(1, 8);
   } else {
     if (blocks <= 1) RIVER_BD_LAUNCH(2, 1);
-    else RIVER_BD_LAUNCH(2, 2);
+    else if (blocks <= 2) RIVER_BD_LAUNCH(2, 2);
+    else RIVER_BD_LAUNCH(2, 4);
   }
 #undef RIVER_BD_LAUNCH
   return k_split > 1 ? k_split : 0;          // partial sums the consumer has to add

@@ -664,8 +664,8 @@ enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
 constexpr int kBdWaves = 8;
 constexpr int kBdKSplit = 4;                                // K slices of the narrow GEMMs (see k_bd_gemm)
 template <int RBW, int MB> struct BdDepth {                 // K tiles in flight per wavefront (register budget)
-  static constexpr int dense = MB == 1 ? (RBW == 1 ? 8 : RBW == 2 ? 5 : RBW == 4 ? 3 : 2) : (RBW == 1 ? 4 : 3);
-  static constexpr int w4 = MB == 1 ? (RBW == 1 ? 6 : RBW == 2 ? 4 : RBW == 4 ? 3 : 2) : (RBW == 1 ? 3 : 3);
+  static constexpr int dense = MB == 1 ? (RBW == 1 ? 8 : RBW == 2 ? 5 : RBW == 4 ? 3 : 2) : (RBW == 1 ? 4 : RBW == 2 ? 3 : 2);
+  static constexpr int w4 = MB == 1 ? (RBW == 1 ? 6 : RBW == 2 ? 4 : RBW == 4 ? 3 : 2) : (RBW <= 2 ? 3 : 2);
 };
 __host__ __device__ inline size_t bd_gemm_lds_bytes(int rbw, int mb) { return (size_t)kBdWaves * rbw * mb * 256 * 4; }
 
