@@ -251,6 +251,7 @@ struct Layout {
       amax_val, amax_idx, state, rec_token, rec_exit, rec_sims, layers, dev, trace, qsz, total;
   size_t cache_bytes, qsz_bytes;
   size_t bd_partial;                     // [kBdKSplit][32][d_model] partial sums of the K-sliced GEMMs
+  size_t bd_ssq;
   size_t bd_stream, bd_stream_bytes;     // batched contexts: the GEMM weights a second time, in stream order (bd::BdB)
   // activation buffers of the GEMM prefill (pf_rows rows each; 0 rows: that path is not offered)
   size_t pf_tok, pf_h, pf_x16, pf_q16, pf_a16, pf_big;
@@ -504,6 +505,7 @@ static Layout make_layout(const river_config *c) {
     y.bd_rec_exit = take((size_t)bd::kRecordsB * B * 4);
     y.bd_rec_sims = take((size_t)bd::kRecordsB * B * c->n_layers * 4);
     y.bd_partial = take((size_t)bd::kBdKSplit * bd::kRows * c->d_model * 4);
+    y.bd_ssq = take((size_t)kMaxGrid * bd::kRows * 4);                          // sums of squares per GEMM workgroup and row
     y.bd_stream_bytes = bd_stream_bytes_of(c);
     y.bd_stream = take(y.bd_stream_bytes);
   }
@@ -1114,7 +1116,8 @@ extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const in
 // by_flag 0): bf16 matrices for the rows in the backbone, 4-bit twins for the others (see
 // bd::k_bd_gemm).  The rows of B are dealt out to one workgroup per CU, eight at a time.
 static int launch_bd_gemm_b(river_ctx *x, const bd::BdB &Bd, const bd::BdB &Bq, int N, const _Float16 *Af, int K,
-                            void *C, int ldc, int epi, int by_flag, int n) {
+                            void *C, int ldc, int epi, int by_flag, int n, bd::BdNorm nrm = bd::BdNorm{},
+                            int *grid_out = nullptr) {
   // A matrix with at most 16 rows per CU (output and down projection) would have every workgroup
   // read the whole activation tile for a single row block; it is dealt out as K slices of four
   // times the rows instead, and the kernel that consumes the sum adds the partial sums up.
@@ -1124,12 +1127,13 @@ static int launch_bd_gemm_b(river_ctx *x, const bd::BdB &Bd, const bd::BdB &Bq, 
   const int rows_per_wg = std::max(8, (per_cu + 7) / 8 * 8);
   const int blocks = (rows_per_wg + 15) / 16;
   const dim3 grid((N + rows_per_wg - 1) / rows_per_wg * k_split), blk(512);
+  if (grid_out) *grid_out = (int)grid.x;
   hipStream_t s = x->stream;
   const int *rv = x->st_b.river;
   if (k_split > 1) { C = x->ws + x->lay.bd_partial; epi = bd::EPI_STORE; }
 #define RIVER_BD_LAUNCH(MB, RBW)                                                                               \
   bd::k_bd_gemm<MB, RBW><<<grid, blk, bd::bd_gemm_lds_bytes(RBW, MB), s>>>(Af, Bd, Bq, N, K, C, ldc, epi, rv, \
-                                                                          by_flag, n, rows_per_wg, k_split)
+                                                                          by_flag, n, rows_per_wg, k_split, nrm)
   if (n <= 16) {
     if (blocks <= 1) RIVER_BD_LAUNCH(1, 1);
     else if (blocks <= 2) RIVER_BD_LAUNCH(1, 2);
@@ -1143,10 +1147,11 @@ static int launch_bd_gemm_b(river_ctx *x, const bd::BdB &Bd, const bd::BdB &Bq, 
 #undef RIVER_BD_LAUNCH
   return k_split > 1 ? k_split : 0;          // partial sums the consumer has to add
 }
-static int launch_bd_gemm(river_ctx *x, int l, int g, const _Float16 *Af, void *C, int ldc, int epi, int n) {
+static int launch_bd_gemm(river_ctx *x, int l, int g, const _Float16 *Af, void *C, int ldc, int epi, int n,
+                          bd::BdNorm nrm = bd::BdNorm{}, int *grid_out = nullptr) {
   const BdGemmShape sh = bd_gemm_shape(&x->cfg, g);
   return launch_bd_gemm_b(x, x->bd_dense_h[(size_t)l * 4 + g], x->bd_twin_h[(size_t)l * 4 + g], sh.N, Af, sh.K, C, ldc,
-                          epi, 1, n);
+                          epi, 1, n, nrm, grid_out);
 }
 
 extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in_tokens, const int32_t *forced_exit,
@@ -1224,10 +1229,14 @@ extern "C" int river_decode_batch(river_ctx *x, int32_t n_seq, const int32_t *in
       attn<<<ga, dim3(256), attn_lds, s>>>(big, D.rope, D.kcache, D.vcache, c.n_q_heads, c.n_kv_heads, n, l, c.max_seq,
                                            seq_stride, st.pos, n_splits, part_o, part_ml, tickets, o16);
     }
-    const int po = launch_bd_gemm(x, l, 1, o16, h, d, bd::EPI_ADD, n);
-    bd::k_bd_rmsnorm<<<dim3(n), dim3(256), 0, s>>>(h, W.ffn_norm, d, c.rms_eps, x16, partial, po);
+    // The output projection completes h; the norm in front of gate/up rides on the two GEMMs:
+    // fp16(h * gain) and the rows' partial sums of squares from the first, 1 / rms applied by the
+    // second (see bd::BdNorm).
+    float *ssq = (float *)(x->ws + y.bd_ssq);
+    int o_grid = 0;
+    launch_bd_gemm(x, l, 1, o16, h, d, bd::EPI_ADD_NORM, n, bd::BdNorm{W.ffn_norm, x16, ssq, nullptr, 0, 0, 0.f}, &o_grid);
     // gate and up rows interleaved, SwiGLU in the epilogue: the down projection's input as fp16
-    launch_bd_gemm(x, l, 2, x16, a16, ffn, bd::EPI_SWIGLU, n);
+    launch_bd_gemm(x, l, 2, x16, a16, ffn, bd::EPI_SWIGLU, n, bd::BdNorm{nullptr, nullptr, nullptr, ssq, o_grid, d, c.rms_eps});
     const int pd = launch_bd_gemm(x, l, 3, a16, h, d, bd::EPI_ADD, n);
     // similarity, the sequences' own exit decisions, and the norm in front of the next GEMM
     const bool may_exit = l + 1 >= c.min_exit_layer && l + 1 < L;

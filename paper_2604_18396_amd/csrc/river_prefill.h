@@ -660,7 +660,35 @@ __global__ __launch_bounds__(256) void k_bd_rmsnorm(float *__restrict__ h, const
 // op (epi): store fp32, add into fp32, or -- with B's rows interleaved as (gate i, up i) --
 // silu(gate) * up stored as fp16 in fragment order (the activation of the down projection; ldc is
 // then its column count).
-enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
+enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2, EPI_ADD_NORM = 3 };
+// The RMSNorm between a GEMM that completes h and the GEMM that consumes norm(h) costs no pass of
+// its own: the producer (EPI_ADD_NORM: h += A B^T) also stores fp16(h * gain) in fragment order
+// and, per workgroup and sequence row, the sum of squares of the h values it completed
+// (ssq_out[workgroup][32]); the consumer adds those partial sums in workgroup order and applies
+// the row's rsqrt(mean(h^2) + eps) to its product tile, which is the same product up to rounding.
+constexpr int kSsqLoads = 16;                               // partial sums per lane: producers of up to 256 workgroups
+struct BdRowScale {                                         // consumer side, per thread (see k_bd_gemm)
+  float *rscale;                                            // LDS [32], or null: no fused norm
+  float part[kSsqLoads];
+  int d;
+  float eps;
+  __device__ __forceinline__ void finish() const {          // by every thread of the workgroup, before a workgroup barrier
+    float v = 0.f;
+#pragma unroll
+    for (int u = 0; u < kSsqLoads; ++u) v += part[u];
+    v = row16_sum(v);
+    if ((threadIdx.x & 15) == 0 && (threadIdx.x >> 4) < kRows) rscale[threadIdx.x >> 4] = 1.0f / sqrtf(v / (float)d + eps);
+  }
+};
+struct BdNorm {
+  const void *gain;          // producer: gain of the norm in front of the consumer
+  _Float16 *xnext;           // producer: fp16(h * gain), fragment order
+  float *ssq_out;            // producer: [gridDim.x][32]
+  const float *ssq_in;       // consumer: the producer's partial sums, or null
+  int ssq_wgs;               // consumer: workgroups of the producer
+  int d;                     // consumer: length of a row of h
+  float eps;
+};
 constexpr int kBdWaves = 8;
 constexpr int kBdKSplit = 4;                                // K slices of the narrow GEMMs (see k_bd_gemm)
 template <int RBW, int MB> struct BdDepth {                 // K tiles in flight per wavefront (register budget)
@@ -674,7 +702,9 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
                                              int K, void *C, int ldc, int epi,
                                              const int *__restrict__ river, int want, int n_rows, int rows_per_wg,
                                              int k_split, int w0, int nw,
-                                             float *red /* [kBdWaves][RBW][MB][256] */) {
+                                             float *red /* [kBdWaves][RBW][MB][256] */, const BdNorm &nrm,
+                                             const BdRowScale &rsc) {
+  const float *rscale = rsc.rscale;
   constexpr int P = W4 ? BdDepth<RBW, MB>::w4 : BdDepth<RBW, MB>::dense;
   constexpr int TILE = W4 ? 128 : 64;                         // columns per K tile
   constexpr int NA = W4 ? 4 : 2;                              // MFMA steps (16-byte A fragments) per tile
@@ -692,6 +722,9 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
   const int nkt_all = (K + TILE - 1) / TILE;
   const int kt0 = (int)((long long)nkt_all * ks / k_split), nkt = (int)((long long)nkt_all * (ks + 1) / k_split);
   struct Stage { uint4 a[MB * NA], b[RBW * (W4 ? 1 : 2)]; uint2 sz[W4 ? RBW : 1]; };
+  float ssq[MB];                                              // EPI_ADD_NORM: this thread's sum of h^2, row i * 16 + (tid % 256) / 16
+#pragma unroll
+  for (int i = 0; i < MB; ++i) ssq[i] = 0.f;
   for (int p0 = wg_r0; p0 < wg_r1; p0 += RBW * 16) {
     // Stream order (see BdB): this lane's 16-byte piece of K tile 0 of row block 0 lies in unit p0 / 8
     // or the next one, at [g][row % 8]; a row block further is 2 units, a K tile further one tile.
@@ -808,6 +841,7 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
     }
     // the partial tiles of the nw wavefronts -> one, in wavefront order; D: register r of lane l is sequence row
     // (l / 16) * 4 + r, B row l % 16
+    if (rscale && p0 == wg_r0) rsc.finish();                  // (visible after the barriers below)
     __syncthreads();                                          // the previous pass has been read
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb)
@@ -821,11 +855,12 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
     for (int e = tid; e < TILE_F; e += nw * 64) {
       const int rb = e / (MB * 256), i = (e / 256) % MB, row = i * 16 + ((e & 255) >> 4), n = p0 + rb * 16 + (e & 15);
       if (row >= n_rows || n >= wg_r1 || !(want < 0 || river[row] == want)) continue;
+      const float rs_row = rscale ? rscale[row] : 1.0f;
       auto total = [&](int idx) {
         float v = red[idx];
 #pragma unroll
         for (int w = 1; w < nw; ++w) v += red[w * TILE_F + idx];
-        return v;
+        return v * rs_row;
       };
       if (epi == EPI_SWIGLU) {
         if (n & 1) continue;
@@ -834,9 +869,32 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
       } else {
         float *p = (float *)C + (size_t)(k_split > 1 ? ks * kRows + row : row) * ldc + n;
         const float v = total(e);
-        if (epi == EPI_ADD) *p += v;
+        if (epi == EPI_ADD_NORM) {
+          const float hv = *p + v;
+          *p = hv;
+          frag_store(nrm.xnext, row, n, (_Float16)(hv * Store<1>::ld(nrm.gain, n)));
+#pragma unroll
+          for (int i2 = 0; i2 < MB; ++i2)
+            if (i2 == i) ssq[i2] = fmaf(hv, hv, ssq[i2]);
+        } else if (epi == EPI_ADD) *p += v;
         else *p = v;
       }
+    }
+  }
+  if (epi == EPI_ADD_NORM) {
+    // this workgroup's sums of squares per sequence row: the 16 lanes of a row, then the thread
+    // groups 256 apart (the same rows), in a fixed order
+    __syncthreads();                                          // the last pass has been read
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      const float sr = row16_sum(ssq[i]);
+      if ((tid & 15) == 0) red[(tid >> 8) * kRows + i * 16 + ((tid & 255) >> 4)] = sr;
+    }
+    __syncthreads();
+    if (tid < MB * 16 && tid < n_rows && (want < 0 || river[tid] == want)) {
+      float v = red[tid];
+      if (nw * 64 > 256) v += red[kRows + tid];
+      nrm.ssq_out[(size_t)blockIdx.x * kRows + tid] = v;
     }
   }
 }
@@ -851,12 +909,25 @@ template <int MB, int RBW>
 __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af, BdB Bd, BdB Bq,
                                                  int N, int K, void *C, int ldc, int epi,
                                                  const int *__restrict__ river, int by_flag, int n_rows,
-                                                 int rows_per_wg, int k_split) {
+                                                 int rows_per_wg, int k_split, BdNorm nrm) {
   extern __shared__ float red[];
   __shared__ int any[2];
+  __shared__ float rscale[kRows];
   if (threadIdx.x < 2) any[threadIdx.x] = 0;
   __syncthreads();
   if ((int)threadIdx.x < n_rows) any[by_flag && river[threadIdx.x] != 0] = 1;
+  // consumer of a fused norm: the producer's partial sums of squares of row threadIdx.x / 16 are
+  // fetched here (16 lanes per row, up to kSsqLoads each) and added up, in a fixed order, where the
+  // first product tile is complete (BdRowScale::finish) -- their latency is the K loop's
+  BdRowScale rsc{nrm.ssq_in ? rscale : nullptr, {}, nrm.d, nrm.eps};
+  if (nrm.ssq_in) {
+    const int row = threadIdx.x >> 4, j0 = threadIdx.x & 15;
+#pragma unroll
+    for (int u = 0; u < kSsqLoads; ++u) {
+      const int j = j0 + 16 * u;
+      rsc.part[u] = row < n_rows && j < nrm.ssq_wgs ? nrm.ssq_in[(size_t)j * kRows + row] : 0.f;
+    }
+  }
   __syncthreads();
   const bool dense = any[0] != 0, twin = any[1] != 0;
   // Both sides: four wavefronts each, side by side -- the 4-bit side's dequantisation runs in the
@@ -865,10 +936,10 @@ __global__ __launch_bounds__(512) void k_bd_gemm(const _Float16 *__restrict__ Af
   const bool second = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) >= ND;   // (a scalar branch)
   if (dense && (!twin || !second))
     bd_gemm_pass<false, MB, RBW>(Af, Bd, N, K, C, ldc, epi, river, by_flag ? 0 : -1, n_rows,
-                                 rows_per_wg, k_split, 0, twin ? ND : kBdWaves, red);
+                                 rows_per_wg, k_split, 0, twin ? ND : kBdWaves, red, nrm, rsc);
   if (twin && (!dense || second))
     bd_gemm_pass<true, MB, RBW>(Af, Bq, N, K, C, ldc, epi, river, 1, n_rows,
-                                rows_per_wg, k_split, dense ? ND : 0, dense ? kBdWaves - ND : kBdWaves, red);
+                                rows_per_wg, k_split, dense ? ND : 0, dense ? kBdWaves - ND : kBdWaves, red, nrm, rsc);
 }
 
 // h[b, :] = E[token[b], :] (also h_prev and the debug view of h(0)); start-of-step state of
