@@ -437,9 +437,9 @@ __global__ __launch_bounds__(256) void k_pf_attn(const _Float16 *__restrict__ q1
 // Batched decode step (several sequences, each at its own position and exit depth)
 // =====================================================================================
 //
-// One decode step for n sequences, seven launches per block: QKV GEMM, attention (with RoPE and
-// the KV write), O-proj GEMM, norm, gate/up GEMM (SwiGLU in its epilogue), down GEMM, block end
-// (similarity, exit decision, next norm).  Every GEMM runs the bf16 backbone matrices for the
+// One decode step for n sequences, six launches per block: QKV GEMM, attention (with RoPE and
+// the KV write), O-proj GEMM, gate/up GEMM (the norm in front of it rides on these two, see BdNorm;
+// SwiGLU in its epilogue), down GEMM, block end (similarity, exit decision, next norm).  Every GEMM runs the bf16 backbone matrices for the
 // rows (sequences) still in the backbone and the 4-bit river twins for the rows that have left
 // it, over the same activation tile, each side touching only its own rows and not read at all
 // when it has none (so a block whose rows all sit on one side reads one weight set).  With
@@ -716,7 +716,7 @@ __device__ __forceinline__ void bd_gemm_pass(const _Float16 *__restrict__ Af, co
   const int r16 = lane & 15, kg = lane >> 4;
   red += (size_t)w0 * RBW * MB * 256;
   // workgroup -> (group of rows, slice of K): with k_split > 1 the output is a partial sum, stored
-  // as rows 32 ks .. of C for the consumer to add up (see k_bd_rmsnorm)
+  // as rows 32 ks .. of C for the consumer to add up (see load_run8)
   const int ks = blockIdx.x % k_split;
   const int wg_r0 = (blockIdx.x / k_split) * rows_per_wg, wg_r1 = min(N, wg_r0 + rows_per_wg);
   const int nkt_all = (K + TILE - 1) / TILE;
