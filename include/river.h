@@ -127,7 +127,10 @@ int river_quantize_w4(const void *w, int64_t rows, int64_t cols, int32_t group, 
                       void *codes, void *scale, void *zero, void *hip_stream);
 
 /* Bytes of DEVICE workspace river_create needs for this configuration (KV cache,
- * RoPE table, activations, partial results, step records); 0 if cfg is invalid. */
+ * RoPE table, activations, partial results, step records); 0 if cfg is invalid.
+ * A batched context (max_batch > 1) also keeps, in the workspace, a second copy of
+ * every block matrix (bf16 and 4-bit) and of the LM head in the order its GEMM
+ * streams them, written by river_create: about the size of the model again. */
 size_t river_workspace_bytes(const river_config *cfg);
 
 /*
