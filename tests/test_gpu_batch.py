@@ -279,6 +279,30 @@ def test_batch_wide_matrices_several_row_blocks_per_workgroup(n_seq):
     B.close()
 
 
+ODD64B = configs.ModelConfig("odd64-batch-bf16", 3, 320, 10, 2, 64, 448, 1002, 10000.0, 1e-5,
+                             configs.DTYPE_BF16, 80, 0, 2.0)
+
+
+@pytest.mark.parametrize("n_seq", [3, 18])
+def test_batch_half_k_tiles(n_seq):
+    """Column counts that are odd multiples of 64 (d_model 320, n_q*hd 640, d_ffn 448): the last
+    128-column tile of the 4-bit GEMMs is half empty, in all four GEMMs of a block."""
+    cfg = ODD64B
+    say(f"batched decode, half K tiles, {n_seq} sequences")
+    B = Batch(cfg, n_seq, [2 + (7 * b) % 23 for b in range(n_seq)], 271)
+    rng = np.random.default_rng(19)
+    for step in range(3):
+        forced = [int(rng.integers(0, cfg.n_layers + 1)) for _ in range(n_seq)]
+        got = B.g.decode_batch(n_seq, B.toks, forced)
+        res = [o.decode_step(t, f) for o, t, f in zip(B.os, B.toks, forced)]
+        hid = np.array([o.hidden() for o in B.os]).transpose(1, 0, 2)
+        B.compare([r[0] for r in res], [r[1] for r in res], [r[2] for r in res], hid,
+                  [o.logits() for o in B.os], got, f"half tiles step {step}")
+        B.toks = [r[0] for r in res]
+    B.compare_caches()
+    B.close()
+
+
 REP2B = configs.ModelConfig("rep2-batch-bf16", 2, 512, 8, 4, 64, 1024, 1002, 10000.0, 1e-5,
                             configs.DTYPE_BF16, 1040, 0, 2.0)
 
