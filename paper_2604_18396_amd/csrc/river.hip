@@ -842,6 +842,13 @@ static int create_impl(const river_config *cfg, const river_weights *w, const ri
     for (const void *f : fns)
       if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lb)) != hipSuccess)
         return fail("hipFuncSetAttribute(max dynamic LDS)", e);
+    if (gemm_prefill_ok(cfg)) {
+      const void *pfg[] = {(const void *)pf::k_pf_gemm<false, false>, (const void *)pf::k_pf_gemm<false, true>,
+                           (const void *)pf::k_pf_gemm<true, false>, (const void *)pf::k_pf_gemm<true, true>};
+      for (const void *f : pfg)
+        if ((e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, pf::kGemmLdsBytes)) != hipSuccess)
+          return fail("hipFuncSetAttribute(prefill GEMM LDS)", e);
+    }
     if (cfg->max_batch > 1) {
       // the widest batched GEMMs keep 64 KiB of partial tiles beside their static LDS
       if ((e = hipFuncSetAttribute((const void *)bd::k_bd_gemm<1, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -959,8 +966,10 @@ static void launch_gemm(river_ctx *x, int l, const int *ms, int nm, const _Float
     N += (int)r;
   }
   for (int i = nm; i < 3; ++i) { B.w[i] = B.w[0]; B.sz[i] = B.sz[0]; B.rows[i] = 0; }
-  const dim3 grid((N + pf::TN - 1) / pf::TN, rows / pf::TM);
-  pf::k_pf_gemm<W4, ADD><<<grid, dim3(256), 0, x->stream>>>(A, K, B, N, K, x->cfg.river_group, C, N);
+  const int n_tiles = (N + pf::TN - 1) / pf::TN, m_tiles = rows / pf::TM;
+  const dim3 grid((n_tiles + 7) / 8 * 8 * m_tiles);            // (see the kernel's workgroup -> tile mapping)
+  pf::k_pf_gemm<W4, ADD><<<grid, dim3(256), pf::kGemmLdsBytes, x->stream>>>(A, K, B, N, K, x->cfg.river_group, C, N,
+                                                                            m_tiles);
 }
 
 // Prefill phase on the matrix cores: the prompt in chunks of up to pf_rows tokens, every block

@@ -31,6 +31,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kChunk = 1024;          // prompt tokens per pass (rows of the activation buffers)
 constexpr int TM = 128, TN = 128, TK = 64;
 constexpr int LDK = TK + 8;           // LDS row stride in halfs: 144 B, rows 4 banks apart
+constexpr int kGemmLdsBytes = 2 * (TM + TN) * LDK * 2;     // k_pf_gemm: two buffers each of the A and B tiles
 
 // v_mfma_f32_32x32x16_f16: D[32x32] += A[32x16] B[16x32].  Lane l supplies row l % 32 of A and
 // column l % 32 of B, eight K values each (those of lane group l / 32; which eight is the same
@@ -93,12 +94,20 @@ __device__ __forceinline__ void gemm_b_row(const GemmB &B, int n, int N, int &ma
 }
 
 template <bool W4, bool ADD>
-__global__ __launch_bounds__(256) void k_pf_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int N, int K,
-                                                 int group, float *C, int ldc) {
-  __shared__ __attribute__((aligned(16))) _Float16 As[TM * LDK];
-  __shared__ __attribute__((aligned(16))) _Float16 Bs[TN * LDK];
+__global__ __launch_bounds__(256, 2) void k_pf_gemm(const _Float16 *__restrict__ A, int lda, GemmB B, int N, int K,
+                                                 int group, float *C, int ldc, int m_tiles) {
+  extern __shared__ __attribute__((aligned(16))) _Float16 pf_lds[];   // kGemmLdsBytes: two buffers each of A and B
+  _Float16 *const As = pf_lds, *const Bs = pf_lds + 2 * TM * LDK;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  // Workgroup -> tile of C.  Consecutive workgroup ids go round the 8 XCDs; the workgroups of one
+  // XCD take all M tiles of a column of N tiles before the next column, so the workgroups resident
+  // on an XCD at a time cover all M tiles of a few N tiles: a B tile is fetched from HBM once (its
+  // XCD's L2 serves the other M tiles) and the A tiles stay in every L2.
+  // (one-dimensional grid of 8 * ceil(N tiles / 8) * m_tiles workgroups)
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int n_tile = (j / m_tiles) * 8 + xcd, m_tile = j % m_tiles;
+  if (n_tile * TN >= N) return;
+  const int m0 = m_tile * TM, n0 = n_tile * TN;
   const int wm = wv >> 1, wn = wv & 1;
 
   // what this thread stages per K tile: four 16-byte segments of A; of B four 16-byte
@@ -132,28 +141,31 @@ __global__ __launch_bounds__(256) void k_pf_gemm(const _Float16 *__restrict__ A,
     }
   }
 
-  uint4 ra[4], rb[W4 ? 1 : 4];
-  uint32_t rsz = 0;
+  // a K tile on its way from global memory to LDS
+  u32x4 fa[4], fb[W4 ? 1 : 4];                  // (native vectors: as structs they are kept in scratch memory)
+  uint32_t fsz = 0;
+  const int nk = K / TK;
   auto load = [&](int kt) {
     const int k0 = kt * TK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ra[i] = *(const uint4 *)(a_src[i] + (size_t)k0 * 2);
+    for (int i = 0; i < 4; ++i) fa[i] = *(const u32x4 *)(a_src[i] + (size_t)k0 * 2);
     if constexpr (W4) {
-      rb[0] = *(const uint4 *)(b_src[0] + (k0 >> 1));
-      rsz = *(const uint32_t *)(b_sz + (size_t)(k0 / group) * 4);
+      fb[0] = *(const u32x4 *)(b_src[0] + (k0 >> 1));
+      fsz = *(const uint32_t *)(b_sz + (size_t)(k0 / group) * 4);
     } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) rb[i] = *(const uint4 *)(b_src[i] + (size_t)k0 * 2);
+      for (int i = 0; i < 4; ++i) fb[i] = *(const u32x4 *)(b_src[i] + (size_t)k0 * 2);
     }
   };
-  auto stage = [&]() {
+  auto stage = [&](int buf) {
+    _Float16 *const As = pf_lds + buf * TM * LDK, *const Bs = pf_lds + 2 * TM * LDK + buf * TN * LDK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(uint4 *)(As + a_dst[i]) = ra[i];
+    for (int i = 0; i < 4; ++i) *(u32x4 *)(As + a_dst[i]) = fa[i];
     if constexpr (W4) {
       // weight = (code - zero) * scale in fp32, then fp16; byte j of the run holds column 2j
       // in its low nibble and column 2j + 1 in its high nibble
-      const float s = bf16_lo(rsz), z = bf16_hi(rsz);
-      const uint32_t wds[4] = {rb[0].x, rb[0].y, rb[0].z, rb[0].w};
+      const float s = bf16_lo(fsz), z = bf16_hi(fsz);
+      const uint32_t wds[4] = {fb[0].x, fb[0].y, fb[0].z, fb[0].w};
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         half8 h;
@@ -167,7 +179,7 @@ __global__ __launch_bounds__(256) void k_pf_gemm(const _Float16 *__restrict__ A,
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) *(half8 *)(Bs + b_dst[i]) = bf16x8_to_half8(rb[i]);
+      for (int i = 0; i < 4; ++i) *(half8 *)(Bs + b_dst[i]) = bf16x8_to_half8(make_uint4(fb[i].x, fb[i].y, fb[i].z, fb[i].w));
     }
   };
 
@@ -179,30 +191,32 @@ __global__ __launch_bounds__(256) void k_pf_gemm(const _Float16 *__restrict__ A,
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = K / TK;
   const int r32 = lane & 31, g8 = (lane >> 5) * 8;
+  // Tile kt is multiplied from LDS buffer kt % 2 while tile kt + 1 (fetched during the previous
+  // iteration) is written into the other buffer and tile kt + 2 is fetched: one workgroup barrier
+  // per K tile.
   load(0);
-  stage();
+  stage(0);
+  if (nk > 1) load(1);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) load(kt + 1);
+    const int cur = kt & 1;
+    if (kt + 1 < nk) stage(cur ^ 1);
+    if (kt + 2 < nk) load(kt + 2);
+    const _Float16 *const Ac = As + cur * TM * LDK, *const Bc = Bs + cur * TN * LDK;
 #pragma unroll
     for (int ks = 0; ks < TK / 16; ++ks) {
       half8 a[2], b[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *(const half8 *)(As + (wm * 64 + i * 32 + r32) * LDK + ks * 16 + g8);
+      for (int i = 0; i < 2; ++i) a[i] = *(const half8 *)(Ac + (wm * 64 + i * 32 + r32) * LDK + ks * 16 + g8);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = *(const half8 *)(Bs + (wn * 64 + j * 32 + r32) * LDK + ks * 16 + g8);
+      for (int j = 0; j < 2; ++j) b[j] = *(const half8 *)(Bc + (wn * 64 + j * 32 + r32) * LDK + ks * 16 + g8);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = mfma16(a[i], b[j], acc[i][j]);
     }
     __syncthreads();
-    if (kt + 1 < nk) {
-      stage();
-      __syncthreads();
-    }
   }
 #pragma unroll
   for (int i = 0; i < 2; ++i)
