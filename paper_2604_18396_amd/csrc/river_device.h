@@ -122,7 +122,7 @@ template <> struct Store<0> {
   static __device__ __forceinline__ float ld(const void *p, size_t i) { return RIVER_GLOBAL(float, p)[i]; }
   static __device__ __forceinline__ float rnd(float v) { return v; }
   static __device__ __forceinline__ void st(void *p, size_t i, float v) { ((float *)p)[i] = v; }
-  static __device__ __forceinline__ void unpack(const uint4 &w, float (&f)[4]) {
+  static __device__ __forceinline__ void unpack(const u32x4 &w, float (&f)[4]) {
     f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
     f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
   }
@@ -152,7 +152,7 @@ template <> struct Store<1> {
   }
   static __device__ __forceinline__ float rnd(float v) { return __uint_as_float((uint32_t)rne(v) << 16); }
   static __device__ __forceinline__ void st(void *p, size_t i, float v) { ((uint16_t *)p)[i] = rne(v); }
-  static __device__ __forceinline__ void unpack(const uint4 &w, float (&f)[8]) {
+  static __device__ __forceinline__ void unpack(const u32x4 &w, float (&f)[8]) {
     f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
     f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
     f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
@@ -174,13 +174,16 @@ template <> struct Store<1> {
 };
 
 // streaming (read-once) 16- and 8-byte loads of weights
-__device__ __forceinline__ uint4 ld_stream16(const void *p) {
-  const u32x4 v = __builtin_nontemporal_load(RIVER_GLOBAL(u32x4, p));
-  return make_uint4(v.x, v.y, v.z, v.w);
+// (16 bytes travel as the native vector type u32x4: arrays of the uint4 struct are not always
+// kept in registers by the compiler, and a stray element in scratch memory puts a wait for all
+// outstanding loads into the streaming loop.  A component of such a vector is copied into a scalar
+// before it is bit-cast: a bit cast applied to the component expression itself reads component 0.)
+__device__ __forceinline__ u32x4 ld_stream16(const void *p) {
+  return __builtin_nontemporal_load(RIVER_GLOBAL(u32x4, p));
 }
-__device__ __forceinline__ uint4 ld_stream8(const void *p) {
+__device__ __forceinline__ u32x4 ld_stream8(const void *p) {
   const u32x2 v = __builtin_nontemporal_load(RIVER_GLOBAL(u32x2, p));
-  return make_uint4(v.x, v.y, 0, 0);
+  return u32x4{v.x, v.y, 0u, 0u};
 }
 
 // ------------------------------------- activations shared between workgroups
@@ -643,7 +646,7 @@ template <int V> struct IC { static constexpr int value = V; };   // compile-tim
 // Registers of one step: kNL lane loads (codes or dense weights) and, for river rows,
 // the (scale, zero) pair of the group each lane load falls in.
 template <int DT> struct Regs {
-  uint4 w[kNL];
+  u32x4 w[kNL];
   typename Store<DT>::SZ sz[kNL];
 };
 
@@ -671,7 +674,7 @@ template <int DT, int R, int U> struct Dense {
       const int off = (step * U + u) * 1024 + lane * 16;
 #pragma unroll
       for (int r = 0; r < R; ++r)
-        g.w[base + r * U + u] = off < row_bytes ? ld_stream16(rw.p[r] + off) : make_uint4(0, 0, 0, 0);
+        g.w[base + r * U + u] = off < row_bytes ? ld_stream16(rw.p[r] + off) : u32x4{0u, 0u, 0u, 0u};
     }
   }
   static __device__ __forceinline__ void fma(const Regs<DT> &g, int base, int cols, int group, int step,
@@ -722,7 +725,7 @@ template <int DT, int R, int U, int CPL> struct W4 {
           g.w[base + r * U + u] = CPL == 32 ? ld_stream16(rw.p[r] + (c >> 1)) : ld_stream8(rw.p[r] + (c >> 1));
           g.sz[base + r * U + u] = Store<DT>::ldsz(rw.sz[r], gi);
         } else {
-          g.w[base + r * U + u] = make_uint4(0, 0, 0, 0);
+          g.w[base + r * U + u] = u32x4{0u, 0u, 0u, 0u};
           g.sz[base + r * U + u] = Store<DT>::pack(0.f, 0.f);
         }
       }
@@ -747,8 +750,9 @@ template <int DT, int R, int U, int CPL> struct W4 {
   // packed dot product accumulates in fp32, and the 1024 offsets leave with the zero point:
   // sum (code - zero) x = sum (1024 + code) x - (zero + 1024) sum x.
   static constexpr bool HALF = DT == 1 && CPL == 32;
-  static __device__ __forceinline__ float dot8h(uint32_t v, const uint4 &xw, float a) {
+  static __device__ __forceinline__ float dot8h(uint32_t v, const u32x4 &xv, float a) {
     const uint32_t m = 0x000f000fu, one = 0x64006400u;
+    const struct { uint32_t x, y, z, w; } xw = {xv.x, xv.y, xv.z, xv.w};    // (scalars: see ld_stream16)
     a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, (v & m) | one), __builtin_bit_cast(half2_t, xw.x), a, false);
     a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, ((v >> 4) & m) | one), __builtin_bit_cast(half2_t, xw.y), a, false);
     a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, ((v >> 8) & m) | one), __builtin_bit_cast(half2_t, xw.z), a, false);
@@ -763,12 +767,12 @@ template <int DT, int R, int U, int CPL> struct W4 {
       const int gi = step * U + u;                         // granule
       if ((gi * 64 + lane) * 32 < cols) {
         const uint32_t *xp = (const uint32_t *)xl + gi * 1024 + lane * 4;
-        const uint4 x0 = *(const uint4 *)xp, x1 = *(const uint4 *)(xp + 256);
-        const uint4 x2 = *(const uint4 *)(xp + 512), x3 = *(const uint4 *)(xp + 768);
+        const u32x4 x0 = *(const u32x4 *)xp, x1 = *(const u32x4 *)(xp + 256);
+        const u32x4 x2 = *(const u32x4 *)(xp + 512), x3 = *(const u32x4 *)(xp + 768);
         const float sx = sums[gi * 64 + lane];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          const uint4 &w = g.w[base + r * U + u];
+          const u32x4 &w = g.w[base + r * U + u];
           const float aq = dot8h(w.w, x3, dot8h(w.z, x2, dot8h(w.y, x1, dot8h(w.x, x0, 0.f))));
           const float s = Store<DT>::scale(g.sz[base + r * U + u]), z = Store<DT>::zero(g.sz[base + r * U + u]);
           acc[r] = fmaf(s, aq - (z + 1024.0f) * sx, acc[r]);
@@ -797,7 +801,7 @@ template <int DT, int R, int U, int CPL> struct W4 {
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          const uint4 &w = g.w[base + r * U + u];
+          const u32x4 &w = g.w[base + r * U + u];
           float aq = dot8(w.x, x) + dot8(w.y, x + 8);
           if constexpr (CPL == 32) aq += dot8(w.z, x + 16) + dot8(w.w, x + 24);
           const float s = Store<DT>::scale(g.sz[base + r * U + u]), z = Store<DT>::zero(g.sz[base + r * U + u]);
@@ -1045,13 +1049,15 @@ __device__ __forceinline__ void run_phase(DevRef D, int l, bool river, const flo
   });
 }
 
-// value of acc[lane] for lane < R (register arrays cannot be indexed by a lane id)
+// value of acc[lane] for lane < R.  Register arrays cannot be indexed by a lane id, and a chain of
+// selects is turned back into such an index by the compiler (which then keeps the accumulators of
+// the streaming loop in scratch memory): the value is put together from masked bit patterns.
 template <int R>
 __device__ __forceinline__ float pick(const float (&acc)[R], int lane) {
-  float v = acc[0];
+  uint32_t bits = 0;
 #pragma unroll
-  for (int r = 1; r < R; ++r) v = lane == r ? acc[r] : v;
-  return v;
+  for (int r = 0; r < R; ++r) bits |= __float_as_uint(acc[r]) & (uint32_t)-(int)(lane == r);
+  return __uint_as_float(bits);
 }
 
 // diagnostics build: workgroup 0 stamps the 100 MHz wall clock at marked points of the
