@@ -317,7 +317,7 @@ __global__ void k_pf_copy_row(const float *__restrict__ src, float *dst, int d) 
 // (second) MFMA of a 32-key block, and V^T is read from LDS with the same assignment.
 // The scores carry log2(e)/sqrt(hd) (folded into q16): base-2 online softmax.
 template <int HD>
-__global__ __launch_bounds__(256) void k_pf_attn(const _Float16 *__restrict__ q16, const void *kcache,
+__global__ __launch_bounds__(256, 2) void k_pf_attn(const _Float16 *__restrict__ q16, const void *kcache,
                                                  const void *vcache, int kv_f16, int nq, int nkv, int l, int max_seq,
                                                  int pos0, int m, _Float16 *o16) {
   constexpr int LDH = HD + 8;                 // K tile row stride (halfs)
