@@ -1127,7 +1127,8 @@ extern "C" int river_decode_step(river_ctx *x, const int32_t *in_token, const in
 static int launch_bd_gemm_b(river_ctx *x, const bd::BdB &Bd, const bd::BdB &Bq, int N, const _Float16 *Af, int K,
                             void *C, int ldc, int epi, int by_flag, int n, bd::BdNorm nrm = bd::BdNorm{},
                             int *grid_out = nullptr) {
-  // A matrix with at most 16 rows per CU (output and down projection) would have every workgroup
+  // A matrix with at most 16 rows per CU (the down projection; the output projection, which also
+  // prepares the next norm, stays whole) would have every workgroup
   // read the whole activation tile for a single row block; it is dealt out as K slices of four
   // times the rows instead, and the kernel that consumes the sum adds the partial sums up.
   int k_split = 1;
