@@ -674,7 +674,9 @@ template <int DT, int R, int U> struct Dense {
       const int off = (step * U + u) * 1024 + lane * 16;
 #pragma unroll
       for (int r = 0; r < R; ++r)
-        g.w[base + r * U + u] = off < row_bytes ? ld_stream16(rw.p[r] + off) : u32x4{0u, 0u, 0u, 0u};
+        // lanes beyond the row load its last 16 bytes (fma does not use them): no load sits behind a
+        // branch on the lane's column
+        g.w[base + r * U + u] = ld_stream16(rw.p[r] + min(off, row_bytes - 16));
     }
   }
   static __device__ __forceinline__ void fma(const Regs<DT> &g, int base, int cols, int group, int step,
@@ -717,17 +719,13 @@ template <int DT, int R, int U, int CPL> struct W4 {
                                                int step, int lane) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int c = ((step * U + u) * 64 + lane) * CPL;
+      // (lanes beyond the row load its last codes, which fma does not use: no load behind a branch)
+      const int c = min(((step * U + u) * 64 + lane) * CPL, cols - CPL);
       const int gi = c / group;
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        if (c < cols) {
-          g.w[base + r * U + u] = CPL == 32 ? ld_stream16(rw.p[r] + (c >> 1)) : ld_stream8(rw.p[r] + (c >> 1));
-          g.sz[base + r * U + u] = Store<DT>::ldsz(rw.sz[r], gi);
-        } else {
-          g.w[base + r * U + u] = u32x4{0u, 0u, 0u, 0u};
-          g.sz[base + r * U + u] = Store<DT>::pack(0.f, 0.f);
-        }
+        g.w[base + r * U + u] = CPL == 32 ? ld_stream16(rw.p[r] + (c >> 1)) : ld_stream8(rw.p[r] + (c >> 1));
+        g.sz[base + r * U + u] = Store<DT>::ldsz(rw.sz[r], gi);
       }
     }
   }
