@@ -1154,10 +1154,12 @@ __global__ __launch_bounds__(256) void k_bd_attn(const float *__restrict__ qkv, 
       }
     }
   };
+  // (the loads of the loop are issued whether or not their rows exist -- beyond the last row they
+  // fetch it again -- so that none sits behind a branch and a batch's wait leaves the next one alone)
   for (; j0 < pc; j0 += 2 * step) {
-    if (j0 + step < pc) load(j0 + step, bb);
+    load(j0 + step, bb);
     consume(j0, ba);
-    if (j0 + 2 * step < pc) load(j0 + 2 * step, ba);
+    load(j0 + 2 * step, ba);
     if (j0 + step < pc) consume(j0 + step, bb);
   }
   // merge: the four lane groups of a wavefront by lane exchange (lanes 16 and 32 apart hold the
