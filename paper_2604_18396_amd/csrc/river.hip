@@ -1133,7 +1133,9 @@ static int launch_bd_gemm_b(river_ctx *x, const bd::BdB &Bd, const bd::BdB &Bq, 
   // times the rows instead, and the kernel that consumes the sum adds the partial sums up.
   int k_split = 1;
   if (epi == bd::EPI_ADD && N <= 16 * x->grid_persist && K >= 4096 && ldc == x->cfg.d_model) k_split = bd::kBdKSplit;
-  const int per_cu = (N * k_split + x->grid_persist - 1) / x->grid_persist;
+  // (the consumer of a fused norm adds up at most 16 * kSsqLoads partial sums per row)
+  const int cus = epi == bd::EPI_ADD_NORM ? std::min(x->grid_persist, 16 * bd::kSsqLoads) : x->grid_persist;
+  const int per_cu = (N * k_split + cus - 1) / cus;
   const int rows_per_wg = std::max(8, (per_cu + 7) / 8 * 8);
   const int blocks = (rows_per_wg + 15) / 16;
   const dim3 grid((N + rows_per_wg - 1) / rows_per_wg * k_split), blk(512);
